@@ -1,0 +1,183 @@
+"""CPU oracle for the MXFP8 linear-layer path: numpy front end of ``mxfp8_oracle.c``.
+
+TEST INFRASTRUCTURE ONLY. The tests, the smoke check and the benchmark's ``cpu_baseline`` leg call
+this; the HIP library and its Python binding never do, and nothing here touches the GPU.
+
+All arithmetic lives in the C file (the paper's definitions, Section 2, Section 3.3, Algorithm 1,
+Appendix A.1-A.3, written out in double precision). This module only compiles it with gcc, loads
+it with ctypes and moves numpy arrays in and out. BF16 tensors travel as ``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mxfp8_oracle.c")
+_LIB = os.path.join(_HERE, "libmxfp8_oracle.so")
+
+K_BLOCK = 32
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP over rows/columns only). Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    i64 = ctypes.c_int64
+    vp = ctypes.c_void_p
+    lib.mxo_threads.restype = ctypes.c_int
+    lib.mxo_e4m3_decode.restype = ctypes.c_double
+    lib.mxo_e4m3_decode.argtypes = [ctypes.c_uint8]
+    lib.mxo_e4m3_encode.restype = ctypes.c_uint8
+    lib.mxo_e4m3_encode.argtypes = [ctypes.c_double]
+    lib.mxo_scale_byte.restype = ctypes.c_int
+    lib.mxo_scale_byte.argtypes = [ctypes.c_double]
+    lib.mxo_round_to_bf16.restype = ctypes.c_uint16
+    lib.mxo_round_to_bf16.argtypes = [ctypes.c_double]
+    for name in ("mxo_quantize_rowwise_f32", "mxo_quantize_colwise_f32",
+                 "mxo_quantize_rowwise_bf16", "mxo_quantize_colwise_bf16"):
+        fn = getattr(lib, name)
+        fn.restype = None
+        fn.argtypes = [vp, i64, i64, i64, u8p, u8p]
+    lib.mxo_dequantize_f64.restype = None
+    lib.mxo_dequantize_f64.argtypes = [u8p, u8p, i64, i64, vp]
+    lib.mxo_dequantize_f32.restype = None
+    lib.mxo_dequantize_f32.argtypes = [u8p, u8p, i64, i64, vp, i64]
+    lib.mxo_dequantize_bf16.restype = None
+    lib.mxo_dequantize_bf16.argtypes = [u8p, u8p, i64, i64, vp, i64]
+    lib.mxo_gemm_rows_f64.restype = ctypes.c_int
+    lib.mxo_gemm_rows_f64.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, i64, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _u8(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def threads() -> int:
+    """Number of host threads the C loops use (OpenMP default: all cores given to the process)."""
+    return int(_load().mxo_threads())
+
+
+def e4m3_decode(code: int) -> float:
+    return float(_load().mxo_e4m3_decode(int(code) & 0xFF))
+
+
+def e4m3_encode(t: float) -> int:
+    return int(_load().mxo_e4m3_encode(float(t)))
+
+
+def scale_byte(amax: float) -> int:
+    return int(_load().mxo_scale_byte(float(amax)))
+
+
+def round_to_bf16_bits(x: float) -> int:
+    return int(_load().mxo_round_to_bf16(float(x)))
+
+
+def _check_src(src: np.ndarray):
+    if src.ndim != 2:
+        raise ValueError("source must be 2-D")
+    if src.dtype == np.float32:
+        kind = "f32"
+    elif src.dtype == np.uint16:
+        kind = "bf16"
+    else:
+        raise TypeError("source must be float32 or uint16 (BF16 bit patterns)")
+    if src.strides[1] != src.itemsize or src.strides[0] % src.itemsize:
+        raise ValueError("source rows must be contiguous")
+    return kind, src.strides[0] // src.itemsize
+
+
+def quantize_rowwise(src: np.ndarray):
+    """[rows x cols] -> (q [rows x cols] u8, s [rows x cols/32] u8); blocks run along a row."""
+    kind, ld = _check_src(src)
+    rows, cols = src.shape
+    if cols % K_BLOCK:
+        raise ValueError("cols must be a multiple of 32")
+    q = np.empty((rows, cols), np.uint8)
+    s = np.empty((rows, cols // K_BLOCK), np.uint8)
+    getattr(_load(), "mxo_quantize_rowwise_" + kind)(src.ctypes.data, rows, cols, ld, _u8(q), _u8(s))
+    return q, s
+
+
+def quantize_colwise(src: np.ndarray):
+    """[rows x cols] -> (qT [cols x rows] u8, sT [cols x rows/32] u8); blocks run down a column."""
+    kind, ld = _check_src(src)
+    rows, cols = src.shape
+    if rows % K_BLOCK:
+        raise ValueError("rows must be a multiple of 32")
+    qT = np.empty((cols, rows), np.uint8)
+    sT = np.empty((cols, rows // K_BLOCK), np.uint8)
+    getattr(_load(), "mxo_quantize_colwise_" + kind)(src.ctypes.data, rows, cols, ld, _u8(qT), _u8(sT))
+    return qT, sT
+
+
+def _check_qs(q: np.ndarray, s: np.ndarray):
+    q = np.ascontiguousarray(q, np.uint8)
+    s = np.ascontiguousarray(s, np.uint8)
+    if q.ndim != 2 or q.shape[1] % K_BLOCK or s.shape != (q.shape[0], q.shape[1] // K_BLOCK):
+        raise ValueError("q must be [rows x cols], s [rows x cols/32]")
+    return q, s
+
+
+def dequantize(q: np.ndarray, s: np.ndarray, dtype: str = "f64") -> np.ndarray:
+    """Decoded values Q * 2^(S-127); 'f64' exact, 'f32'/'bf16' rounded once (bf16 as uint16)."""
+    q, s = _check_qs(q, s)
+    rows, cols = q.shape
+    lib = _load()
+    if dtype == "f64":
+        out = np.empty((rows, cols), np.float64)
+        lib.mxo_dequantize_f64(_u8(q), _u8(s), rows, cols, out.ctypes.data)
+    elif dtype == "f32":
+        out = np.empty((rows, cols), np.float32)
+        lib.mxo_dequantize_f32(_u8(q), _u8(s), rows, cols, out.ctypes.data, cols)
+    elif dtype == "bf16":
+        out = np.empty((rows, cols), np.uint16)
+        lib.mxo_dequantize_bf16(_u8(q), _u8(s), rows, cols, out.ctypes.data, cols)
+    else:
+        raise ValueError(dtype)
+    return out
+
+
+def gemm_rows(a_q, a_s, b_q, b_s, rows):
+    """Rows ``rows`` of C = A * B^T over decoded operands in double: returns (C, sum|a*b|)."""
+    a_q, a_s = _check_qs(a_q, a_s)
+    b_q, b_s = _check_qs(b_q, b_s)
+    M, K = a_q.shape
+    N, Kb = b_q.shape
+    if K != Kb:
+        raise ValueError("operands disagree on K")
+    idx = np.ascontiguousarray(rows, np.int64)
+    if idx.size and (idx.min() < 0 or idx.max() >= M):
+        raise ValueError("row index out of range")
+    C = np.empty((idx.size, N), np.float64)
+    A = np.empty((idx.size, N), np.float64)
+    rc = _load().mxo_gemm_rows_f64(_u8(a_q), _u8(a_s), _u8(b_q), _u8(b_s), M, N, K,
+                                   idx.ctypes.data, idx.size, C.ctypes.data, A.ctypes.data)
+    if rc != 0:
+        raise MemoryError("oracle GEMM could not allocate its decoded operands")
+    return C, A
+
+
+def gemm(a_q, a_s, b_q, b_s):
+    """All of C = A * B^T (see gemm_rows)."""
+    return gemm_rows(a_q, a_s, b_q, b_s, np.arange(np.asarray(a_q).shape[0]))
