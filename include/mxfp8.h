@@ -1,0 +1,120 @@
+/*
+ * mxfp8.h -- C ABI of the MXFP8 linear-layer path for AMD MI355X (gfx950 / CDNA4).
+ *
+ * The library implements, as hand-written HIP kernels, the three operations a linear layer
+ * needs when it is trained with the MXFP8 recipe:
+ *
+ *   quantize    a FP32/BF16 tensor -> blocks of K = 32 E4M3 elements Q_i sharing one UE8M0
+ *               power-of-two scale X (Section 2; conversion rule of Section 3.3, Algorithm 1 and
+ *               Appendix A.1/A.2: X = amax/448 rounded UP to a power of two, Q_i = RNE(V_i / X),
+ *               saturating), along rows, along columns, or both from one read of the source
+ *               (Section 3.2: every tensor is kept in two copies, one per reduction axis);
+ *   gemm        the block-scaled matrix product with FP32 accumulation for the forward pass,
+ *               the activation-gradient pass and the weight-gradient pass (Section 2,
+ *               Section 3.2 / Figure 2, Appendix A.3), on the scaled MX MFMA instructions;
+ *   dequantize  the decode Q_i * X (Section 2).
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers (HIP global memory of the current device). The
+ *     caller owns every buffer; the library allocates nothing, keeps no state between calls and
+ *     never synchronises: work is enqueued on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and the call returns immediately.
+ *   - All tensors are row-major. "ld" arguments are leading dimensions in ELEMENTS.
+ *   - A block is 32 consecutive elements along the quantization axis, so that axis must be a
+ *     multiple of 32 (the paper defines no partial block); a dimension of 0 is accepted and
+ *     does nothing.
+ *   - Scale bytes hold n + 127 for X = 2^n, n in [-127, 127]; 0xFF marks a NaN block.
+ *     Element bytes are OCP E4M3 (bias 7, max 448, 0x7F/0xFF = NaN, no infinity).
+ *   - Errors are reported by return code only, detected on the host before any launch; when a
+ *     call fails no output byte has been written. MXFP8_ERR_HIP means the launch itself was
+ *     rejected by the runtime (the HIP error stays readable through hipGetLastError()).
+ *   - The library targets gfx950 only and fails with MXFP8_ERR_HIP on any other device.
+ */
+#ifndef MXFP8_H
+#define MXFP8_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MXFP8_OK = 0,
+    MXFP8_ERR_NULL = 1,  /* a required pointer is NULL */
+    MXFP8_ERR_SHAPE = 2, /* negative dimension, axis not a multiple of 32, ld too small */
+    MXFP8_ERR_ALIGN = 3, /* pointer or leading dimension not aligned as documented */
+    MXFP8_ERR_DTYPE = 4, /* unknown mxfp8_dtype */
+    MXFP8_ERR_MODE = 5,  /* unknown mxfp8_axis / mxfp8_pass */
+    MXFP8_ERR_HIP = 6    /* kernel launch rejected by the HIP runtime, or not a gfx950 device */
+} mxfp8_status;
+
+typedef enum { MXFP8_F32 = 0, MXFP8_BF16 = 1 } mxfp8_dtype;
+typedef enum { MXFP8_ROWWISE = 1, MXFP8_COLWISE = 2, MXFP8_BOTH = 3 } mxfp8_axis;
+typedef enum { MXFP8_FPROP = 0, MXFP8_DGRAD = 1, MXFP8_WGRAD = 2 } mxfp8_pass;
+
+/*
+ * Convert src [rows x cols] (FP32 or BF16, leading dimension ld_src >= cols) to MXFP8-E4M3.
+ * Section 3.3 / Algorithm 1 / Appendix A.1 (scale), Appendix A.2 (elements), Section 3.2 (axes).
+ *
+ *   MXFP8_ROWWISE  blocks are 32 consecutive columns of a row:
+ *                    q_row [rows x cols] bytes, s_row [rows x cols/32] bytes.
+ *   MXFP8_COLWISE  blocks are 32 consecutive rows of a column; the copy is stored TRANSPOSED so
+ *                  that each block is again contiguous:
+ *                    q_colT [cols x rows] bytes, s_colT [cols x rows/32] bytes.
+ *   MXFP8_BOTH     both copies, each computed from the source itself, in one pass over src.
+ *
+ * Requirements: rows % 32 == 0 and cols % 32 == 0; src 16-byte aligned and ld_src a multiple
+ * of 16 bytes; q_row and q_colT 16-byte aligned. Outputs not selected by `axis` are ignored and
+ * may be NULL. Outputs are dense (leading dimension = their column count) and must not overlap src.
+ *
+ * Special values (the paper asks for "special care" without fixing it): a block containing a NaN
+ * gets scale 0xFF and all elements 0x7F; a block containing +-Inf and no NaN gets scale 254
+ * (Algorithm 1's clamp), its infinities saturate to +-448 and its finite values are divided by
+ * 2^127; the sign of every input, zero included, is kept.
+ */
+mxfp8_status mxfp8_quantize(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                            int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
+                            uint8_t *q_colT, uint8_t *s_colT, void *hip_stream);
+
+/*
+ * C [M x N] = A [M x K] * B [N x K]^T with per-block scales (Section 2, Appendix A.3):
+ *   C[m, n] = sum over blocks b of 2^(a_s[m,b] + b_s[n,b] - 254) * sum_{i<32} A[m,32b+i] * B[n,32b+i]
+ * accumulated in FP32 by the scaled MFMA instructions. Both operands are K-contiguous MXFP8:
+ * a_q [M x K], a_s [M x K/32], b_q [N x K], b_s [N x K/32] (dense).
+ *
+ * `pass` names which of the three products of a linear layer this is (Section 3.2, Figure 2),
+ * i.e. which quantized copies the caller passes; the arithmetic is the same for all three:
+ *   MXFP8_FPROP  Y  [T x O] : A = X_row  [T x H], B = W_row  [O x H]   (reduction over H)
+ *   MXFP8_DGRAD  dX [T x H] : A = dY_row [T x O], B = W_colT [H x O]   (reduction over O)
+ *   MXFP8_WGRAD  dW [O x H] : A = dY_colT[O x T], B = X_colT [H x T]   (reduction over T)
+ *
+ * c is FP32 or BF16 (rounded to nearest even from the FP32 accumulator), leading dimension
+ * ldc >= N. Requirements: K % 128 == 0 (one scaled MFMA consumes four blocks); a_q, b_q, a_s, b_s
+ * 16-byte aligned; c 16-byte aligned and ldc * sizeof(element) a multiple of 16. M and N are
+ * arbitrary; M, N or K equal to 0 is accepted (K == 0 stores zeros).
+ * A scale byte 0xFF or an element NaN makes every output it touches NaN; products that overflow
+ * FP32 give +-Inf or NaN as the hardware accumulator does.
+ */
+mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
+                        const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
+                        void *c, mxfp8_dtype c_dtype, int64_t ldc, void *hip_stream);
+
+/*
+ * Decode q [rows x cols], s [rows x cols/32] (dense, blocks along a row) to
+ * dst[r, c] = E4M3(q[r, c]) * 2^(s[r, c/32] - 127) (Section 2), FP32 or BF16, leading dimension
+ * ld_dst >= cols. The product is rounded once to the destination type (exact in FP32 unless it
+ * overflows to +-Inf); scale 0xFF or element 0x7F/0xFF gives NaN.
+ * Requirements: cols % 32 == 0; q and dst 16-byte aligned; ld_dst * sizeof(element) a multiple
+ * of 16. A colwise copy is decoded by passing q_colT/s_colT with rows and cols swapped.
+ */
+mxfp8_status mxfp8_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
+                              void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst, void *hip_stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *mxfp8_status_string(mxfp8_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MXFP8_H */

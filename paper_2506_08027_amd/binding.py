@@ -1,0 +1,165 @@
+"""Thin ctypes binding of ``libmxfp8.so``: same names as the C ABI, argument marshalling only.
+
+PyTorch supplies device memory and the current HIP stream; every step of the path (amax, scale,
+element conversion, transposed column copy, block-scaled GEMM, decode) runs in the HIP kernels
+behind the C entry points. There is no fallback: if the library is missing or an entry point
+reports an error, a Python exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmxfp8.so")
+
+OK = 0
+F32, BF16 = 0, 1
+ROWWISE, COLWISE, BOTH = 1, 2, 3
+FPROP, DGRAD, WGRAD = 0, 1, 2
+K_BLOCK = 32
+
+_AXIS = {"rowwise": ROWWISE, "colwise": COLWISE, "both": BOTH, ROWWISE: ROWWISE, COLWISE: COLWISE, BOTH: BOTH}
+_PASS = {"fprop": FPROP, "dgrad": DGRAD, "wgrad": WGRAD, FPROP: FPROP, DGRAD: DGRAD, WGRAD: WGRAD}
+
+_lib = None
+
+
+class MXFP8Error(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what} failed with status {code}: {status_string(code)}")
+        self.code = code
+
+
+def load() -> ctypes.CDLL:
+    """Load the in-tree HIP library; fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2506_08027_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.mxfp8_quantize.restype = ci
+    lib.mxfp8_quantize.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, vp, vp]
+    lib.mxfp8_gemm.restype = ci
+    lib.mxfp8_gemm.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, vp]
+    lib.mxfp8_dequantize.restype = ci
+    lib.mxfp8_dequantize.argtypes = [vp, vp, i64, i64, vp, ci, i64, vp]
+    lib.mxfp8_status_string.restype = ctypes.c_char_p
+    lib.mxfp8_status_string.argtypes = [ci]
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load().mxfp8_status_string(int(code)).decode()
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise TypeError(f"only float32 and bfloat16 are supported, got {t}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _need_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("all tensors must live in GPU memory")
+
+
+# ---- raw entry points: same names and argument order as include/mxfp8.h -----------------------
+
+def mxfp8_quantize(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=None, stream=None) -> None:
+    """src [rows x cols] float32/bfloat16 (row stride = leading dimension) -> the selected copies."""
+    _need_cuda(src, q_row, s_row, q_colT, s_colT)
+    if src.dim() != 2 or (src.numel() and src.stride(1) != 1):
+        raise ValueError("src must be 2-D with contiguous rows")
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else max(cols, 1)
+    rc = load().mxfp8_quantize(_ptr(src), _dtype_code(src.dtype), rows, cols, ld, _AXIS[axis],
+                               _ptr(q_row), _ptr(s_row), _ptr(q_colT), _ptr(s_colT), _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_quantize")
+
+
+def mxfp8_gemm(pass_, a_q, a_s, b_q, b_s, c, stream=None) -> None:
+    """c [M x N] (float32/bfloat16) = A [M x K] . B [N x K]^T with block scales [. x K/32]."""
+    _need_cuda(a_q, a_s, b_q, b_s, c)
+    M, K = a_q.shape
+    N, Kb = b_q.shape
+    if K != Kb or tuple(a_s.shape) != (M, K // K_BLOCK) or tuple(b_s.shape) != (N, K // K_BLOCK):
+        raise ValueError("operand shapes disagree")
+    if tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
+        raise ValueError("c must be [M x N] with contiguous rows")
+    for t in (a_q, a_s, b_q, b_s):
+        if not t.is_contiguous() or t.dtype != torch.uint8:
+            raise ValueError("quantized operands must be dense uint8")
+    ldc = c.stride(0) if M > 1 else max(N, 1)
+    rc = load().mxfp8_gemm(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c),
+                           _dtype_code(c.dtype), ldc, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_gemm")
+
+
+def mxfp8_dequantize(q, s, dst, stream=None) -> None:
+    """dst [rows x cols] (float32/bfloat16) = E4M3(q) * 2^(s - 127), blocks along a row."""
+    _need_cuda(q, s, dst)
+    rows, cols = q.shape
+    if tuple(s.shape) != (rows, cols // K_BLOCK) or tuple(dst.shape) != (rows, cols):
+        raise ValueError("shapes disagree")
+    if not q.is_contiguous() or not s.is_contiguous() or q.dtype != torch.uint8 or s.dtype != torch.uint8:
+        raise ValueError("q and s must be dense uint8")
+    if dst.numel() and dst.stride(1) != 1:
+        raise ValueError("dst rows must be contiguous")
+    ld = dst.stride(0) if rows > 1 else max(cols, 1)
+    rc = load().mxfp8_dequantize(_ptr(q), _ptr(s), rows, cols, _ptr(dst), _dtype_code(dst.dtype), ld,
+                                 _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_dequantize")
+
+
+# ---- conveniences that only allocate the outputs ----------------------------------------------
+
+def quantize(src, axis="both"):
+    """Allocate outputs and call mxfp8_quantize. Returns a dict with the selected copies:
+    'q_row' [R x C], 's_row' [R x C/32], 'q_colT' [C x R], 's_colT' [C x R/32] (uint8)."""
+    rows, cols = src.shape
+    ax = _AXIS[axis]
+    out = {}
+    u8 = dict(dtype=torch.uint8, device=src.device)
+    if ax & ROWWISE:
+        out["q_row"] = torch.empty((rows, cols), **u8)
+        out["s_row"] = torch.empty((rows, cols // K_BLOCK), **u8)
+    if ax & COLWISE:
+        out["q_colT"] = torch.empty((cols, rows), **u8)
+        out["s_colT"] = torch.empty((cols, rows // K_BLOCK), **u8)
+    mxfp8_quantize(src, ax, out.get("q_row"), out.get("s_row"), out.get("q_colT"), out.get("s_colT"))
+    return out
+
+
+def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32):
+    c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
+    mxfp8_gemm(pass_, a_q, a_s, b_q, b_s, c)
+    return c
+
+
+def dequantize(q, s, out_dtype=torch.float32):
+    dst = torch.empty(tuple(q.shape), dtype=out_dtype, device=q.device)
+    mxfp8_dequantize(q, s, dst)
+    return dst

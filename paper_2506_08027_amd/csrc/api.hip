@@ -1,0 +1,104 @@
+// C ABI of the MXFP8 library: argument validation on the host, then one kernel launch on the
+// caller's stream. Nothing is allocated, nothing is synchronised, no state is kept.
+#include "../../include/mxfp8.h"
+
+#include <hip/hip_runtime.h>
+
+namespace mxfp8 {
+hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
+                           uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                           hipStream_t stream);
+hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
+                             bool bf16, int64_t ld, hipStream_t stream);
+hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
+                       int64_t N, int64_t K, void *c, bool c_bf16, int64_t ldc, hipStream_t stream);
+}  // namespace mxfp8
+
+namespace {
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool valid_dtype(int d) { return d == MXFP8_F32 || d == MXFP8_BF16; }
+inline int64_t esize(int d) { return d == MXFP8_BF16 ? 2 : 4; }
+constexpr int64_t kMaxDim = 0x7FFFFFFF;  // kernels index rows and columns with 32-bit tile math
+}  // namespace
+
+extern "C" {
+
+mxfp8_status mxfp8_quantize(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                            int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
+                            uint8_t *q_colT, uint8_t *s_colT, void *hip_stream)
+{
+    if (!valid_dtype(src_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (axis != MXFP8_ROWWISE && axis != MXFP8_COLWISE && axis != MXFP8_BOTH)
+        return MXFP8_ERR_MODE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || rows % 32 || cols % 32 || ld_src < cols)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    const bool want_row = axis & MXFP8_ROWWISE, want_col = axis & MXFP8_COLWISE;
+    if (!src || (want_row && (!q_row || !s_row)) || (want_col && (!q_colT || !s_colT)))
+        return MXFP8_ERR_NULL;
+    if (!aligned16(src) || (ld_src * esize(src_dtype)) % 16 || (want_row && !aligned16(q_row)) ||
+        (want_col && !aligned16(q_colT)))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_quantize(src, src_dtype == MXFP8_BF16, rows, cols, ld_src, (int)axis,
+                                                q_row, s_row, q_colT, s_colT,
+                                                static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
+                        const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c, mxfp8_dtype c_dtype,
+                        int64_t ldc, void *hip_stream)
+{
+    if (!valid_dtype(c_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD)
+        return MXFP8_ERR_MODE;
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 128 || ldc < N)
+        return MXFP8_ERR_SHAPE;
+    if (M == 0 || N == 0)
+        return MXFP8_OK;
+    if (!c || (K > 0 && (!a_q || !a_s || !b_q || !b_s)))
+        return MXFP8_ERR_NULL;
+    if (!aligned16(c) || (ldc * esize(c_dtype)) % 16 ||
+        (K > 0 && (!aligned16(a_q) || !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16, ldc,
+                                            static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
+                              mxfp8_dtype dst_dtype, int64_t ld_dst, void *hip_stream)
+{
+    if (!valid_dtype(dst_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || cols % 32 || ld_dst < cols)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    if (!q || !s || !dst)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(q) || !aligned16(dst) || (ld_dst * esize(dst_dtype)) % 16)
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_dequantize(q, s, rows, cols, dst, dst_dtype == MXFP8_BF16, ld_dst,
+                                                  static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+const char *mxfp8_status_string(mxfp8_status status)
+{
+    switch (status) {
+    case MXFP8_OK: return "ok";
+    case MXFP8_ERR_NULL: return "required pointer is NULL";
+    case MXFP8_ERR_SHAPE: return "bad shape: negative, not a multiple of the block size, or leading dimension too small";
+    case MXFP8_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
+    case MXFP8_ERR_DTYPE: return "unknown element type";
+    case MXFP8_ERR_MODE: return "unknown axis or pass";
+    case MXFP8_ERR_HIP: return "HIP launch failed (is this a gfx950 device?)";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Device-side helpers shared by the MXFP8 kernels (gfx950 only).
+//
+// Number formats (Section 2, Table 1): elements are OCP E4M3 (1-4-3, bias 7, max 448, NaN =
+// S.1111.111); a scale byte s stands for X = 2^(s-127), 0xFF for NaN; blocks have 32 elements.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mxfp8 {
+
+typedef short v2s __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef unsigned short v2us __attribute__((ext_vector_type(2)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kBlock = 32;
+
+// ---- cross-lane moves inside a row of 16 lanes (DPP, no LDS traffic) -------------------------
+// quad_perm [1,0,3,2] / [2,3,0,1]: exchange with lane^1 / lane^2; row_half_mirror: lane i <-> 7-i
+// inside each group of 8 (after the two quad steps every lane of a quad holds the quad result, so
+// the mirror delivers the other quad of the same 8 lanes).
+__device__ __forceinline__ uint32_t dpp_xor1(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);
+}
+__device__ __forceinline__ uint32_t dpp_xor2(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
+}
+__device__ __forceinline__ uint32_t dpp_half_mirror(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);
+}
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// max of the two 16-bit halves, both halves at once (v_pk_max_u16)
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    v2us x = __builtin_bit_cast(v2us, a), y = __builtin_bit_cast(v2us, b);
+    v2us r = __builtin_elementwise_max(x, y);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// ---- scale byte from the block amax, in the bit space (Algorithm 1 / Appendix A.1) ----------
+// For amax = 1.m * 2^(e-127) the smallest n with amax <= 448 * 2^n is e-127-8, plus one when
+// 1.m > 1.75; adding (2.0 - 1.75) - 1ulp to the mantissa carries into the exponent field exactly
+// in that case. The lower clamp (byte 0 = 2^-127) covers zero and every FP32 subnormal.
+// abs_bits = |amax| as FP32 bits. Inf -> 254 (the clamp of Algorithm 1), NaN -> 0xFF.
+__device__ __forceinline__ uint32_t scale_byte_from_f32_bits(uint32_t abs_bits)
+{
+    int s = (int)((abs_bits + 0x1FFFFFu) >> 23) - 8;
+    s = s < 0 ? 0 : s;
+    if (abs_bits >= 0x7F800000u)
+        s = abs_bits > 0x7F800000u ? 0xFF : 254;
+    return (uint32_t)s;
+}
+// Same rule on BF16 bits (the upper half of the FP32 pattern; the lower mantissa bits are zero).
+__device__ __forceinline__ uint32_t scale_byte_from_bf16_bits(uint32_t abs_bits16)
+{
+    int s = (int)((abs_bits16 + 0x1Fu) >> 7) - 8;
+    s = s < 0 ? 0 : s;
+    if (abs_bits16 >= 0x7F80u)
+        s = abs_bits16 > 0x7F80u ? 0xFF : 254;
+    return (uint32_t)s;
+}
+
+// The conversion instructions divide by 2^(exponent field of the scale operand - 127) and read an
+// exponent field of 0 as 2^-127, so the scale byte shifted into the exponent field is the operand.
+__device__ __forceinline__ float scale_operand(uint32_t scale_byte)
+{
+    return __uint_as_float(scale_byte << 23);
+}
+
+// ---- element conversion (Appendix A.2): RNE to E4M3 of V / X --------------------------------
+// v_cvt_scalef32_pk_fp8_{f32,bf16} round to nearest even, keep the sign of zero and of
+// underflows and produce subnormals, but answer NaN for |V/X| > 464 instead of saturating.
+// With the round-up scale no finite block reaches that; only +-Inf inputs do, and those are
+// patched to +-448 by the callers (fix_inf_*).
+__device__ __forceinline__ uint32_t cvt2_f32(uint32_t old, float a, float b, float scale, bool hi)
+{
+    v2s o = __builtin_bit_cast(v2s, old);
+    v2s r = hi ? __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(o, a, b, scale, true)
+               : __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(o, a, b, scale, false);
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ uint32_t cvt2_bf16(uint32_t old, uint32_t pair, float scale, bool hi)
+{
+    v2s o = __builtin_bit_cast(v2s, old);
+    v2bf p = __builtin_bit_cast(v2bf, pair);
+    v2s r = hi ? __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(o, p, scale, true)
+               : __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(o, p, scale, false);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// Saturating rule for infinities: the element byte becomes sign | 0x7E (+-448).
+__device__ __forceinline__ uint32_t inf_byte_f32(uint32_t bits, uint32_t q)
+{
+    return (bits & 0x7FFFFFFFu) == 0x7F800000u ? ((bits >> 24) & 0x80u) | 0x7Eu : q;
+}
+__device__ __forceinline__ uint32_t inf_byte_bf16(uint32_t bits16, uint32_t q)
+{
+    return (bits16 & 0x7FFFu) == 0x7F80u ? ((bits16 >> 8) & 0x80u) | 0x7Eu : q;
+}
+
+}  // namespace mxfp8
