@@ -28,7 +28,8 @@
  *   - Errors are reported by return code only, detected on the host before any launch; when a
  *     call fails no output byte has been written. MXFP8_ERR_HIP means the launch itself was
  *     rejected by the runtime (the HIP error stays readable through hipGetLastError()).
- *   - The library targets gfx950 only and fails with MXFP8_ERR_HIP on any other device.
+ *   - The code objects are built for gfx950 only: on any other device the launch is rejected and
+ *     the call returns MXFP8_ERR_HIP.
  */
 #ifndef MXFP8_H
 #define MXFP8_H
@@ -91,8 +92,10 @@ mxfp8_status mxfp8_quantize(const void *src, mxfp8_dtype src_dtype, int64_t rows
  *
  * c is FP32 or BF16 (rounded to nearest even from the FP32 accumulator), leading dimension
  * ldc >= N. Requirements: K % 128 == 0 (one scaled MFMA consumes four blocks); a_q, b_q, a_s, b_s
- * 16-byte aligned; c 16-byte aligned and ldc * sizeof(element) a multiple of 16. M and N are
- * arbitrary; M, N or K equal to 0 is accepted (K == 0 stores zeros).
+ * 16-byte aligned; c aligned to its element size. When c is 16-byte aligned and
+ * ldc * sizeof(element) is a multiple of 16 the result is written with 128-bit stores, otherwise
+ * element by element (slower, same values). M and N are arbitrary; M, N or K equal to 0 is
+ * accepted (K == 0 stores zeros).
  * A scale byte 0xFF or an element NaN makes every output it touches NaN; products that overflow
  * FP32 give +-Inf or NaN as the hardware accumulator does.
  */

@@ -61,7 +61,7 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
         return MXFP8_OK;
     if (!c || (K > 0 && (!a_q || !a_s || !b_q || !b_s)))
         return MXFP8_ERR_NULL;
-    if (!aligned16(c) || (ldc * esize(c_dtype)) % 16 ||
+    if (reinterpret_cast<uintptr_t>(c) % esize(c_dtype) ||
         (K > 0 && (!aligned16(a_q) || !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))))
         return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16, ldc,

@@ -64,7 +64,7 @@ template <class Cfg, bool OUT_BF16>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
-    int tiles_m, int tiles_n)
+    int tiles_m, int tiles_n, bool vec_store)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN;
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         for (int j = 0; j < TN; ++j) {
             const int n = n0 + wn * Cfg::WN + j * 16 + 4 * g;
             const v4f v = acc[i][j];
-            if (n + 3 < N) {
+            if (vec_store && n + 3 < N) {
                 if constexpr (OUT_BF16) {
                     v2bf p0 = {(__bf16)v[0], (__bf16)v[1]}, p1 = {(__bf16)v[2], (__bf16)v[3]};
                     *reinterpret_cast<uint2 *>(crow + (int64_t)n * 2) =
@@ -222,13 +222,15 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
 {
     const int tiles_m = (M + Cfg::BM - 1) / Cfg::BM, tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
     auto kern = gemm_kernel<Cfg, OUT_BF16>;
+    const int64_t ldc_bytes = ldc * (OUT_BF16 ? 2 : 4);
+    // 128-bit (FP32) / 64-bit (BF16) stores need every row start aligned; otherwise element stores
+    const bool vec_store = (reinterpret_cast<uintptr_t>(c) % 16 == 0) && (ldc_bytes % 16 == 0);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess)
         return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream,
-                       a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc * (OUT_BF16 ? 2 : 4), tiles_m,
-                       tiles_n);
+                       a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, vec_store);
     return hipGetLastError();
 }
 
