@@ -14,30 +14,39 @@
 // four consecutive n of one m: the epilogue is one 128-bit store per 16x16 tile and lane.
 //
 // Tiling. A workgroup of WAVES_M x WAVES_N wavefronts computes a BM x BN tile of C, K in steps of
-// 128 bytes. A and B tiles (and one dword of four scale bytes per row) are staged through LDS,
-// double-buffered: the global loads of step k+1 are issued before the MFMAs of step k and
-// written to the other buffer afterwards, one barrier per step. LDS rows are 128 bytes; the
-// 16-byte chunk index is XORed with (row/2)%8 so that the 16 lanes of a fragment read hit 16
-// different bank groups.
+// 128 bytes (= one MFMA, four scale blocks). A and B tiles go from global memory straight into
+// LDS (global_load_lds_dwordx4: no staging registers), two LDS stages: the loads of step k+1 are
+// issued before the MFMAs of step k, one barrier per step. LDS rows are 128 bytes; the 16-byte
+// chunk index is XORed with (row/2)%8 so that the 16 lanes of a fragment read hit 16 different
+// bank groups. A direct-to-LDS load writes lane l of a wavefront to LDS offset 16*l, so the
+// swizzle is applied on the global side: each lane fetches the chunk that belongs at its slot.
+// Scale bytes are read from global memory (they are tiny and L2-resident), one byte per lane and
+// MFMA tile, one step ahead.
 #include "mxfp8_device.h"
 
 namespace mxfp8 {
 
 constexpr int BK = 128;  // K bytes per step = 4 scale blocks = one MFMA
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
-
 template <int BM_, int BN_, int WAVES_M_, int WAVES_N_> struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static constexpr int THREADS = 64 * WAVES;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile
     static constexpr int TM = WM / 16, TN = WN / 16;            // MFMA tiles per wavefront
     static constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + 4 * (BM + BN);
-    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-    static constexpr int A_LOADS = A_BYTES / 16 / THREADS, B_LOADS = B_BYTES / 16 / THREADS;
-    static_assert(A_BYTES % (16 * THREADS) == 0 && B_BYTES % (16 * THREADS) == 0, "tile/threads");
-    static_assert(BM <= THREADS * 4 && BN <= THREADS * 4, "scale loads");
+    // LDS map: A[2] | B[2] | A scales[2] (one dword = 4 scale bytes per row) | B scales[2]
+    static constexpr int A_OFF = 0, B_OFF = 2 * A_BYTES, SA_OFF = B_OFF + 2 * B_BYTES, SB_OFF = SA_OFF + 2 * BM * 4;
+    static constexpr int LDS_BYTES = SB_OFF + 2 * BN * 4;
+    // one direct-to-LDS instruction moves 8 rows x 128 bytes (or 64 scale dwords) per wavefront
+    static constexpr int A_LOADS = BM / 8 / WAVES, B_LOADS = BN / 8 / WAVES;
+    static constexpr int SA_LOADS = (BM / 64 + WAVES - 1) / WAVES, SB_LOADS = (BN / 64 + WAVES - 1) / WAVES;
+    static constexpr int NA = A_LOADS + SA_LOADS, NB = B_LOADS + SB_LOADS;  // DMA slots per step
+    static_assert(BM % (8 * WAVES) == 0 && BN % (8 * WAVES) == 0, "tile rows per wavefront");
+    static_assert(BM % 64 == 0 && BN % 64 == 0, "scale rows per instruction");
+    static_assert(NB <= 2 * TM, "the B loads of the next step are issued with the MFMAs of the first column");
+    static_assert(NA <= (TN - 1) * TM, "the A loads are issued one per MFMA after the first column");
+    static_assert(A_LOADS < 16, "wait-count immediate");
 };
 
 // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2. Renumber them so
@@ -60,76 +69,126 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
     tn = panel * PANEL + in_panel % width;
 }
 
+// Global memory -> LDS without passing through registers: lane l of the wavefront fetches BYTES
+// bytes from base + voff (its own address) and the hardware writes them to LDS address
+// lds_addr + l*BYTES (lds_addr is wavefront-uniform and travels in M0).
+// Emitted as inline assembly on purpose: the compiler's wait-count pass treats a pending LDS-DMA
+// load as "may complete out of order with LDS reads" and then turns every wait on an LDS read
+// into a wait for ALL outstanding LDS reads, which would serialise the fragment prefetch.
+// Completion is tracked by hand with s_waitcnt vmcnt(n) in front of the barriers.
+template <int BYTES>
+__device__ __forceinline__ void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+{
+    const uint32_t m0v = lds_addr;  // callers pass a wavefront-uniform (scalar) address
+    if constexpr (BYTES == 16)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
+                     : "memory");
+}
+
+// Nothing may be scheduled across this point: the instruction order below is the schedule.
+#define MXFP8_PIN() __builtin_amdgcn_sched_barrier(0)
+// s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding, n < 16)
+#define MXFP8_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+
+// Software pipeline. LDS holds two A buffers and two B buffers. In K step kt (buffers kt & 1):
+//   column 0   : the A fragments of the step are read into registers (they stay there for the
+//                whole step) while the first column of MFMAs already runs one fragment behind;
+//                the B tile of step kt+1 is requested into the other B buffer, one DMA
+//                instruction per MFMA;
+//   barrier    : every wavefront has its A fragments, so the A buffer of this step is dead;
+//   columns 1..: B fragments stream through two register sets; the A tile of step kt+2 is
+//                requested into the dead A buffer, again one DMA instruction per MFMA;
+//   end        : wait until at most the A(kt+2) requests are outstanding, i.e. B(kt+1) (and the
+//                older A(kt+1)) have landed; barrier.
+// So B is fetched one step ahead and A two steps ahead: about 96 KB of a 256x256 tile pair are
+// in flight while 64 KB are being consumed, which is what hides the L2/HBM latency with a single
+// wavefront per SIMD.
 template <class Cfg, bool OUT_BF16>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
     int tiles_m, int tiles_n, bool vec_store)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, TM = Cfg::TM, TN = Cfg::TN;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform: lives in an SGPR
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
     const int r16 = lane & 15, g = lane >> 4;
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     const int nkb = K / kBlock;  // scale bytes per row
     const int KT = K / BK;
 
-    // ---- global -> register staging (coalesced: 8 lanes cover one 128-byte row segment) ------
-    const int ld_chunk = tid & 7;
-    const int ld_row = tid >> 3;
-    constexpr int ROWS_PER_PASS = Cfg::THREADS / 8;
-    uint4 ra[Cfg::A_LOADS], rb[Cfg::B_LOADS];
-    uint32_t rsa = 0, rsb = 0;
-    const uint8_t *a_src[Cfg::A_LOADS];
-    const uint8_t *b_src[Cfg::B_LOADS];
+    // ---- global -> LDS addressing: wavefront w owns 8-row groups w*LOADS.. of each tile; one
+    // instruction fills 8 consecutive rows, lane l lands at row l/8, physical chunk l%8, and
+    // fetches the logical chunk that the XOR swizzle stores there. Offsets are relative to the
+    // tile origin (32-bit: a tile spans at most 256 rows of K bytes).
+    const int ld_r = lane >> 3, ld_c = lane & 7;
+    uint32_t a_goff[Cfg::A_LOADS], b_goff[Cfg::B_LOADS], as_goff[Cfg::SA_LOADS], bs_goff[Cfg::SB_LOADS];
 #pragma unroll
     for (int i = 0; i < Cfg::A_LOADS; ++i) {
-        const int row = min(m0 + ld_row + i * ROWS_PER_PASS, M - 1);  // clamp: ragged tiles re-read a valid row
-        a_src[i] = a_q + (int64_t)row * K + ld_chunk * 16;
+        const int row = (wave * Cfg::A_LOADS + i) * 8 + ld_r;
+        const int chunk = ld_c ^ ((row >> 1) & 7);
+        a_goff[i] = (uint32_t)min(row, M - 1 - m0) * (uint32_t)K + chunk * 16;  // ragged tiles re-read a valid row
     }
 #pragma unroll
     for (int i = 0; i < Cfg::B_LOADS; ++i) {
-        const int row = min(n0 + ld_row + i * ROWS_PER_PASS, N - 1);
-        b_src[i] = b_q + (int64_t)row * K + ld_chunk * 16;
+        const int row = (wave * Cfg::B_LOADS + i) * 8 + ld_r;
+        const int chunk = ld_c ^ ((row >> 1) & 7);
+        b_goff[i] = (uint32_t)min(row, N - 1 - n0) * (uint32_t)K + chunk * 16;
     }
-    const uint8_t *sa_src = a_s + (int64_t)min(m0 + tid, M - 1) * nkb;
-    const uint8_t *sb_src = b_s + (int64_t)min(n0 + tid, N - 1) * nkb;
+#pragma unroll
+    for (int i = 0; i < Cfg::SA_LOADS; ++i)
+        as_goff[i] = (uint32_t)min((wave + i * Cfg::WAVES) * 64 + lane, M - 1 - m0) * (uint32_t)nkb;
+#pragma unroll
+    for (int i = 0; i < Cfg::SB_LOADS; ++i)
+        bs_goff[i] = (uint32_t)min((wave + i * Cfg::WAVES) * 64 + lane, N - 1 - n0) * (uint32_t)nkb;
+    const uint8_t *a_tile = a_q + (int64_t)m0 * K, *b_tile = b_q + (int64_t)n0 * K;
+    const uint8_t *as_tile = a_s + (int64_t)m0 * nkb, *bs_tile = b_s + (int64_t)n0 * nkb;
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
 
-    auto load_global = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < Cfg::A_LOADS; ++i)
-            ra[i] = *reinterpret_cast<const uint4 *>(a_src[i] + (int64_t)kt * BK);
-#pragma unroll
-        for (int i = 0; i < Cfg::B_LOADS; ++i)
-            rb[i] = *reinterpret_cast<const uint4 *>(b_src[i] + (int64_t)kt * BK);
-        if (tid < BM)
-            rsa = *reinterpret_cast<const uint32_t *>(sa_src + kt * 4);
-        if (tid < BN)
-            rsb = *reinterpret_cast<const uint32_t *>(sb_src + kt * 4);
+    // DMA slot t (compile-time after unrolling) of the A / B loads of K step kt into buffer buf
+    auto issue_a = [&](int t, int kt, int buf) __attribute__((always_inline)) {
+        if (t < Cfg::A_LOADS) {
+            dma_load<16>(a_tile + (int64_t)kt * BK, a_goff[t],
+                         lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
+        } else if (t < Cfg::NA) {
+            const int i = t - Cfg::A_LOADS;
+            if (Cfg::BM / 64 >= Cfg::WAVES * (i + 1) || wave + i * Cfg::WAVES < Cfg::BM / 64)
+                dma_load<4>(as_tile + kt * 4, as_goff[i],
+                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + (wave + i * Cfg::WAVES) * 256);
+        }
     };
-    auto store_lds = [&](int buf) {
-        uint8_t *base = lds + buf * Cfg::STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < Cfg::A_LOADS; ++i) {
-            const int row = ld_row + i * ROWS_PER_PASS;
-            *reinterpret_cast<uint4 *>(base + row * BK + swz(row, ld_chunk) * 16) = ra[i];
+    auto issue_b = [&](int t, int kt, int buf) __attribute__((always_inline)) {
+        if (t < Cfg::B_LOADS) {
+            dma_load<16>(b_tile + (int64_t)kt * BK, b_goff[t],
+                         lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
+        } else if (t < Cfg::NB) {
+            const int i = t - Cfg::B_LOADS;
+            if (Cfg::BN / 64 >= Cfg::WAVES * (i + 1) || wave + i * Cfg::WAVES < Cfg::BN / 64)
+                dma_load<4>(bs_tile + kt * 4, bs_goff[i],
+                            lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + (wave + i * Cfg::WAVES) * 256);
         }
-#pragma unroll
-        for (int i = 0; i < Cfg::B_LOADS; ++i) {
-            const int row = ld_row + i * ROWS_PER_PASS;
-            *reinterpret_cast<uint4 *>(base + Cfg::A_BYTES + row * BK + swz(row, ld_chunk) * 16) = rb[i];
-        }
-        uint32_t *sc = reinterpret_cast<uint32_t *>(base + Cfg::A_BYTES + Cfg::B_BYTES);
-        if (tid < BM)
-            sc[tid] = rsa;
-        if (tid < BN)
-            sc[BM + tid] = rsb;
+    };
+
+    // ---- fragment addresses (bytes inside an A or B buffer): row*128 + swizzled 16-byte chunk for
+    // the two K halves a lane holds; tile i sits 16 rows = 2048 bytes further (the swizzle term
+    // (row/2)%8 does not change with multiples of 16 rows). Scale byte: row*4 + K block.
+    const int a_row = wm * Cfg::WM + r16, b_row = wn * Cfg::WN + r16;
+    const int a_off0 = a_row * BK + ((g ^ ((a_row >> 1) & 7)) << 4), a_off1 = a_row * BK + (((4 + g) ^ ((a_row >> 1) & 7)) << 4);
+    const int b_off0 = b_row * BK + ((g ^ ((b_row >> 1) & 7)) << 4), b_off1 = b_row * BK + (((4 + g) ^ ((b_row >> 1) & 7)) << 4);
+    const int a_soff = a_row * 4 + g, b_soff = b_row * 4 + g;
+    auto read_frag = [&](const uint8_t *base, int off0, int off1) __attribute__((always_inline)) {
+        const v4i lo = *reinterpret_cast<const v4i *>(base + off0);
+        const v4i hi = *reinterpret_cast<const v4i *>(base + off1);
+        return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     };
 
     v4f acc[TM][TN];
@@ -139,49 +198,82 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         for (int j = 0; j < TN; ++j)
             acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](int buf) {
-        const uint8_t *base = lds + buf * Cfg::STAGE_BYTES;
-        const uint8_t *as_ = base;
-        const uint8_t *bs_ = base + Cfg::A_BYTES;
-        const uint32_t *sc = reinterpret_cast<const uint32_t *>(base + Cfg::A_BYTES + Cfg::B_BYTES);
-        v8i fa[TM];
-        int sa[TM];
+    // DMA issue plan inside a step of TM*TN MFMAs: the B requests go out with the MFMAs of the
+    // first column (two with the first MFMAs when there are more requests than MFMAs), the A
+    // requests one per MFMA right after the mid-step barrier. Issuing them early matters more than
+    // spacing them out: each request must have landed by the end of the step (B) or of the next (A).
+    constexpr int A_FIRST = TM, A_EVERY = 1;
+    auto step = [&](int kt) __attribute__((always_inline)) {
+        const int cur = kt & 1, nxt = cur ^ 1;
+        // past the end of K the prefetches fetch the last step again into buffers nobody reads any
+        // more: every step runs the same branch-free code and the wait counts stay valid
+        const int kt1 = min(kt + 1, KT - 1), kt2 = min(kt + 2, KT - 1);
+        const uint8_t *abuf = lds + Cfg::A_OFF + cur * Cfg::A_BYTES, *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES;
+        const uint8_t *sabuf = lds + Cfg::SA_OFF + cur * Cfg::BM * 4, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
+        v8i fa[TM], fb[2];
+        int sa[TM], sb[2];
+        fb[0] = read_frag(bbuf, b_off0, b_off1);
+        sb[0] = (sbbuf[b_soff]);
+        fa[0] = read_frag(abuf, a_off0, a_off1);
+        sa[0] = (sabuf[a_soff]);
+        MXFP8_PIN();
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int row = wm * Cfg::WM + i * 16 + r16;
-            const v4i lo = *reinterpret_cast<const v4i *>(as_ + row * BK + swz(row, g) * 16);
-            const v4i hi = *reinterpret_cast<const v4i *>(as_ + row * BK + swz(row, 4 + g) * 16);
-            fa[i] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            sa[i] = (int)(sc[row] >> (8 * g));
+            if (i + 1 < TM) {
+                fa[i + 1] = read_frag(abuf, a_off0 + (i + 1) * 2048, a_off1 + (i + 1) * 2048);
+                sa[i + 1] = (sabuf[a_soff + (i + 1) * 64]);
+            } else if (TN > 1) {
+                fb[1] = read_frag(bbuf, b_off0 + 2048, b_off1 + 2048);
+                sb[1] = (sbbuf[b_soff + 64]);
+            }
+            MXFP8_PIN();
+            acc[i][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[0], fa[i], acc[i][0], 0, 0, 0, sb[0], 0,
+                                                                         sa[i]);
+            MXFP8_PIN();
+            issue_b(i, kt1, nxt);
+            if (i + TM < Cfg::NB)
+                issue_b(i + TM, kt1, nxt);
+            MXFP8_PIN();
         }
+        __syncthreads();  // all A fragments of this step are in registers: its A buffer may be refilled
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int row = wn * Cfg::WN + j * 16 + r16;
-            const v4i lo = *reinterpret_cast<const v4i *>(bs_ + row * BK + swz(row, g) * 16);
-            const v4i hi = *reinterpret_cast<const v4i *>(bs_ + row * BK + swz(row, 4 + g) * 16);
-            const v8i fb = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            const int sb = (int)(sc[BM + row] >> (8 * g));
+        for (int j = 1; j < TN; ++j) {
+            if (j + 1 < TN) {
+                fb[(j + 1) & 1] = read_frag(bbuf, b_off0 + (j + 1) * 2048, b_off1 + (j + 1) * 2048);
+                sb[(j + 1) & 1] = (sbbuf[b_soff + (j + 1) * 64]);
+            }
+            MXFP8_PIN();
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb, fa[i], acc[i][j], 0, 0, 0, sb,
-                                                                             0, sa[i]);
+            for (int i = 0; i < TM; ++i) {
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j & 1], fa[i], acc[i][j], 0, 0, 0,
+                                                                             sb[j & 1], 0, sa[i]);
+                MXFP8_PIN();
+                const int m = j * TM + i;
+                if (m >= A_FIRST && (m - A_FIRST) % A_EVERY == 0 && (m - A_FIRST) / A_EVERY < Cfg::NA)
+                    issue_a((m - A_FIRST) / A_EVERY, kt2, cur);
+                MXFP8_PIN();
+            }
         }
+        MXFP8_WAIT_VMCNT(Cfg::A_LOADS);  // everything older than this step's A requests has landed
+        __syncthreads();
     };
 
     if (KT > 0) {
-        load_global(0);
-        store_lds(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more)
-            load_global(kt + 1);
-        compute(kt & 1);
-        if (more)
-            store_lds((kt + 1) & 1);
+#pragma unroll
+        for (int t = 0; t < Cfg::NA; ++t)
+            issue_a(t, 0, 0);
+#pragma unroll
+        for (int t = 0; t < Cfg::NB; ++t)
+            issue_b(t, 0, 0);
+#pragma unroll
+        for (int t = 0; t < Cfg::NA; ++t)
+            issue_a(t, min(1, KT - 1), 1);
+        MXFP8_WAIT_VMCNT(0);
         __syncthreads();
     }
+    for (int kt = 0; kt < KT; ++kt)
+        step(kt);
+    MXFP8_WAIT_VMCNT(0);  // drain the redundant tail prefetches before the LDS allocation is released
 
     // ---- epilogue: lane (r16, g) of tile (i, j) holds C[m0w + 16i + r16][n0w + 16j + 4g + 0..3]
 #pragma unroll
