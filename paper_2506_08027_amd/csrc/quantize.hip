@@ -2,18 +2,22 @@
 // columns, or both from a single read of the source (Section 3.2; conversion of Section 3.3,
 // Algorithm 1, Appendix A.1 and A.2).
 //
-// Work decomposition. One wavefront owns a tile of 32 rows x 16*VEC columns, VEC = elements per
-// 128-bit load (8 for BF16, 4 for FP32). Lane l = 16*rs + cc holds, in registers, rows
-// 8*rs .. 8*rs+7 of column chunk cc (VEC consecutive columns): eight 128-bit loads, each covering
-// 256 contiguous bytes of four rows per instruction.
-//   * Row direction: a 32-column block is spread over 32/VEC neighbouring lanes of one row of 16
-//     lanes, so its amax is a DPP butterfly (no LDS); each lane then converts its own VEC values.
-//   * Column direction: a 32-row block is 8 rows in each of the four lanes {cc, cc+16, cc+32,
-//     cc+48}; the per-lane maxima are combined with two lane exchanges, then every lane converts
-//     its 8 rows x VEC columns walking DOWN the column, so the packed bytes come out in the order
-//     the transposed copy stores them (8 consecutive bytes per column, no transpose in memory).
-// A workgroup stacks four wavefronts vertically (128 rows), so the four 32-byte pieces of a
-// 128-byte line of the transposed copy are written by the same workgroup at the same time.
+// Work decomposition. A workgroup of four wavefronts owns a tile of 128 rows x 128 columns; each
+// wavefront owns 32 rows of it (one column block) and holds them in registers:
+//   BF16: lane l = 16*rs + cc holds rows 8*rs..8*rs+7   of columns 8*cc..8*cc+7 (8 x 128-bit loads)
+//   FP32: lane l = 32*rs + cc holds rows 16*rs..16*rs+15 of columns 4*cc..4*cc+3 (16 x 128-bit loads)
+// so every load instruction reads whole 256/512-byte row segments.
+//   * Row direction: a 32-column block is spread over 4 (BF16) or 8 (FP32) neighbouring lanes of a
+//     DPP row, so its amax is a DPP butterfly; each lane converts its own values and stores them
+//     directly: the 16 or 32 lanes of a row segment write one full 128-byte line.
+//   * Column direction: a 32-row block is split over the 4 (BF16) or 2 (FP32) lanes that share cc;
+//     the per-lane maxima are combined with lane exchanges, then every lane converts its rows
+//     walking DOWN each column, so the packed bytes come out in the order the transposed copy
+//     stores them. The 8- or 16-byte pieces are staged in LDS as [column][128 row bytes] and
+//     written out by the whole workgroup as full 128-byte lines of q_colT (a direct store would
+//     scatter 32-byte pieces, which the memory system handles at roughly half the rate).
+//   * Scale bytes take the same road: they are collected in LDS and leave as one dword per row
+//     (4 column blocks) and one dword per column (4 row blocks) instead of single bytes.
 //
 // amax is taken as an unsigned integer maximum of the magnitude bits: exact, independent of
 // denormal modes, and it orders NaN > Inf > finite, which is all the special-value rule needs.
@@ -23,11 +27,19 @@ namespace mxfp8 {
 
 constexpr int kQuantWaves = 4;
 constexpr int kQuantThreads = 64 * kQuantWaves;
-constexpr int kTileRows = 32;  // per wavefront
+constexpr int kTile = 128;  // rows and columns per workgroup
 
-template <bool BF16> struct Vec;
-template <> struct Vec<true> { static constexpr int n = 8; };
-template <> struct Vec<false> { static constexpr int n = 4; };
+template <bool BF16> struct QTraits;
+template <> struct QTraits<true> {
+    static constexpr int VEC = 8;    // elements per 128-bit load
+    static constexpr int ROWS = 8;   // rows per lane
+    static constexpr int CC = 16;    // lanes along the columns
+};
+template <> struct QTraits<false> {
+    static constexpr int VEC = 4;
+    static constexpr int ROWS = 16;
+    static constexpr int CC = 32;
+};
 
 // magnitude bits of one 128-bit vector, reduced to one value per lane
 template <bool BF16> __device__ __forceinline__ uint32_t lane_amax(const uint4 &x)
@@ -49,15 +61,43 @@ template <bool BF16> __device__ __forceinline__ uint32_t scale_byte(uint32_t abs
         return scale_byte_from_f32_bits(abs_bits);
 }
 
-// BF16 element `j` (0..7) of a 128-bit vector, as 16 bits
-__device__ __forceinline__ uint32_t bf16_at(const uint4 &x, int j)
-{
-    const uint32_t w = (j >> 1) == 0 ? x.x : (j >> 1) == 1 ? x.y : (j >> 1) == 2 ? x.z : x.w;
-    return (j & 1) ? w >> 16 : w & 0xFFFFu;
-}
 __device__ __forceinline__ uint32_t word_at(const uint4 &x, int j)
 {
     return j == 0 ? x.x : j == 1 ? x.y : j == 2 ? x.z : x.w;
+}
+// element j of a 128-bit vector as raw bits (16 bits for BF16, 32 for FP32)
+template <bool BF16> __device__ __forceinline__ uint32_t elem_at(const uint4 &x, int j)
+{
+    if constexpr (BF16) {
+        const uint32_t w = word_at(x, j >> 1);
+        return (j & 1) ? w >> 16 : w & 0xFFFFu;
+    } else {
+        return word_at(x, j);
+    }
+}
+template <bool BF16> __device__ __forceinline__ uint32_t inf_byte(uint32_t bits, uint32_t q)
+{
+    if constexpr (BF16)
+        return inf_byte_bf16(bits, q);
+    else
+        return inf_byte_f32(bits, q);
+}
+
+// Four element bytes of column j taken from rows r0..r0+3 of the lane's registers.
+template <bool BF16, int NROWS>
+__device__ __forceinline__ uint32_t convert_down4(const uint4 (&x)[NROWS], int r0, int j, float sc)
+{
+    uint32_t q = 0;
+    if constexpr (BF16) {
+        // pair (row r, row r+1) of column j: bytes [1:0] or [3:2] of each word
+        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+        q = cvt2_bf16(q, __builtin_amdgcn_perm(word_at(x[r0 + 1], j >> 1), word_at(x[r0], j >> 1), sel), sc, false);
+        q = cvt2_bf16(q, __builtin_amdgcn_perm(word_at(x[r0 + 3], j >> 1), word_at(x[r0 + 2], j >> 1), sel), sc, true);
+    } else {
+        q = cvt2_f32(q, __uint_as_float(word_at(x[r0], j)), __uint_as_float(word_at(x[r0 + 1], j)), sc, false);
+        q = cvt2_f32(q, __uint_as_float(word_at(x[r0 + 2], j)), __uint_as_float(word_at(x[r0 + 3], j)), sc, true);
+    }
+    return q;
 }
 
 template <bool BF16, bool ROW, bool COL>
@@ -66,34 +106,44 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     uint8_t *__restrict__ q_row, uint8_t *__restrict__ s_row, uint8_t *__restrict__ q_colT,
     uint8_t *__restrict__ s_colT, uint32_t tiles_x)
 {
-    constexpr int VEC = Vec<BF16>::n;
-    constexpr int TILE_COLS = 16 * VEC;
+    using T = QTraits<BF16>;
+    constexpr int VEC = T::VEC, ROWS = T::ROWS, CC = T::CC;
     constexpr int ESIZE = BF16 ? 2 : 4;
-    constexpr int LANES_PER_BLOCK = kBlock / VEC;  // 4 (BF16) or 8 (FP32)
+    constexpr int LANES_PER_BLOCK = kBlock / VEC;  // lanes sharing a row block: 4 (BF16) or 8 (FP32)
+    constexpr int PIECE = ROWS;                    // bytes a lane contributes to one column of q_colT
 
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int cc = lane & 15;
-    const int rs = lane >> 4;
+    // column copy staged as [128 columns][128 row bytes]; row / column scale bytes as [128][4]
+    __shared__ __attribute__((aligned(16))) uint8_t lds_q[COL ? kTile * kTile : 16];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_rs[ROW ? kTile * 4 : 16];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_cs[COL ? kTile * 4 : 16];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int cc = lane % CC;
+    const int rs = lane / CC;
+    const int lrow0 = wave * 32 + rs * ROWS;  // first row of this lane inside the tile
+    const int lcol0 = cc * VEC;               // first column of this lane inside the tile
+    const int64_t nb_row = cols / kBlock, nb_col = rows / kBlock;
+
     const uint32_t tile_y = blockIdx.x / tiles_x, tile_x = blockIdx.x - tile_y * tiles_x;
-    const int64_t col0 = (int64_t)tile_x * TILE_COLS + cc * VEC;
-    const int64_t row0 = ((int64_t)tile_y * kQuantWaves + wave) * kTileRows + rs * 8;
-    // rows % 32 == 0 and cols % 32 == 0: a wavefront tile is wholly inside or outside in rows, and
-    // whole 32-column blocks (groups of LANES_PER_BLOCK lanes) are inside or outside in columns.
+    const int64_t wg_col0 = (int64_t)tile_x * kTile, wg_row0 = (int64_t)tile_y * kTile;
+    const int64_t col0 = wg_col0 + lcol0, row0 = wg_row0 + lrow0;
+    // rows % 32 == 0 and cols % 32 == 0: a wavefront's 32 rows are wholly inside or outside a
+    // ragged tile, and whole 32-column blocks (groups of LANES_PER_BLOCK lanes) are too.
     const bool active = col0 < cols && row0 < rows;
 
-    uint4 x[8];
+    uint4 x[ROWS];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < ROWS; ++i) {
         x[i] = make_uint4(0, 0, 0, 0);
         if (active)
             x[i] = *reinterpret_cast<const uint4 *>(src + (row0 + i) * ld_bytes + col0 * ESIZE);
     }
 
     if constexpr (ROW) {
-        const int64_t nb = cols / kBlock;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < ROWS; ++i) {
             uint32_t am = lane_amax<BF16>(x[i]);
             am = umax(am, dpp_xor1(am));
             am = umax(am, dpp_xor2(am));
@@ -115,21 +165,16 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
                 if (sb == 0xFF) {
                     q0 = 0x7F7F7F7Fu;
                     q1 = 0x7F7F7F7Fu;
-                } else if constexpr (BF16) {
+                } else {
                     uint32_t f0 = 0, f1 = 0;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        f0 |= inf_byte_bf16(bf16_at(x[i], j), (q0 >> (8 * j)) & 0xFFu) << (8 * j);
-                        f1 |= inf_byte_bf16(bf16_at(x[i], 4 + j), (q1 >> (8 * j)) & 0xFFu) << (8 * j);
+                        f0 |= inf_byte<BF16>(elem_at<BF16>(x[i], j), (q0 >> (8 * j)) & 0xFFu) << (8 * j);
+                        if constexpr (BF16)
+                            f1 |= inf_byte<BF16>(elem_at<BF16>(x[i], 4 + j), (q1 >> (8 * j)) & 0xFFu) << (8 * j);
                     }
                     q0 = f0;
                     q1 = f1;
-                } else {
-                    uint32_t f0 = 0;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        f0 |= inf_byte_f32(word_at(x[i], j), (q0 >> (8 * j)) & 0xFFu) << (8 * j);
-                    q0 = f0;
                 }
             }
             if (active) {
@@ -138,32 +183,33 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
                     *reinterpret_cast<uint2 *>(qp) = make_uint2(q0, q1);
                 else
                     *reinterpret_cast<uint32_t *>(qp) = q0;
-                if ((cc % LANES_PER_BLOCK) == 0)
-                    s_row[(row0 + i) * nb + col0 / kBlock] = (uint8_t)sb;
             }
+            if ((cc % LANES_PER_BLOCK) == 0)
+                lds_rs[(lrow0 + i) * 4 + cc / LANES_PER_BLOCK] = (uint8_t)sb;
         }
     }
 
     if constexpr (COL) {
-        const int64_t nb = rows / kBlock;
-        // per-lane maxima of the 8 rows, element-wise over the VEC columns
+        // per-lane maxima of the lane's rows, element-wise over the VEC columns
         uint32_t cm[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             uint32_t m = 0;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < ROWS; ++i) {
                 const uint32_t v = word_at(x[i], w);
                 if constexpr (BF16)
                     m = pk_max_u16(m, v & 0x7FFF7FFFu);
                 else
                     m = umax(m, v & 0x7FFFFFFFu);
             }
-            // the other three lanes holding rows of the same 32-row block: lane ^ 16, lane ^ 32
-            uint32_t o = (uint32_t)__shfl_xor((int)m, 16, 64);
+            // the other lanes holding rows of the same 32-row block share cc: lane ^ 32 (and ^ 16)
+            uint32_t o = (uint32_t)__shfl_xor((int)m, 32, 64);
             m = BF16 ? pk_max_u16(m, o) : umax(m, o);
-            o = (uint32_t)__shfl_xor((int)m, 32, 64);
-            m = BF16 ? pk_max_u16(m, o) : umax(m, o);
+            if constexpr (BF16) {
+                o = (uint32_t)__shfl_xor((int)m, 16, 64);
+                m = pk_max_u16(m, o);
+            }
             cm[w] = m;
         }
 #pragma unroll
@@ -175,48 +221,85 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
                 am = cm[j];
             const uint32_t sb = scale_byte<BF16>(am);
             const float sc = scale_operand(sb);
-            uint32_t q0 = 0, q1 = 0;  // rows 0..3 and 4..7 of this lane, one byte each
-            if constexpr (BF16) {
-                // pair (row i, row i+1) of column j: bytes [1:0] or [3:2] of each word
-                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-#define MXFP8_PAIR(i) __builtin_amdgcn_perm(word_at(x[(i) + 1], j >> 1), word_at(x[i], j >> 1), sel)
-                q0 = cvt2_bf16(q0, MXFP8_PAIR(0), sc, false);
-                q0 = cvt2_bf16(q0, MXFP8_PAIR(2), sc, true);
-                q1 = cvt2_bf16(q1, MXFP8_PAIR(4), sc, false);
-                q1 = cvt2_bf16(q1, MXFP8_PAIR(6), sc, true);
-#undef MXFP8_PAIR
-            } else {
-#define MXFP8_F(i) __uint_as_float(word_at(x[i], j))
-                q0 = cvt2_f32(q0, MXFP8_F(0), MXFP8_F(1), sc, false);
-                q0 = cvt2_f32(q0, MXFP8_F(2), MXFP8_F(3), sc, true);
-                q1 = cvt2_f32(q1, MXFP8_F(4), MXFP8_F(5), sc, false);
-                q1 = cvt2_f32(q1, MXFP8_F(6), MXFP8_F(7), sc, true);
-#undef MXFP8_F
-            }
-            if (sb >= 254) {
-                if (sb == 0xFF) {
-                    q0 = 0x7F7F7F7Fu;
-                    q1 = 0x7F7F7F7Fu;
-                } else {
-                    uint32_t f0 = 0, f1 = 0;
+            uint32_t q[ROWS / 4];  // one byte per row of this lane, in row order
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if constexpr (BF16) {
-                            f0 |= inf_byte_bf16(bf16_at(x[i], j), (q0 >> (8 * i)) & 0xFFu) << (8 * i);
-                            f1 |= inf_byte_bf16(bf16_at(x[4 + i], j), (q1 >> (8 * i)) & 0xFFu) << (8 * i);
-                        } else {
-                            f0 |= inf_byte_f32(word_at(x[i], j), (q0 >> (8 * i)) & 0xFFu) << (8 * i);
-                            f1 |= inf_byte_f32(word_at(x[4 + i], j), (q1 >> (8 * i)) & 0xFFu) << (8 * i);
-                        }
+            for (int r = 0; r < ROWS / 4; ++r)
+                q[r] = convert_down4<BF16, ROWS>(x, 4 * r, j, sc);
+            if (sb >= 254) {
+#pragma unroll
+                for (int r = 0; r < ROWS / 4; ++r) {
+                    if (sb == 0xFF) {
+                        q[r] = 0x7F7F7F7Fu;
+                    } else {
+                        uint32_t f = 0;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            f |= inf_byte<BF16>(elem_at<BF16>(x[4 * r + i], j), (q[r] >> (8 * i)) & 0xFFu) << (8 * i);
+                        q[r] = f;
                     }
-                    q0 = f0;
-                    q1 = f1;
                 }
             }
-            if (active) {
-                *reinterpret_cast<uint2 *>(q_colT + (col0 + j) * rows + row0) = make_uint2(q0, q1);
-                if (rs == 0)
-                    s_colT[(col0 + j) * nb + row0 / kBlock] = (uint8_t)sb;
+            // stage: column (lcol0 + j), row bytes lrow0 .. lrow0 + PIECE - 1. The 16-byte slot index
+            // inside the 128-byte column line is XORed with the column chunk so that the lanes of one
+            // store instruction (same j, consecutive cc) fall into different LDS banks.
+            const int col = lcol0 + j;
+            const int slot16 = (lrow0 >> 4) ^ (cc & 7);
+            uint8_t *dst = lds_q + col * kTile + slot16 * 16 + (lrow0 & 15);
+            if constexpr (BF16)
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(q[0], q[1]);
+            else
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(q[0], q[1], q[2], q[3]);
+            if (rs == 0)
+                lds_cs[col * 4 + wave] = (uint8_t)sb;
+        }
+    }
+
+    __syncthreads();
+
+    // ---- write-out of the staged pieces: full 128-byte lines, one dword of scales per row/column
+    if constexpr (ROW) {
+        if (tid < kTile) {
+            const int64_t r = wg_row0 + tid;
+            if (r < rows) {
+                const uint32_t w = *reinterpret_cast<const uint32_t *>(lds_rs + tid * 4);
+                uint8_t *sp = s_row + r * nb_row + wg_col0 / kBlock;
+                if (wg_col0 + kTile <= cols && (nb_row & 3) == 0 && (reinterpret_cast<uintptr_t>(s_row) & 3) == 0) {
+                    *reinterpret_cast<uint32_t *>(sp) = w;
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if (wg_col0 + b * kBlock < cols)
+                            sp[b] = (uint8_t)(w >> (8 * b));
+                }
+            }
+        }
+    }
+    if constexpr (COL) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int chunk = p * kQuantThreads + tid;  // 16-byte chunk of the staged tile
+            const int col = chunk >> 3, part = chunk & 7;
+            const int64_t c = wg_col0 + col, r = wg_row0 + part * 16;
+            if (c < cols && r < rows) {
+                const int slot16 = part ^ ((col / VEC) & 7);
+                const uint4 v = *reinterpret_cast<const uint4 *>(lds_q + col * kTile + slot16 * 16);
+                *reinterpret_cast<uint4 *>(q_colT + c * rows + r) = v;
+            }
+        }
+        if (tid >= kTile) {  // the upper half of the workgroup, so that it overlaps the row scales
+            const int col = tid - kTile;
+            const int64_t c = wg_col0 + col;
+            if (c < cols) {
+                const uint32_t w = *reinterpret_cast<const uint32_t *>(lds_cs + col * 4);
+                uint8_t *sp = s_colT + c * nb_col + wg_row0 / kBlock;
+                if (wg_row0 + kTile <= rows && (nb_col & 3) == 0 && (reinterpret_cast<uintptr_t>(s_colT) & 3) == 0) {
+                    *reinterpret_cast<uint32_t *>(sp) = w;
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if (wg_row0 + b * kBlock < rows)
+                            sp[b] = (uint8_t)(w >> (8 * b));
+                }
             }
         }
     }
@@ -227,9 +310,8 @@ static hipError_t launch_quantize_t(const void *src, int64_t rows, int64_t cols,
                                     uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
                                     hipStream_t stream)
 {
-    constexpr int TILE_COLS = 16 * Vec<BF16>::n;
-    const int64_t tiles_x = (cols + TILE_COLS - 1) / TILE_COLS;
-    const int64_t tiles_y = (rows + kTileRows * kQuantWaves - 1) / (kTileRows * kQuantWaves);
+    const int64_t tiles_x = (cols + kTile - 1) / kTile;
+    const int64_t tiles_y = (rows + kTile - 1) / kTile;
     if (tiles_x * tiles_y > 0x7FFFFFFF)
         return hipErrorInvalidConfiguration;
     dim3 grid((unsigned)(tiles_x * tiles_y));
