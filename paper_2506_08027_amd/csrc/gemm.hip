@@ -45,8 +45,7 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_> struct GemmCfg {
     static_assert(BM % (8 * WAVES) == 0 && BN % (8 * WAVES) == 0, "tile rows per wavefront");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "scale rows per instruction");
     static_assert(NB <= 2 * TM, "the B loads of the next step are issued with the MFMAs of the first column");
-    static_assert(NA <= (TN - 1) * TM, "the A loads are issued one per MFMA after the first column");
-    static_assert(A_LOADS < 16, "wait-count immediate");
+    static_assert(NA + NB < 64, "wait-count immediate");
 };
 
 // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2. Renumber them so
@@ -90,22 +89,11 @@ __device__ __forceinline__ void dma_load(const uint8_t *base, uint32_t voff, uin
 
 // Nothing may be scheduled across this point: the instruction order below is the schedule.
 #define MXFP8_PIN() __builtin_amdgcn_sched_barrier(0)
-// s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding, n < 16)
-#define MXFP8_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+// s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt is split over bits 3:0 and 15:14)
+#define MXFP8_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
-// Software pipeline. LDS holds two A buffers and two B buffers. In K step kt (buffers kt & 1):
-//   column 0   : the A fragments of the step are read into registers (they stay there for the
-//                whole step) while the first column of MFMAs already runs one fragment behind;
-//                the B tile of step kt+1 is requested into the other B buffer, one DMA
-//                instruction per MFMA;
-//   barrier    : every wavefront has its A fragments, so the A buffer of this step is dead;
-//   columns 1..: B fragments stream through two register sets; the A tile of step kt+2 is
-//                requested into the dead A buffer, again one DMA instruction per MFMA;
-//   end        : wait until at most the A(kt+2) requests are outstanding, i.e. B(kt+1) (and the
-//                older A(kt+1)) have landed; barrier.
-// So B is fetched one step ahead and A two steps ahead: about 96 KB of a 256x256 tile pair are
-// in flight while 64 KB are being consumed, which is what hides the L2/HBM latency with a single
-// wavefront per SIMD.
+// The kernel. LDS holds two A buffers, two B buffers and their scale dwords; the software pipeline
+// is described at the step lambda below.
 template <class Cfg, bool OUT_BF16>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
@@ -146,10 +134,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     }
 #pragma unroll
     for (int i = 0; i < Cfg::SA_LOADS; ++i)
-        as_goff[i] = (uint32_t)min((wave + i * Cfg::WAVES) * 64 + lane, M - 1 - m0) * (uint32_t)nkb;
+        as_goff[i] = (uint32_t)min(((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 64 + lane, M - 1 - m0) * (uint32_t)nkb;
 #pragma unroll
     for (int i = 0; i < Cfg::SB_LOADS; ++i)
-        bs_goff[i] = (uint32_t)min((wave + i * Cfg::WAVES) * 64 + lane, N - 1 - n0) * (uint32_t)nkb;
+        bs_goff[i] = (uint32_t)min(((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 64 + lane, N - 1 - n0) * (uint32_t)nkb;
     const uint8_t *a_tile = a_q + (int64_t)m0 * K, *b_tile = b_q + (int64_t)n0 * K;
     const uint8_t *as_tile = a_s + (int64_t)m0 * nkb, *bs_tile = b_s + (int64_t)n0 * nkb;
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
@@ -161,9 +149,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
                          lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
         } else if (t < Cfg::NA) {
             const int i = t - Cfg::A_LOADS;
-            if (Cfg::BM / 64 >= Cfg::WAVES * (i + 1) || wave + i * Cfg::WAVES < Cfg::BM / 64)
-                dma_load<4>(as_tile + kt * 4, as_goff[i],
-                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + (wave + i * Cfg::WAVES) * 256);
+            // every wavefront issues the same number of requests (the wait counts rely on it):
+            // with fewer 64-row groups than wavefronts some groups are simply fetched twice
+            dma_load<4>(as_tile + kt * 4, as_goff[i],
+                        lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);
         }
     };
     auto issue_b = [&](int t, int kt, int buf) __attribute__((always_inline)) {
@@ -172,9 +161,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
                          lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
         } else if (t < Cfg::NB) {
             const int i = t - Cfg::B_LOADS;
-            if (Cfg::BN / 64 >= Cfg::WAVES * (i + 1) || wave + i * Cfg::WAVES < Cfg::BN / 64)
-                dma_load<4>(bs_tile + kt * 4, bs_goff[i],
-                            lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + (wave + i * Cfg::WAVES) * 256);
+            dma_load<4>(bs_tile + kt * 4, bs_goff[i],
+                        lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 256);
         }
     };
 
@@ -198,63 +186,78 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         for (int j = 0; j < TN; ++j)
             acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // DMA issue plan inside a step of TM*TN MFMAs: the B requests go out with the MFMAs of the
-    // first column (two with the first MFMAs when there are more requests than MFMAs), the A
-    // requests one per MFMA right after the mid-step barrier. Issuing them early matters more than
-    // spacing them out: each request must have landed by the end of the step (B) or of the next (A).
-    constexpr int A_FIRST = TM, A_EVERY = 1;
+    v8i fa[TM];  // A fragments and scale bytes of the current step (refilled in place, see below)
+    int sa[TM];
+
+    // ---- one K step (buffers cur = kt & 1, nxt = the other one) ----------------------------------
+    // State on entry: the A fragments and A scale bytes of step kt are in registers (fa, sa); B(kt)
+    // is in LDS buffer cur; A(kt+1) is in flight towards (or already in) A buffer nxt.
+    //   column 0      : MFMAs start at once (only the first B fragment has to arrive); the B tile of
+    //                   step kt+1 is requested into B buffer nxt, one DMA instruction per MFMA;
+    //   columns 1..-2 : B fragments stream through two register sets; the A tile of step kt+2 is
+    //                   requested into A buffer cur (its fragments were pulled into registers during
+    //                   the previous step), in the second half of each column, when the prefetch
+    //                   read of the next B fragment has drained from the LDS queue;
+    //   barrier M     : wait until only the requests of this step are outstanding, i.e. A(kt+1) has
+    //                   landed for every wavefront;
+    //   last column   : after MFMA (i, last) the registers of A fragment i are dead and are refilled
+    //                   in place with fragment i of A(kt+1): the fragment reads of the next step are
+    //                   spread over this column instead of bursting at its start;
+    //   barrier E     : wait until B(kt+1) has landed (only this step's A requests may be pending).
+    // So B is fetched one step ahead, A almost two, with 96 KB in flight against 64 KB in use.
+    constexpr int A_LO = (TN - 2) * (TM - TM / 2) >= Cfg::NA ? TM / 2 : 0;  // first MFMA of a column that issues
+    static_assert((TN - 2) * (TM - A_LO) >= Cfg::NA, "A requests fit into columns 1..TN-2");
     auto step = [&](int kt) __attribute__((always_inline)) {
         const int cur = kt & 1, nxt = cur ^ 1;
         // past the end of K the prefetches fetch the last step again into buffers nobody reads any
         // more: every step runs the same branch-free code and the wait counts stay valid
         const int kt1 = min(kt + 1, KT - 1), kt2 = min(kt + 2, KT - 1);
-        const uint8_t *abuf = lds + Cfg::A_OFF + cur * Cfg::A_BYTES, *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES;
-        const uint8_t *sabuf = lds + Cfg::SA_OFF + cur * Cfg::BM * 4, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
-        v8i fa[TM], fb[2];
-        int sa[TM], sb[2];
-        fb[0] = read_frag(bbuf, b_off0, b_off1);
-        sb[0] = (sbbuf[b_soff]);
-        fa[0] = read_frag(abuf, a_off0, a_off1);
-        sa[0] = (sabuf[a_soff]);
-        MXFP8_PIN();
+        const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
+        const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::BM * 4;
+        // B fragments stream through NFB register sets, fetched NFB-1 columns ahead of their use
+        constexpr int NFB = 3;
+        v8i fb[NFB];
+        int sb[NFB];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (i + 1 < TM) {
-                fa[i + 1] = read_frag(abuf, a_off0 + (i + 1) * 2048, a_off1 + (i + 1) * 2048);
-                sa[i + 1] = (sabuf[a_soff + (i + 1) * 64]);
-            } else if (TN > 1) {
-                fb[1] = read_frag(bbuf, b_off0 + 2048, b_off1 + 2048);
-                sb[1] = (sbbuf[b_soff + 64]);
-            }
-            MXFP8_PIN();
-            acc[i][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[0], fa[i], acc[i][0], 0, 0, 0, sb[0], 0,
-                                                                         sa[i]);
-            MXFP8_PIN();
-            issue_b(i, kt1, nxt);
-            if (i + TM < Cfg::NB)
-                issue_b(i + TM, kt1, nxt);
-            MXFP8_PIN();
+        for (int j = 0; j < NFB - 1 && j < TN; ++j) {
+            fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
+            sb[j] = sbbuf[b_soff + j * 64];
         }
-        __syncthreads();  // all A fragments of this step are in registers: its A buffer may be refilled
+        MXFP8_PIN();
+        int a_slot = 0;  // compile-time after unrolling
 #pragma unroll
-        for (int j = 1; j < TN; ++j) {
-            if (j + 1 < TN) {
-                fb[(j + 1) & 1] = read_frag(bbuf, b_off0 + (j + 1) * 2048, b_off1 + (j + 1) * 2048);
-                sb[(j + 1) & 1] = (sbbuf[b_soff + (j + 1) * 64]);
+        for (int j = 0; j < TN; ++j) {
+            if (j + NFB - 1 < TN) {
+                fb[(j + NFB - 1) % NFB] = read_frag(bbuf, b_off0 + (j + NFB - 1) * 2048, b_off1 + (j + NFB - 1) * 2048);
+                sb[(j + NFB - 1) % NFB] = sbbuf[b_soff + (j + NFB - 1) * 64];
+            }
+            if (j == TN - 1) {
+                MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);  // all but this step's requests: A(kt+1) is in LDS
+                __syncthreads();
             }
             MXFP8_PIN();
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j & 1], fa[i], acc[i][j], 0, 0, 0,
-                                                                             sb[j & 1], 0, sa[i]);
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j % NFB], fa[i], acc[i][j], 0, 0, 0,
+                                                                             sb[j % NFB], 0, sa[i]);
                 MXFP8_PIN();
-                const int m = j * TM + i;
-                if (m >= A_FIRST && (m - A_FIRST) % A_EVERY == 0 && (m - A_FIRST) / A_EVERY < Cfg::NA)
-                    issue_a((m - A_FIRST) / A_EVERY, kt2, cur);
+                if (j == 0) {
+                    issue_b(i, kt1, nxt);
+                    if (i + TM < Cfg::NB)
+                        issue_b(i + TM, kt1, nxt);
+                } else if (j < TN - 1 && i >= A_LO) {
+                    if (a_slot < Cfg::NA)
+                        issue_a(a_slot, kt2, cur);
+                    ++a_slot;
+                }
+                if (j == TN - 1) {
+                    fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
+                    sa[i] = sanext[a_soff + i * 64];
+                }
                 MXFP8_PIN();
             }
         }
-        MXFP8_WAIT_VMCNT(Cfg::A_LOADS);  // everything older than this step's A requests has landed
+        MXFP8_WAIT_VMCNT(Cfg::NA);  // everything older than this step's A requests: B(kt+1) is in LDS
         __syncthreads();
     };
 
@@ -270,6 +273,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
             issue_a(t, min(1, KT - 1), 1);
         MXFP8_WAIT_VMCNT(0);
         __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
+            sa[i] = (lds + Cfg::SA_OFF)[a_soff + i * 64];
+        }
+        __syncthreads();  // A buffer 0 is refilled by the requests of step 0 from here on
     }
     for (int kt = 0; kt < KT; ++kt)
         step(kt);
