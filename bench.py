@@ -46,7 +46,7 @@ def cpu_baseline():
     """The oracle as it stands on the host cores, on a bounded sample of the same workload."""
     import oracle
     from paper_2506_08027_amd import synth_inputs as si
-    rows_q, rows_g, cols_g = 4096, 256, O
+    rows_q, rows_g, cols_g = 8192, 2048, O
     x = si.activations(rows_q, H, seed=2)
     w = si.weights(O, H, seed=4)
     t0 = time.perf_counter()
@@ -68,12 +68,29 @@ def cpu_baseline():
     }
 
 
+def traffic_from_profile(row_prefix):
+    """HBM-side bytes per launch (fetched + written) measured with rocprofv3 PMC counters and kept in
+    profiles/hbm_traffic_pmc.txt (the counters cannot be read from inside this process)."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")) as f:
+            for line in f:
+                if line.startswith(row_prefix):
+                    cells = [c.strip() for c in line.split("|")]
+                    return (float(cells[1]) + float(cells[2])) * 1e6
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, used to scale the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -134,6 +151,13 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = dt / args.steps * 1e3
     step_flops = 3 * 2.0 * T * H * O
     gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_ev]))
@@ -154,10 +178,11 @@ def main():
                    "T": T, "H": H, "O": O},
         "gemm_tflops_fprop": gemm_tflops, "quantize_gbs_bf16_both": quant_gbs,
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / MFMA_FP8_PEAK_TFLOPS, "traffic": None,
+                     "frac": gemm_tflops / MFMA_FP8_PEAK_TFLOPS,
+                     "traffic": traffic_from_profile("fprop 8192x14336x4096"),
                      "kernel": "gemm_kernel (fprop 8192x14336x4096, BF16 out)", "avg_ms": gemm_ms},
         "roofline_quantize": {"bound": "hbm", "achieved": quant_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": quant_gbs / HBM_PEAK_GBS, "traffic": None,
+                              "frac": quant_gbs / HBM_PEAK_GBS, "traffic": traffic_from_profile("quantize X BF16"),
                               "kernel": "quantize_kernel<BF16, row+col> (X 8192x4096)", "avg_ms": quant_ms},
     }
     if not args.no_cpu_baseline:
