@@ -46,14 +46,14 @@ def cpu_baseline():
     """The oracle as it stands on the host cores, on a bounded sample of the same workload."""
     import oracle
     from paper_2506_08027_amd import synth_inputs as si
-    rows_q, rows_g, cols_g = 8192, 2048, O
+    rows_q, rows_g, cols_g = 4096, 4096, 4096   # about 20 s of oracle time on 8 to 16 cores
     x = si.activations(rows_q, H, seed=2)
-    w = si.weights(O, H, seed=4)
+    w = si.weights(cols_g, H, seed=4)
     t0 = time.perf_counter()
     xq, xs = oracle.quantize_rowwise(x)
     oracle.quantize_colwise(x)
     tq = time.perf_counter() - t0
-    wq, ws = oracle.quantize_rowwise(w[:cols_g])     # operands for the GEMM sample
+    wq, ws = oracle.quantize_rowwise(w)              # operands for the GEMM sample
     t0 = time.perf_counter()
     oracle.gemm_rows(xq, xs, wq, ws, np.arange(rows_g))
     tg = time.perf_counter() - t0
