@@ -94,8 +94,9 @@ mxfp8_status mxfp8_quantize(const void *src, mxfp8_dtype src_dtype, int64_t rows
  * ldc >= N. Requirements: K % 128 == 0 (one scaled MFMA consumes four blocks); a_q, b_q, a_s, b_s
  * 16-byte aligned; c aligned to its element size. When c is 16-byte aligned and
  * ldc * sizeof(element) is a multiple of 16 the result is written with 128-bit stores, otherwise
- * element by element (slower, same values). M and N are arbitrary; M, N or K equal to 0 is
- * accepted (K == 0 stores zeros).
+ * element by element (slower, same values). M and N are arbitrary up to 2^30 with at most 2^31 - 1
+ * tiles of 128 x 128 in C, K up to 2^24 (larger shapes return MXFP8_ERR_SHAPE); M, N or K equal to
+ * 0 is accepted (K == 0 stores zeros).
  * A scale byte 0xFF or an element NaN makes every output it touches NaN; products that overflow
  * FP32 give +-Inf or NaN as the hardware accumulator does.
  */

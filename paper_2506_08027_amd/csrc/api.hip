@@ -19,6 +19,10 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline bool valid_dtype(int d) { return d == MXFP8_F32 || d == MXFP8_BF16; }
 inline int64_t esize(int d) { return d == MXFP8_BF16 ? 2 : 4; }
 constexpr int64_t kMaxDim = 0x7FFFFFFF;  // kernels index rows and columns with 32-bit tile math
+// GEMM: tile origins (multiples of up to 256 past M or N) stay in 32 bits, a lane's byte offset inside
+// a 256-row operand tile (255 * K + 127) stays in 32 bits unsigned, and the grid (one workgroup per
+// 128x128 tile at the finest) fits the launch
+constexpr int64_t kMaxGemmMN = int64_t(1) << 30, kMaxGemmK = int64_t(1) << 24;
 }  // namespace
 
 extern "C" {
@@ -55,7 +59,8 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
         return MXFP8_ERR_DTYPE;
     if (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD)
         return MXFP8_ERR_MODE;
-    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim || K % 128 || ldc < N)
+    if (M < 0 || N < 0 || K < 0 || M > kMaxGemmMN || N > kMaxGemmMN || K > kMaxGemmK || K % 128 || ldc < N ||
+        ((M + 127) / 128) * ((N + 127) / 128) > kMaxDim)
         return MXFP8_ERR_SHAPE;
     if (M == 0 || N == 0)
         return MXFP8_OK;

@@ -14,14 +14,13 @@
 // four consecutive n of one m: the epilogue is one 128-bit store per 16x16 tile and lane.
 //
 // Tiling. A workgroup of WAVES_M x WAVES_N wavefronts computes a BM x BN tile of C, K in steps of
-// 128 bytes (= one MFMA, four scale blocks). A and B tiles go from global memory straight into
-// LDS (global_load_lds_dwordx4: no staging registers), two LDS stages: the loads of step k+1 are
-// issued before the MFMAs of step k, one barrier per step. LDS rows are 128 bytes; the 16-byte
-// chunk index is XORed with (row/2)%8 so that the 16 lanes of a fragment read hit 16 different
-// bank groups. A direct-to-LDS load writes lane l of a wavefront to LDS offset 16*l, so the
-// swizzle is applied on the global side: each lane fetches the chunk that belongs at its slot.
-// Scale bytes are read from global memory (they are tiny and L2-resident), one byte per lane and
-// MFMA tile, one step ahead.
+// 128 bytes (= one MFMA, four scale blocks). A and B tiles and one dword of scale bytes per row
+// and step go from global memory straight into LDS (global_load_lds_dword{,x4}: no staging
+// registers), two LDS buffers per operand; the software pipeline is described at the step lambda
+// of the kernel. LDS rows are 128 bytes; the 16-byte chunk index is XORed with (row/2)%8 so that
+// the 16 lanes of a fragment read hit 16 different bank groups. A direct-to-LDS load writes lane l
+// of a wavefront to LDS offset 16*l, so the swizzle is applied on the global side: each lane
+// fetches the chunk that belongs at its slot.
 #include "mxfp8_device.h"
 
 namespace mxfp8 {
@@ -68,25 +67,6 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
     tn = panel * PANEL + in_panel % width;
 }
 
-// Global memory -> LDS without passing through registers: lane l of the wavefront fetches BYTES
-// bytes from base + voff (its own address) and the hardware writes them to LDS address
-// lds_addr + l*BYTES (lds_addr is wavefront-uniform and travels in M0).
-// Emitted as inline assembly on purpose: the compiler's wait-count pass treats a pending LDS-DMA
-// load as "may complete out of order with LDS reads" and then turns every wait on an LDS read
-// into a wait for ALL outstanding LDS reads, which would serialise the fragment prefetch.
-// Completion is tracked by hand with s_waitcnt vmcnt(n) in front of the barriers.
-template <int BYTES>
-__device__ __forceinline__ void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
-{
-    const uint32_t m0v = lds_addr;  // callers pass a wavefront-uniform (scalar) address
-    if constexpr (BYTES == 16)
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
-                     : "memory");
-    else
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
-                     : "memory");
-}
-
 // Nothing may be scheduled across this point: the instruction order below is the schedule.
 #define MXFP8_PIN() __builtin_amdgcn_sched_barrier(0)
 // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt is split over bits 3:0 and 15:14)
@@ -100,7 +80,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
     int tiles_m, int tiles_n, bool vec_store)
 {
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    MXFP8_DYNAMIC_LDS(lds);
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     const int tid = threadIdx.x;
     const int lane = tid & 63;

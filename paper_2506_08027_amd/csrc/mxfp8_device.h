@@ -106,4 +106,31 @@ __device__ __forceinline__ uint32_t inf_byte_bf16(uint32_t bits16, uint32_t q)
     return (bits16 & 0x7FFFu) == 0x7F80u ? ((bits16 >> 8) & 0x80u) | 0x7Eu : q;
 }
 
+// ---- what exists only on the GPU --------------------------------------------------------------
+// The CPU tests compile these kernel sources as host C++ against an execution model of their own;
+// that build defines MXFP8_HOST_MODEL and brings its own versions of the two items below.
+#ifndef MXFP8_HOST_MODEL
+// The workgroup's dynamically sized LDS block (size given at launch).
+#define MXFP8_DYNAMIC_LDS(name) extern __shared__ __attribute__((aligned(1024))) uint8_t name[]
+
+// Global memory -> LDS without passing through registers: lane l of the wavefront fetches BYTES
+// bytes from base + voff (its own address) and the hardware writes them to LDS address
+// lds_addr + l*BYTES (lds_addr is wavefront-uniform and travels in M0).
+// Emitted as inline assembly on purpose: the compiler's wait-count pass treats a pending LDS-DMA
+// load as "may complete out of order with LDS reads" and then turns every wait on an LDS read
+// into a wait for ALL outstanding LDS reads, which would serialise the fragment prefetch.
+// Completion is tracked by hand with s_waitcnt vmcnt(n) in front of the barriers.
+template <int BYTES>
+__device__ __forceinline__ void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+{
+    const uint32_t m0v = lds_addr;  // callers pass a wavefront-uniform (scalar) address
+    if constexpr (BYTES == 16)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
+                     : "memory");
+}
+#endif  // MXFP8_HOST_MODEL
+
 }  // namespace mxfp8

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     constexpr int VEC = T::VEC, ROWS = T::ROWS, CC = T::CC;
     constexpr int ESIZE = BF16 ? 2 : 4;
     constexpr int LANES_PER_BLOCK = kBlock / VEC;  // lanes sharing a row block: 4 (BF16) or 8 (FP32)
-    constexpr int PIECE = ROWS;                    // bytes a lane contributes to one column of q_colT
+    [[maybe_unused]] constexpr int PIECE = ROWS;                    // bytes a lane contributes to one column of q_colT
 
     // column copy staged as [128 columns][128 row bytes]; row / column scale bytes as [128][4]
     __shared__ __attribute__((aligned(16))) uint8_t lds_q[COL ? kTile * kTile : 16];

@@ -1,0 +1,191 @@
+// Runs the library's C ABI on the CPU execution model (tests/host_model/wavesim.h): reads a list
+// of calls from a text file, feeds them binary inputs, writes the outputs back as files.
+// Every buffer is an exact-size heap block (AddressSanitizer guards its ends), outputs start out
+// filled with 0xA5, and inputs are checked to be unchanged after the call.
+//
+//   quantize   <f32|bf16> <rows> <cols> <ld> <axis 1|2|3> <src.bin> <out-prefix>
+//   gemm       <pass 0|1|2> <M> <N> <K> <f32|bf16> <ldc> <a_q> <a_s> <b_q> <b_s> <c.bin>
+//   dequantize <rows> <cols> <f32|bf16> <ld> <q.bin> <s.bin> <out.bin>
+// Each call prints "status <code> blocks <ids of the simulated workgroups...>".
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <fstream>
+#include <sstream>
+#include <string>
+#include <vector>
+
+#include "../../include/mxfp8.h"
+#include "wavesim.h"
+
+// buffers live until the process ends and fiber stacks are reused across launches: no leak report wanted
+extern "C" const char *__asan_default_options() { return "detect_leaks=0:detect_stack_use_after_return=0"; }
+
+namespace {
+
+struct Buf {
+    uint8_t *p = nullptr;
+    size_t n = 0;
+    std::vector<uint8_t> copy;
+};
+
+Buf load(const std::string &path, size_t expect)
+{
+    Buf b;
+    FILE *f = fopen(path.c_str(), "rb");
+    if (!f) {
+        fprintf(stderr, "cannot open %s\n", path.c_str());
+        exit(2);
+    }
+    fseek(f, 0, SEEK_END);
+    b.n = (size_t)ftell(f);
+    fseek(f, 0, SEEK_SET);
+    if (b.n != expect) {
+        fprintf(stderr, "%s holds %zu bytes, the call needs %zu\n", path.c_str(), b.n, expect);
+        exit(2);
+    }
+    b.p = b.n ? (uint8_t *)aligned_alloc(16, (b.n + 15) / 16 * 16) : nullptr;
+    // aligned_alloc rounds the size up; re-allocate exactly when that would hide an overrun
+    if (b.n % 16) {
+        free(b.p);
+        void *q = nullptr;
+        if (posix_memalign(&q, 16, b.n) != 0)
+            exit(2);
+        b.p = (uint8_t *)q;
+    }
+    if (b.n && fread(b.p, 1, b.n, f) != b.n)
+        exit(2);
+    fclose(f);
+    b.copy.assign(b.p, b.p + b.n);
+    wavesim::register_buffer(b.p, b.n, path.c_str());
+    return b;
+}
+
+Buf output(size_t n)
+{
+    Buf b;
+    b.n = n;
+    if (n) {
+        void *q = nullptr;
+        if (posix_memalign(&q, 16, n) != 0)
+            exit(2);
+        b.p = (uint8_t *)q;
+        memset(b.p, 0xA5, n);
+        wavesim::register_buffer(b.p, n, "output");
+    }
+    return b;
+}
+
+void save(const std::string &path, const Buf &b)
+{
+    FILE *f = fopen(path.c_str(), "wb");
+    if (!f || (b.n && fwrite(b.p, 1, b.n, f) != b.n)) {
+        fprintf(stderr, "cannot write %s\n", path.c_str());
+        exit(2);
+    }
+    fclose(f);
+}
+
+void unchanged(const Buf &b, const char *what)
+{
+    if (b.n && memcmp(b.p, b.copy.data(), b.n) != 0) {
+        fprintf(stderr, "the call modified its input %s\n", what);
+        exit(4);
+    }
+}
+
+mxfp8_dtype dtype_of(const std::string &s)
+{
+    if (s == "f32")
+        return MXFP8_F32;
+    if (s == "bf16")
+        return MXFP8_BF16;
+    fprintf(stderr, "unknown dtype %s\n", s.c_str());
+    exit(2);
+}
+
+void report(int status)
+{
+    printf("status %d blocks", status);
+    if (status == 0)
+        for (unsigned b : wavesim::g.simulated)
+            printf(" %u", b);
+    printf("\n");
+    fflush(stdout);
+}
+
+}  // namespace
+
+int main(int argc, char **argv)
+{
+    if (argc != 2) {
+        fprintf(stderr, "usage: %s <case file>\n", argv[0]);
+        return 2;
+    }
+    std::ifstream in(argv[1]);
+    std::string line;
+    while (std::getline(in, line)) {
+        std::istringstream ls(line);
+        std::string op;
+        if (!(ls >> op) || op[0] == '#')
+            continue;
+        wavesim::clear_buffers();
+        wavesim::g.simulated.clear();
+        if (op == "quantize") {
+            std::string dt, src, prefix;
+            long rows, cols, ld;
+            int axis;
+            ls >> dt >> rows >> cols >> ld >> axis >> src >> prefix;
+            const size_t es = dt == "bf16" ? 2 : 4;
+            // the source spans (rows-1)*ld + cols elements: no padding after the last row
+            Buf s = load(src, rows > 0 ? ((size_t)(rows - 1) * ld + cols) * es : 0);
+            const bool r = axis & 1, c = axis & 2;
+            Buf qr = output(r ? (size_t)rows * cols : 0), sr = output(r ? (size_t)rows * cols / 32 : 0);
+            Buf qc = output(c ? (size_t)rows * cols : 0), sc = output(c ? (size_t)rows * cols / 32 : 0);
+            const int st = mxfp8_quantize(s.p, dtype_of(dt), rows, cols, ld, (mxfp8_axis)axis, qr.p, sr.p, qc.p, sc.p, nullptr);
+            unchanged(s, "src");
+            report(st);
+            if (r) {
+                save(prefix + ".q_row", qr);
+                save(prefix + ".s_row", sr);
+            }
+            if (c) {
+                save(prefix + ".q_colT", qc);
+                save(prefix + ".s_colT", sc);
+            }
+        } else if (op == "gemm") {
+            int pass;
+            long M, N, K, ldc;
+            std::string dt, aq, as, bq, bs, cout;
+            ls >> pass >> M >> N >> K >> dt >> ldc >> aq >> as >> bq >> bs >> cout;
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)M * K / 32);
+            Buf b = load(bq, (size_t)N * K), sb = load(bs, (size_t)N * K / 32);
+            Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * es : 0);
+            const int st = mxfp8_gemm((mxfp8_pass)pass, a.p, sa.p, b.p, sb.p, M, N, K, c.p, dtype_of(dt), ldc, nullptr);
+            unchanged(a, "a_q");
+            unchanged(sa, "a_s");
+            unchanged(b, "b_q");
+            unchanged(sb, "b_s");
+            report(st);
+            save(cout, c);
+        } else if (op == "dequantize") {
+            long rows, cols, ld;
+            std::string dt, q, s, out;
+            ls >> rows >> cols >> dt >> ld >> q >> s >> out;
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf qb = load(q, (size_t)rows * cols), sb = load(s, (size_t)rows * cols / 32);
+            Buf o = output(rows > 0 ? ((size_t)(rows - 1) * ld + cols) * es : 0);
+            const int st = mxfp8_dequantize(qb.p, sb.p, rows, cols, o.p, dtype_of(dt), ld, nullptr);
+            unchanged(qb, "q");
+            unchanged(sb, "s");
+            report(st);
+            save(out, o);
+        } else {
+            fprintf(stderr, "unknown operation %s\n", op.c_str());
+            return 2;
+        }
+    }
+    return 0;
+}

@@ -1,0 +1,102 @@
+"""CPU checks of the C ABI: the shared library loads without a GPU, exports every function that
+include/mxfp8.h declares, and its host-side validation rejects bad calls before anything is
+launched (so these calls are safe on a machine with no GPU; valid calls are made only in the GPU
+tests)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2506_08027_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2506_08027_amd.build import build_library
+        build_library()
+    return ctypes.CDLL(binding.LIB_PATH)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mxfp8.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mxfp8_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert declared_functions() == ["mxfp8_dequantize", "mxfp8_gemm", "mxfp8_quantize", "mxfp8_status_string"]
+
+
+def test_library_exports_every_declared_function(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_binding_mirrors_the_header():
+    import paper_2506_08027_amd as mx
+    for name in declared_functions():
+        if name != "mxfp8_status_string":
+            assert callable(getattr(mx, name)), name
+    assert (mx.ROWWISE, mx.COLWISE, mx.BOTH) == (1, 2, 3)
+    assert (mx.FPROP, mx.DGRAD, mx.WGRAD) == (0, 1, 2)
+
+
+def test_status_strings(lib):
+    lib.mxfp8_status_string.restype = ctypes.c_char_p
+    seen = {lib.mxfp8_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and all(seen)
+    assert lib.mxfp8_status_string(0) == b"ok"
+    assert lib.mxfp8_status_string(99)  # never NULL
+
+
+I64, P = ctypes.c_int64, ctypes.c_void_p
+FAKE = P(0x1000)          # 16-byte aligned and never dereferenced: every call below fails validation first
+
+
+def test_quantize_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_quantize
+    f.argtypes = [P, ctypes.c_int, I64, I64, I64, ctypes.c_int, P, P, P, P, P]
+    assert f(FAKE, 7, 32, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, None) == 4          # dtype
+    assert f(FAKE, 0, 32, 32, 32, 4, FAKE, FAKE, FAKE, FAKE, None) == 5          # axis
+    assert f(FAKE, 0, 33, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, None) == 2          # rows % 32
+    assert f(FAKE, 0, 32, 64, 32, 3, FAKE, FAKE, FAKE, FAKE, None) == 2          # ld < cols
+    assert f(FAKE, 0, -32, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, None) == 2
+    assert f(FAKE, 0, 1 << 32, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, None) == 2
+    assert f(None, 0, 32, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, None) == 1
+    assert f(FAKE, 0, 32, 32, 32, 2, None, None, None, FAKE, None) == 1          # colwise needs q_colT
+    assert f(P(0x1004), 0, 32, 32, 32, 1, FAKE, FAKE, None, None, None) == 3     # src alignment
+    assert f(FAKE, 1, 32, 32, 36, 1, FAKE, FAKE, None, None, None) == 3          # BF16 ld: 72 bytes
+    assert f(FAKE, 0, 0, 32, 32, 3, None, None, None, None, None) == 0           # nothing to do
+
+
+def test_gemm_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_gemm
+    f.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, ctypes.c_int, I64, P]
+    ok = (FAKE, FAKE, FAKE, FAKE)
+    assert f(3, *ok, 64, 64, 128, FAKE, 0, 64, None) == 5
+    assert f(0, *ok, 64, 64, 128, FAKE, 2, 64, None) == 4
+    assert f(0, *ok, 64, 64, 96, FAKE, 0, 64, None) == 2                         # K % 128
+    assert f(0, *ok, 64, 64, 128, FAKE, 0, 63, None) == 2                        # ldc < N
+    assert f(0, *ok, 64, 64, (1 << 24) + 128, FAKE, 0, 64, None) == 2            # K beyond the 32-bit tile offsets
+    assert f(0, *ok, (1 << 30) + 1, 64, 128, FAKE, 0, 64, None) == 2
+    assert f(0, *ok, 1 << 30, 1 << 30, 128, FAKE, 0, 1 << 30, None) == 2         # more tiles than a grid holds
+    assert f(0, None, FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, None) == 1
+    assert f(0, *ok, 64, 64, 128, None, 0, 64, None) == 1
+    assert f(0, P(0x1008), FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, None) == 3
+    assert f(0, *ok, 64, 64, 128, P(0x1002), 0, 64, None) == 3                   # FP32 c needs 4-byte alignment
+    assert f(0, *ok, 0, 64, 128, None, 0, 64, None) == 0
+
+
+def test_dequantize_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_dequantize
+    f.argtypes = [P, P, I64, I64, P, ctypes.c_int, I64, P]
+    assert f(FAKE, FAKE, 4, 48, FAKE, 0, 48, None) == 2
+    assert f(FAKE, FAKE, 4, 64, FAKE, 0, 32, None) == 2
+    assert f(FAKE, FAKE, 4, 64, FAKE, 5, 64, None) == 4
+    assert f(None, FAKE, 4, 64, FAKE, 0, 64, None) == 1
+    assert f(FAKE, FAKE, 4, 64, P(0x1008), 0, 64, None) == 3
+    assert f(FAKE, FAKE, 4, 64, FAKE, 1, 68, None) == 3                          # BF16 ld: 136 bytes
+    assert f(FAKE, FAKE, 0, 64, None, 0, 64, None) == 0

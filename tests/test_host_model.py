@@ -1,0 +1,266 @@
+"""CPU tests that run the HIP kernel sources themselves, unchanged, on a host execution model.
+
+tests/host_model/ compiles paper_2506_08027_amd/csrc/*.hip as host C++ (AddressSanitizer and
+alignment checks on) against a stand-in for the HIP runtime header that runs every workgroup as 64
+cooperative fibers per wavefront: cross-lane instructions and barriers are rendezvous points,
+direct-to-LDS loads complete only at the `s_waitcnt vmcnt` that retires them (their destination
+holds NaN-decoding poison until then), and one wavefront always runs maximally ahead of the others.
+What these tests establish before any GPU run:
+  * every global and LDS access of the kernels stays inside its buffer for ragged and multi-tile
+    shapes (the usual cause of a GPU memory fault), inputs are not modified, padding is not written;
+  * the index arithmetic, swizzles, scale handling and the wait/barrier protocol of the software
+    pipeline produce the oracle's result (bit-exact for quantize/dequantize; the modelled MFMA sums
+    in double, so the GEMM matches the oracle to FP32 rounding);
+  * the launchers pick grids and tile configurations that cover the output exactly once.
+They say nothing about speed or about the numerics of the real matrix instruction: those are the
+GPU tests' business. The instruction semantics the model relies on are the ones probed on hardware
+and documented in the kernel sources."""
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_08027_amd import synth_inputs as si
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+MODEL_DIR = os.path.join(HERE, "host_model")
+BINARY = os.path.join(MODEL_DIR, "_build", "hostmodel")
+SENTINEL = 0xA5
+
+
+@pytest.fixture(scope="session")
+def hostmodel():
+    res = subprocess.run([os.path.join(MODEL_DIR, "build.sh"), BINARY], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-4000:]
+    return BINARY
+
+
+def run_case(binary, tmp_path, lines, expect_ok=True, **env):
+    case = tmp_path / "case.txt"
+    case.write_text("\n".join(lines) + "\n")
+    res = subprocess.run([binary, str(case)], capture_output=True, text=True, timeout=600,
+                         env=dict(os.environ, **{k: str(v) for k, v in env.items()}))
+    if expect_ok:
+        assert res.returncode == 0, (res.stdout + res.stderr)[-4000:]
+    calls = []
+    for line in res.stdout.splitlines():
+        tok = line.split()
+        if tok[:1] == ["status"]:
+            calls.append((int(tok[1]), [int(t) for t in tok[3:]]))
+    return res, calls
+
+
+def put(tmp_path, name, arr):
+    path = tmp_path / name
+    np.ascontiguousarray(arr).tofile(path)
+    return str(path)
+
+
+def get(path, dtype, shape):
+    return np.fromfile(path, dtype=dtype).reshape(shape)
+
+
+# ---- quantize -------------------------------------------------------------------------------------
+def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None):
+    rows, cols = x.shape
+    ld = ld or cols
+    stored = np.zeros((rows, ld), x.dtype)
+    stored[:, :cols] = x
+    flat = stored.reshape(-1)[: (rows - 1) * ld + cols]
+    src = put(tmp_path, "x.bin", flat)
+    prefix = str(tmp_path / "out")
+    _, calls = run_case(hostmodel, tmp_path,
+                        [f"quantize {'bf16' if bf16 else 'f32'} {rows} {cols} {ld} {axis} {src} {prefix}"])
+    assert calls[0][0] == 0
+    tiles = ((rows + 127) // 128) * ((cols + 127) // 128)
+    assert calls[0][1] == list(range(tiles))
+    xin = np.ascontiguousarray(x)          # the oracle takes FP32 values or BF16 bit patterns (uint16)
+    if axis & 1:
+        q, s = oracle.quantize_rowwise(xin)
+        assert np.array_equal(get(prefix + ".q_row", np.uint8, q.shape), q)
+        assert np.array_equal(get(prefix + ".s_row", np.uint8, s.shape), s)
+    if axis & 2:
+        q, s = oracle.quantize_colwise(xin)
+        assert np.array_equal(get(prefix + ".q_colT", np.uint8, q.shape), q)
+        assert np.array_equal(get(prefix + ".s_colT", np.uint8, s.shape), s)
+
+
+@pytest.mark.parametrize("axis", [1, 2, 3])
+def test_quantize_fp32_with_every_special_block(hostmodel, tmp_path, axis):
+    _quantize_and_compare(hostmodel, tmp_path, si.tiny_with_specials(256, seed=0), False, axis)
+
+
+@pytest.mark.parametrize("axis", [1, 2, 3])
+def test_quantize_bf16_with_special_blocks(hostmodel, tmp_path, axis):
+    x = si.to_bf16_bits(si.tiny_with_specials(256, seed=1))
+    _quantize_and_compare(hostmodel, tmp_path, x, True, axis)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape,ld", [((160, 96), 128), ((32, 288), 288), ((288, 32), 40)])
+def test_quantize_ragged_tiles_and_leading_dimension(hostmodel, tmp_path, bf16, shape, ld):
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal(shape) * np.exp(rng.standard_normal(shape[1]))).astype(np.float32)
+    x[5, 3], x[40 % shape[0], 70 % shape[1]] = np.inf, np.nan
+    if bf16:
+        x = si.to_bf16_bits(x)
+        ld = (ld + 7) // 8 * 8
+    else:
+        ld = (ld + 3) // 4 * 4
+    _quantize_and_compare(hostmodel, tmp_path, x, bf16, 3, ld)
+
+
+# ---- dequantize -----------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True])
+def test_dequantize_all_codes_and_padding_untouched(hostmodel, tmp_path, bf16):
+    scales = np.array([0, 1, 100, 126, 127, 128, 200, 253, 254, 255], np.uint8)
+    q = np.tile(np.arange(256, dtype=np.uint8), (len(scales), 1))           # [10 x 256]
+    s = np.repeat(scales[:, None], 8, axis=1)
+    ld = 264
+    out = str(tmp_path / "d.bin")
+    _, calls = run_case(hostmodel, tmp_path, [
+        f"dequantize {q.shape[0]} 256 {'bf16' if bf16 else 'f32'} {ld} {put(tmp_path, 'q.bin', q)} "
+        f"{put(tmp_path, 's.bin', s)} {out}"])
+    assert calls[0][0] == 0
+    n = (q.shape[0] - 1) * ld + 256
+    ref = oracle.dequantize(q, s, "bf16" if bf16 else "f32")
+    if bf16:
+        got = np.zeros(q.shape[0] * ld, np.uint16)
+        got[:n] = np.fromfile(out, np.uint16)
+        got = got.reshape(q.shape[0], ld)
+        ref = np.asarray(ref, np.uint16)
+        pad = 0xA5A5
+    else:
+        got = np.zeros(q.shape[0] * ld, np.uint32)
+        got[:n] = np.fromfile(out, np.uint32)
+        got = got.reshape(q.shape[0], ld)
+        ref = np.asarray(ref, np.float32).view(np.uint32)
+        pad = 0xA5A5A5A5
+    val, exp = got[:, :256], ref
+    nan_exp = np.isnan(ref.view(np.float32)) if not bf16 else ((ref & 0x7FFF) > 0x7F80)
+    nan_got = np.isnan(val.view(np.float32)) if not bf16 else ((val & 0x7FFF) > 0x7F80)
+    assert np.array_equal(nan_got, nan_exp)
+    assert np.array_equal(val[~nan_exp], exp[~nan_exp])
+    assert (got[:-1, 256:] == pad).all()
+
+
+# ---- gemm -----------------------------------------------------------------------------------------
+def _operands(M, N, K, seed, spikes=False):
+    a = si.gradients(M, K, seed=seed, spikes=spikes) if spikes else si.activations(M, K, seed=seed, bf16=False)
+    b = si.weights(N, K, seed=seed + 1, bf16=False)
+    return oracle.quantize_rowwise(np.asarray(a, np.float32)) + oracle.quantize_rowwise(np.asarray(b, np.float32))
+
+
+def _gemm_case(tmp_path, M, N, K, ops, bf16=False, ldc=None, tag=""):
+    a_q, a_s, b_q, b_s = ops
+    ldc = ldc or N
+    names = [put(tmp_path, f"{n}{tag}.bin", v) for n, v in (("aq", a_q), ("as", a_s), ("bq", b_q), ("bs", b_s))]
+    out = str(tmp_path / f"c{tag}.bin")
+    return f"gemm 0 {M} {N} {K} {'bf16' if bf16 else 'f32'} {ldc} {' '.join(names)} {out}", out
+
+
+def _check_gemm(out, M, N, ldc, ops, bf16, expect_full=True):
+    """Compares whatever part of C the simulated workgroups wrote against the oracle. The modelled
+    instruction sums in double and rounds once, so the result is within one FP32 rounding of the sum
+    (2^-23 relative to sum|a b| covers it) plus, for BF16 output, one BF16 rounding of the value."""
+    a_q, a_s, b_q, b_s = ops
+    n = (M - 1) * ldc + N
+    if bf16:
+        raw = np.full(M * ldc, 0xA5A5, np.uint16)
+        raw[:n] = np.fromfile(out, np.uint16)
+        raw = raw.reshape(M, ldc)
+        written = raw[:, :N] != 0xA5A5
+        val = si.bf16_bits_to_f32(raw[:, :N])
+        pad_ok = (raw[:, N:] == 0xA5A5).all()
+    else:
+        raw = np.full(M * ldc, 0xA5A5A5A5, np.uint32)
+        raw[:n] = np.fromfile(out, np.uint32)
+        raw = raw.reshape(M, ldc)
+        written = raw[:, :N] != 0xA5A5A5A5
+        val = raw[:, :N].view(np.float32)
+        pad_ok = (raw[:, N:] == 0xA5A5A5A5).all()
+    assert pad_ok, "bytes between rows of C were written"
+    if expect_full:
+        assert written.all()
+    rows = np.unique(np.nonzero(written)[0])
+    assert rows.size
+    ref, absum = oracle.gemm_rows(a_q, a_s, b_q, b_s, rows)
+    tol = 2.0 ** -23 * absum + (2.0 ** -8 * np.abs(ref) if bf16 else 0.0) + 1e-300
+    w = written[rows]
+    err = np.abs(val[rows].astype(np.float64) - ref)
+    assert not np.isnan(val[rows][w]).any(), "NaN in C: a tile was read before its loads were waited for"
+    assert (err[w] <= tol[w]).all(), float((err[w] / tol[w]).max())
+    return int(written.sum())
+
+
+MODES = [dict(), dict(WAVESIM_DMA="eager"), dict(WAVESIM_ORDER="down"), dict(WAVESIM_DMA="eager", WAVESIM_ORDER="down")]
+
+
+@pytest.mark.parametrize("mode", MODES, ids=["lazy-up", "eager-up", "lazy-down", "eager-down"])
+def test_gemm_small_tiles_ragged(hostmodel, tmp_path, mode):
+    """128x128 configuration: 2x2 tiles, ragged in M and N, K = one, two and three steps (prologue
+    and tail prefetch clamps), FP32 and BF16 output, padded C."""
+    lines, checks = [], []
+    for i, (M, N, K, bf16, ldc) in enumerate([(200, 136, 384, False, 136), (130, 129, 128, True, 136),
+                                               (64, 200, 256, False, 204)]):
+        ops = _operands(M, N, K, seed=10 + i)
+        line, out = _gemm_case(tmp_path, M, N, K, ops, bf16, ldc, tag=str(i))
+        lines.append(line)
+        checks.append((out, M, N, ldc, ops, bf16))
+    _, calls = run_case(hostmodel, tmp_path, lines, **mode)
+    assert [c[0] for c in calls] == [0, 0, 0]
+    for c in checks:
+        _check_gemm(*c)
+
+
+@pytest.mark.parametrize("mode", [MODES[0], MODES[3]], ids=["lazy-up", "eager-down"])
+def test_gemm_large_tiles_sampled_workgroups(hostmodel, tmp_path, mode):
+    """256x256 configuration (taken when there are at least 128 such tiles): first, last (ragged in
+    both directions) and two interior workgroups of a 9 x 16 tile grid."""
+    M, N, K = 2048 + 72, 4096 - 100, 384
+    ops = _operands(M, N, K, seed=20, spikes=True)
+    line, out = _gemm_case(tmp_path, M, N, K, ops, bf16=True)
+    _, calls = run_case(hostmodel, tmp_path, [line], WAVESIM_BLOCKS=4, **mode)
+    assert calls[0] == (0, [0, 47, 95, 143])
+    n_written = _check_gemm(out, M, N, N, ops, True, expect_full=False)
+    # two interior tiles, plus the two corner tiles of the XCD-aware order, whatever their raggedness:
+    # every simulated workgroup wrote a disjoint tile
+    assert 2 * 256 * 256 < n_written <= 4 * 256 * 256
+
+
+def test_gemm_unaligned_c_takes_element_stores(hostmodel, tmp_path):
+    M, N, K = 40, 37, 128
+    ops = _operands(M, N, K, seed=30)
+    line, out = _gemm_case(tmp_path, M, N, K, ops, bf16=True, ldc=37)
+    _, calls = run_case(hostmodel, tmp_path, [line])
+    assert calls[0][0] == 0
+    _check_gemm(out, M, N, 37, ops, True)
+
+
+def test_gemm_k_zero_stores_zeros(hostmodel, tmp_path):
+    M, N = 70, 40
+    empty = np.zeros((0,), np.uint8)
+    line, out = _gemm_case(tmp_path, M, N, 0, (empty, empty, empty, empty))
+    _, calls = run_case(hostmodel, tmp_path, [line])
+    assert calls[0][0] == 0
+    assert (np.fromfile(out, np.float32) == 0).all()
+
+
+def test_model_notices_a_missing_wait(hostmodel, tmp_path):
+    """Self-test of the model: with every partial `s_waitcnt vmcnt(n > 0)` of the K loop ignored the
+    fragments are read before their tiles have landed, and the result must come out as NaN."""
+    M, N, K = 128, 128, 384
+    ops = _operands(M, N, K, seed=40)
+    line, out = _gemm_case(tmp_path, M, N, K, ops)
+    run_case(hostmodel, tmp_path, [line], WAVESIM_DROP_PARTIAL_WAITS=1)
+    assert np.isnan(np.fromfile(out, np.float32)).all()
+
+
+def test_validation_errors_reach_the_caller(hostmodel, tmp_path):
+    ops = _operands(32, 32, 128, seed=50)
+    good, _ = _gemm_case(tmp_path, 32, 32, 128, ops)
+    bad_k = good.replace("gemm 0 32 32 128 f32 32", "gemm 0 32 32 128 f32 16")      # ldc < N
+    res, calls = run_case(hostmodel, tmp_path, [bad_k], expect_ok=False)
+    assert calls and calls[0][0] == 2
