@@ -151,6 +151,39 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    def timed_ms(fn, reps=10):
+        for _ in range(3):
+            fn()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def tiled_scale_variants():
+        """Same kernels with the scale bytes in the tiled layout (MXFP8_SCALES_TILED), timed outside the
+        step: reported next to the headline numbers, which stay on the row-major entry points."""
+        lay = mx.SCALES_TILED
+
+        def tbufs(r, c):
+            return dict(q_row=torch.empty((r, c), **u8), s_row=torch.empty(mx.mxfp8_scale_bytes(r, c, lay), **u8),
+                        q_colT=torch.empty((c, r), **u8), s_colT=torch.empty(mx.mxfp8_scale_bytes(c, r, lay), **u8))
+        Xt, Wt, dYt = tbufs(T, H), tbufs(O, H), tbufs(T, O)
+        q_x = timed_ms(lambda: mx.mxfp8_quantize_ex(X, mx.BOTH, **Xt, scale_layout=lay))
+        mx.mxfp8_quantize_ex(W, mx.BOTH, **Wt, scale_layout=lay)
+        q_dy = timed_ms(lambda: mx.mxfp8_quantize_ex(dY, mx.BOTH, **dYt, scale_layout=lay))
+        g = timed_ms(lambda: mx.mxfp8_gemm_ex(mx.FPROP, Xt["q_row"], Xt["s_row"], Wt["q_row"], Wt["s_row"], Y, lay))
+        return {"fprop_tflops": 2.0 * T * H * O / (g * 1e-3) / 1e12, "fprop_ms": g,
+                "quantize_x_bf16_both_gbs": T * H * 4.0625 / (q_x * 1e-3) / 1e9, "quantize_x_ms": q_x,
+                "quantize_dy_f32_both_gbs": T * O * 6.0625 / (q_dy * 1e-3) / 1e9, "quantize_dy_ms": q_dy}
+
+    try:
+        tiled = tiled_scale_variants()
+    except Exception as exc:  # the headline measurement above must survive a problem in the extra one
+        tiled = {"error": repr(exc)}
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -185,6 +218,7 @@ def main():
                               "frac": quant_gbs / HBM_PEAK_GBS, "traffic": traffic_from_profile("quantize X BF16"),
                               "kernel": "quantize_kernel<BF16, row+col> (X 8192x4096)", "avg_ms": quant_ms},
     }
+    out["tiled_scale_layout"] = tiled
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

@@ -46,13 +46,31 @@ typedef enum {
     MXFP8_ERR_SHAPE = 2, /* negative dimension, axis not a multiple of 32, ld too small */
     MXFP8_ERR_ALIGN = 3, /* pointer or leading dimension not aligned as documented */
     MXFP8_ERR_DTYPE = 4, /* unknown mxfp8_dtype */
-    MXFP8_ERR_MODE = 5,  /* unknown mxfp8_axis / mxfp8_pass */
+    MXFP8_ERR_MODE = 5,  /* unknown mxfp8_axis / mxfp8_pass / mxfp8_scale_layout */
     MXFP8_ERR_HIP = 6    /* kernel launch rejected by the HIP runtime, or not a gfx950 device */
 } mxfp8_status;
 
 typedef enum { MXFP8_F32 = 0, MXFP8_BF16 = 1 } mxfp8_dtype;
 typedef enum { MXFP8_ROWWISE = 1, MXFP8_COLWISE = 2, MXFP8_BOTH = 3 } mxfp8_axis;
 typedef enum { MXFP8_FPROP = 0, MXFP8_DGRAD = 1, MXFP8_WGRAD = 2 } mxfp8_pass;
+
+/*
+ * How the scale bytes of a quantized [rows x cols] operand (nb = cols/32 blocks per row) are stored.
+ * The paper fixes the values, not their place in memory; both layouts hold the same bytes.
+ *   MXFP8_SCALES_ROWMAJOR  s[r * nb + b]: dense [rows x nb]. What the plain entry points use.
+ *   MXFP8_SCALES_TILED     s[((r/64 * ceil(nb/4) + b/4) * 64 + r%64) * 4 + b%4]: the four scale bytes
+ *                          that one 128-wide K step of the GEMM needs for a row form a dword, and the
+ *                          dwords of 64 consecutive rows are contiguous (256 bytes), so both the
+ *                          quantizer's scale stores and the GEMM's scale loads move whole cache lines
+ *                          instead of 4 bytes per line. The buffer holds ceil(rows/64) * ceil(nb/4)
+ *                          * 256 bytes (mxfp8_scale_bytes); bytes that belong to rows >= rows or
+ *                          blocks >= nb are unspecified filler. Must be 16-byte aligned.
+ */
+typedef enum { MXFP8_SCALES_ROWMAJOR = 0, MXFP8_SCALES_TILED = 1 } mxfp8_scale_layout;
+
+/* Size in bytes of the scale buffer of a [rows x cols] operand in `layout` (host arithmetic only);
+ * -1 for negative sizes, cols not a multiple of 32 or an unknown layout. */
+int64_t mxfp8_scale_bytes(int64_t rows, int64_t cols, mxfp8_scale_layout layout);
 
 /*
  * Convert src [rows x cols] (FP32 or BF16, leading dimension ld_src >= cols) to MXFP8-E4M3.
@@ -77,6 +95,14 @@ typedef enum { MXFP8_FPROP = 0, MXFP8_DGRAD = 1, MXFP8_WGRAD = 2 } mxfp8_pass;
 mxfp8_status mxfp8_quantize(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
                             int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
                             uint8_t *q_colT, uint8_t *s_colT, void *hip_stream);
+
+/* mxfp8_quantize with the scale bytes of both copies stored in `scale_layout` (s_row describes the
+ * [rows x cols] operand, s_colT the transposed [cols x rows] one). Same values, same requirements;
+ * tiled scale buffers must be 16-byte aligned and sized by mxfp8_scale_bytes. */
+mxfp8_status mxfp8_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                               int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
+                               uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout,
+                               void *hip_stream);
 
 /*
  * C [M x N] = A [M x K] * B [N x K]^T with per-block scales (Section 2, Appendix A.3):
@@ -104,6 +130,12 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
                         const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
                         void *c, mxfp8_dtype c_dtype, int64_t ldc, void *hip_stream);
 
+/* mxfp8_gemm with a_s and b_s both stored in `scale_layout` (Section 2, Appendix A.3: same sum). */
+mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
+                           const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
+                           void *c, mxfp8_dtype c_dtype, int64_t ldc, mxfp8_scale_layout scale_layout,
+                           void *hip_stream);
+
 /*
  * Decode q [rows x cols], s [rows x cols/32] (dense, blocks along a row) to
  * dst[r, c] = E4M3(q[r, c]) * 2^(s[r, c/32] - 127) (Section 2), FP32 or BF16, leading dimension
@@ -114,6 +146,11 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
  */
 mxfp8_status mxfp8_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
                               void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst, void *hip_stream);
+
+/* mxfp8_dequantize with s stored in `scale_layout` (Section 2). */
+mxfp8_status mxfp8_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
+                                 void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst,
+                                 mxfp8_scale_layout scale_layout, void *hip_stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp8_status_string(mxfp8_status status);

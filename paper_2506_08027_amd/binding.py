@@ -19,6 +19,7 @@ OK = 0
 F32, BF16 = 0, 1
 ROWWISE, COLWISE, BOTH = 1, 2, 3
 FPROP, DGRAD, WGRAD = 0, 1, 2
+SCALES_ROWMAJOR, SCALES_TILED = 0, 1
 K_BLOCK = 32
 
 _AXIS = {"rowwise": ROWWISE, "colwise": COLWISE, "both": BOTH, ROWWISE: ROWWISE, COLWISE: COLWISE, BOTH: BOTH}
@@ -49,6 +50,14 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_gemm.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, vp]
     lib.mxfp8_dequantize.restype = ci
     lib.mxfp8_dequantize.argtypes = [vp, vp, i64, i64, vp, ci, i64, vp]
+    lib.mxfp8_quantize_ex.restype = ci
+    lib.mxfp8_quantize_ex.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, vp, ci, vp]
+    lib.mxfp8_gemm_ex.restype = ci
+    lib.mxfp8_gemm_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, ci, vp]
+    lib.mxfp8_dequantize_ex.restype = ci
+    lib.mxfp8_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
+    lib.mxfp8_scale_bytes.restype = i64
+    lib.mxfp8_scale_bytes.argtypes = [i64, i64, ci]
     lib.mxfp8_status_string.restype = ctypes.c_char_p
     lib.mxfp8_status_string.argtypes = [ci]
     _lib = lib
@@ -85,81 +94,131 @@ def _need_cuda(*tensors):
 
 # ---- raw entry points: same names and argument order as include/mxfp8.h -----------------------
 
+def mxfp8_scale_bytes(rows: int, cols: int, scale_layout: int = SCALES_ROWMAJOR) -> int:
+    """Bytes of the scale buffer of a [rows x cols] operand (host arithmetic in the library)."""
+    n = load().mxfp8_scale_bytes(rows, cols, scale_layout)
+    if n < 0:
+        raise ValueError("bad shape or layout")
+    return n
+
+
+def _check_scales(s, rows, cols, scale_layout, what):
+    if s.dtype != torch.uint8 or not s.is_contiguous():
+        raise ValueError(f"{what} must be dense uint8")
+    if scale_layout == SCALES_ROWMAJOR:
+        if tuple(s.shape) != (rows, cols // K_BLOCK):
+            raise ValueError(f"{what} must be [{rows} x {cols // K_BLOCK}]")
+    elif s.numel() < mxfp8_scale_bytes(rows, cols, scale_layout):
+        raise ValueError(f"{what} holds {s.numel()} bytes, the tiled layout needs "
+                         f"{mxfp8_scale_bytes(rows, cols, scale_layout)}")
+
+
 def mxfp8_quantize(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=None, stream=None) -> None:
     """src [rows x cols] float32/bfloat16 (row stride = leading dimension) -> the selected copies."""
+    mxfp8_quantize_ex(src, axis, q_row, s_row, q_colT, s_colT, SCALES_ROWMAJOR, stream)
+
+
+def mxfp8_quantize_ex(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=None,
+                      scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """mxfp8_quantize with the scale bytes stored in `scale_layout` (tiled buffers: flat uint8 of
+    mxfp8_scale_bytes(rows, cols) / mxfp8_scale_bytes(cols, rows) bytes)."""
     _need_cuda(src, q_row, s_row, q_colT, s_colT)
     if src.dim() != 2 or (src.numel() and src.stride(1) != 1):
         raise ValueError("src must be 2-D with contiguous rows")
     rows, cols = src.shape
     ld = src.stride(0) if rows > 1 else max(cols, 1)
-    rc = load().mxfp8_quantize(_ptr(src), _dtype_code(src.dtype), rows, cols, ld, _AXIS[axis],
-                               _ptr(q_row), _ptr(s_row), _ptr(q_colT), _ptr(s_colT), _stream(stream))
+    if scale_layout != SCALES_ROWMAJOR:   # the library cannot see buffer sizes: check them here
+        if s_row is not None and _AXIS[axis] & ROWWISE:
+            _check_scales(s_row, rows, cols, scale_layout, "s_row")
+        if s_colT is not None and _AXIS[axis] & COLWISE:
+            _check_scales(s_colT, cols, rows, scale_layout, "s_colT")
+    rc = load().mxfp8_quantize_ex(_ptr(src), _dtype_code(src.dtype), rows, cols, ld, _AXIS[axis],
+                                  _ptr(q_row), _ptr(s_row), _ptr(q_colT), _ptr(s_colT), scale_layout,
+                                  _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_quantize")
 
 
 def mxfp8_gemm(pass_, a_q, a_s, b_q, b_s, c, stream=None) -> None:
     """c [M x N] (float32/bfloat16) = A [M x K] . B [N x K]^T with block scales [. x K/32]."""
+    mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, SCALES_ROWMAJOR, stream)
+
+
+def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """mxfp8_gemm with both scale operands stored in `scale_layout`."""
     _need_cuda(a_q, a_s, b_q, b_s, c)
     M, K = a_q.shape
     N, Kb = b_q.shape
-    if K != Kb or tuple(a_s.shape) != (M, K // K_BLOCK) or tuple(b_s.shape) != (N, K // K_BLOCK):
+    if K != Kb:
         raise ValueError("operand shapes disagree")
+    _check_scales(a_s, M, K, scale_layout, "a_s")
+    _check_scales(b_s, N, K, scale_layout, "b_s")
     if tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
         raise ValueError("c must be [M x N] with contiguous rows")
     for t in (a_q, a_s, b_q, b_s):
         if not t.is_contiguous() or t.dtype != torch.uint8:
             raise ValueError("quantized operands must be dense uint8")
     ldc = c.stride(0) if M > 1 else max(N, 1)
-    rc = load().mxfp8_gemm(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c),
-                           _dtype_code(c.dtype), ldc, _stream(stream))
+    rc = load().mxfp8_gemm_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c),
+                              _dtype_code(c.dtype), ldc, scale_layout, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_gemm")
 
 
 def mxfp8_dequantize(q, s, dst, stream=None) -> None:
     """dst [rows x cols] (float32/bfloat16) = E4M3(q) * 2^(s - 127), blocks along a row."""
+    mxfp8_dequantize_ex(q, s, dst, SCALES_ROWMAJOR, stream)
+
+
+def mxfp8_dequantize_ex(q, s, dst, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """mxfp8_dequantize with s stored in `scale_layout`."""
     _need_cuda(q, s, dst)
     rows, cols = q.shape
-    if tuple(s.shape) != (rows, cols // K_BLOCK) or tuple(dst.shape) != (rows, cols):
+    if tuple(dst.shape) != (rows, cols):
         raise ValueError("shapes disagree")
-    if not q.is_contiguous() or not s.is_contiguous() or q.dtype != torch.uint8 or s.dtype != torch.uint8:
-        raise ValueError("q and s must be dense uint8")
+    _check_scales(s, rows, cols, scale_layout, "s")
+    if not q.is_contiguous() or q.dtype != torch.uint8:
+        raise ValueError("q must be dense uint8")
     if dst.numel() and dst.stride(1) != 1:
         raise ValueError("dst rows must be contiguous")
     ld = dst.stride(0) if rows > 1 else max(cols, 1)
-    rc = load().mxfp8_dequantize(_ptr(q), _ptr(s), rows, cols, _ptr(dst), _dtype_code(dst.dtype), ld,
-                                 _stream(stream))
+    rc = load().mxfp8_dequantize_ex(_ptr(q), _ptr(s), rows, cols, _ptr(dst), _dtype_code(dst.dtype), ld,
+                                    scale_layout, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_dequantize")
 
 
 # ---- conveniences that only allocate the outputs ----------------------------------------------
 
-def quantize(src, axis="both"):
-    """Allocate outputs and call mxfp8_quantize. Returns a dict with the selected copies:
-    'q_row' [R x C], 's_row' [R x C/32], 'q_colT' [C x R], 's_colT' [C x R/32] (uint8)."""
+def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR):
+    """Allocate outputs and call mxfp8_quantize_ex. Returns a dict with the selected copies:
+    'q_row' [R x C], 's_row' [R x C/32], 'q_colT' [C x R], 's_colT' [C x R/32] (uint8); with
+    tiled scales 's_row' and 's_colT' are flat buffers of mxfp8_scale_bytes bytes."""
     rows, cols = src.shape
     ax = _AXIS[axis]
     out = {}
     u8 = dict(dtype=torch.uint8, device=src.device)
+    tiled = scale_layout != SCALES_ROWMAJOR
     if ax & ROWWISE:
         out["q_row"] = torch.empty((rows, cols), **u8)
-        out["s_row"] = torch.empty((rows, cols // K_BLOCK), **u8)
+        out["s_row"] = torch.empty((mxfp8_scale_bytes(rows, cols, scale_layout),) if tiled
+                                   else (rows, cols // K_BLOCK), **u8)
     if ax & COLWISE:
         out["q_colT"] = torch.empty((cols, rows), **u8)
-        out["s_colT"] = torch.empty((cols, rows // K_BLOCK), **u8)
-    mxfp8_quantize(src, ax, out.get("q_row"), out.get("s_row"), out.get("q_colT"), out.get("s_colT"))
+        out["s_colT"] = torch.empty((mxfp8_scale_bytes(cols, rows, scale_layout),) if tiled
+                                    else (cols, rows // K_BLOCK), **u8)
+    mxfp8_quantize_ex(src, ax, out.get("q_row"), out.get("s_row"), out.get("q_colT"), out.get("s_colT"),
+                      scale_layout)
     return out
 
 
-def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32):
+def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):
     c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
-    mxfp8_gemm(pass_, a_q, a_s, b_q, b_s, c)
+    mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout)
     return c
 
 
-def dequantize(q, s, out_dtype=torch.float32):
+def dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):
     dst = torch.empty(tuple(q.shape), dtype=out_dtype, device=q.device)
-    mxfp8_dequantize(q, s, dst)
+    mxfp8_dequantize_ex(q, s, dst, scale_layout)
     return dst

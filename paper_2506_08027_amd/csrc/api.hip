@@ -6,17 +6,19 @@
 
 namespace mxfp8 {
 hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
-                           uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                           uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales,
                            hipStream_t stream);
 hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
-                             bool bf16, int64_t ld, hipStream_t stream);
+                             bool bf16, bool tiled_scales, int64_t ld, hipStream_t stream);
 hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
-                       int64_t N, int64_t K, void *c, bool c_bf16, int64_t ldc, hipStream_t stream);
+                       int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                       hipStream_t stream);
 }  // namespace mxfp8
 
 namespace {
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == MXFP8_F32 || d == MXFP8_BF16; }
+inline bool valid_layout(int l) { return l == MXFP8_SCALES_ROWMAJOR || l == MXFP8_SCALES_TILED; }
 inline int64_t esize(int d) { return d == MXFP8_BF16 ? 2 : 4; }
 constexpr int64_t kMaxDim = 0x7FFFFFFF;  // kernels index rows and columns with 32-bit tile math
 // GEMM: tile origins (multiples of up to 256 past M or N) stay in 32 bits, a lane's byte offset inside
@@ -27,12 +29,31 @@ constexpr int64_t kMaxGemmMN = int64_t(1) << 30, kMaxGemmK = int64_t(1) << 24;
 
 extern "C" {
 
+int64_t mxfp8_scale_bytes(int64_t rows, int64_t cols, mxfp8_scale_layout layout)
+{
+    if (rows < 0 || cols < 0 || cols % 32 || !valid_layout(layout))
+        return -1;
+    const int64_t nb = cols / 32;
+    return layout == MXFP8_SCALES_TILED ? ((rows + 63) / 64) * ((nb + 3) / 4) * 256 : rows * nb;
+}
+
 mxfp8_status mxfp8_quantize(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
                             int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
                             uint8_t *q_colT, uint8_t *s_colT, void *hip_stream)
 {
+    return mxfp8_quantize_ex(src, src_dtype, rows, cols, ld_src, axis, q_row, s_row, q_colT, s_colT,
+                             MXFP8_SCALES_ROWMAJOR, hip_stream);
+}
+
+mxfp8_status mxfp8_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                               int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
+                               uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout,
+                               void *hip_stream)
+{
     if (!valid_dtype(src_dtype))
         return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout))
+        return MXFP8_ERR_MODE;
     if (axis != MXFP8_ROWWISE && axis != MXFP8_COLWISE && axis != MXFP8_BOTH)
         return MXFP8_ERR_MODE;
     if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || rows % 32 || cols % 32 || ld_src < cols)
@@ -45,8 +66,11 @@ mxfp8_status mxfp8_quantize(const void *src, mxfp8_dtype src_dtype, int64_t rows
     if (!aligned16(src) || (ld_src * esize(src_dtype)) % 16 || (want_row && !aligned16(q_row)) ||
         (want_col && !aligned16(q_colT)))
         return MXFP8_ERR_ALIGN;
+    const bool tiled = scale_layout == MXFP8_SCALES_TILED;  // tiled scales are written as dwords
+    if (tiled && ((want_row && !aligned16(s_row)) || (want_col && !aligned16(s_colT))))
+        return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_quantize(src, src_dtype == MXFP8_BF16, rows, cols, ld_src, (int)axis,
-                                                q_row, s_row, q_colT, s_colT,
+                                                q_row, s_row, q_colT, s_colT, tiled,
                                                 static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
@@ -55,8 +79,17 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
                         const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c, mxfp8_dtype c_dtype,
                         int64_t ldc, void *hip_stream)
 {
+    return mxfp8_gemm_ex(pass, a_q, a_s, b_q, b_s, M, N, K, c, c_dtype, ldc, MXFP8_SCALES_ROWMAJOR, hip_stream);
+}
+
+mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
+                           const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c, mxfp8_dtype c_dtype,
+                           int64_t ldc, mxfp8_scale_layout scale_layout, void *hip_stream)
+{
     if (!valid_dtype(c_dtype))
         return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout))
+        return MXFP8_ERR_MODE;
     if (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD)
         return MXFP8_ERR_MODE;
     if (M < 0 || N < 0 || K < 0 || M > kMaxGemmMN || N > kMaxGemmMN || K > kMaxGemmK || K % 128 || ldc < N ||
@@ -69,7 +102,8 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
     if (reinterpret_cast<uintptr_t>(c) % esize(c_dtype) ||
         (K > 0 && (!aligned16(a_q) || !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))))
         return MXFP8_ERR_ALIGN;
-    const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16, ldc,
+    const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16,
+                                            scale_layout == MXFP8_SCALES_TILED, ldc,
                                             static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
@@ -77,8 +111,17 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
 mxfp8_status mxfp8_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
                               mxfp8_dtype dst_dtype, int64_t ld_dst, void *hip_stream)
 {
+    return mxfp8_dequantize_ex(q, s, rows, cols, dst, dst_dtype, ld_dst, MXFP8_SCALES_ROWMAJOR, hip_stream);
+}
+
+mxfp8_status mxfp8_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
+                                 mxfp8_dtype dst_dtype, int64_t ld_dst, mxfp8_scale_layout scale_layout,
+                                 void *hip_stream)
+{
     if (!valid_dtype(dst_dtype))
         return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout))
+        return MXFP8_ERR_MODE;
     if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || cols % 32 || ld_dst < cols)
         return MXFP8_ERR_SHAPE;
     if (rows == 0 || cols == 0)
@@ -87,7 +130,8 @@ mxfp8_status mxfp8_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, 
         return MXFP8_ERR_NULL;
     if (!aligned16(q) || !aligned16(dst) || (ld_dst * esize(dst_dtype)) % 16)
         return MXFP8_ERR_ALIGN;
-    const hipError_t e = mxfp8::launch_dequantize(q, s, rows, cols, dst, dst_dtype == MXFP8_BF16, ld_dst,
+    const hipError_t e = mxfp8::launch_dequantize(q, s, rows, cols, dst, dst_dtype == MXFP8_BF16,
+                                                  scale_layout == MXFP8_SCALES_TILED, ld_dst,
                                                   static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
@@ -100,7 +144,7 @@ const char *mxfp8_status_string(mxfp8_status status)
     case MXFP8_ERR_SHAPE: return "bad shape: negative, not a multiple of the block size, or leading dimension too small";
     case MXFP8_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
     case MXFP8_ERR_DTYPE: return "unknown element type";
-    case MXFP8_ERR_MODE: return "unknown axis or pass";
+    case MXFP8_ERR_MODE: return "unknown axis, pass or scale layout";
     case MXFP8_ERR_HIP: return "HIP launch failed (is this a gfx950 device?)";
     }
     return "unknown status";

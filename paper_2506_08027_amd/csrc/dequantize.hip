@@ -26,7 +26,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
-template <bool BF16>
+template <bool BF16, bool TILED>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restrict__ q,
                                                          const uint8_t *__restrict__ s, int64_t rows,
                                                          int64_t cols, uint8_t *__restrict__ dst,
@@ -40,7 +40,13 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restri
          t += (int64_t)gridDim.x * blockDim.x) {
         const int64_t r = t / per_row;
         const int64_t c = (t - r * per_row) * EPT;
-        const uint32_t sb = s[r * nb + c / kBlock];
+        uint32_t sb;
+        if constexpr (TILED) {  // byte of (row r, block b): ((r/64 * ceil(nb/4) + b/4) * 64 + r%64) * 4 + b%4
+            const int64_t b = c / kBlock;
+            sb = s[(((r >> 6) * ((nb + 3) / 4) + (b >> 2)) * 64 + (r & 63)) * 4 + (b & 3)];
+        } else {
+            sb = s[r * nb + c / kBlock];
+        }
         const int e = (int)sb - 127;
         const float nanv = __uint_as_float(0x7FC00000u);
         if constexpr (BF16) {
@@ -68,20 +74,28 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restri
     }
 }
 
-hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
-                             bool bf16, int64_t ld, hipStream_t stream)
+template <bool TILED>
+static hipError_t launch_dequantize_t(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
+                                      bool bf16, int64_t ld, hipStream_t stream)
 {
     const int64_t total = rows * (cols / (bf16 ? 8 : 4));
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 64)
         blocks = 256 * 64;  // grid-stride beyond 64 workgroups per compute unit
     if (bf16)
-        hipLaunchKernelGGL(dequantize_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, q, s, rows,
+        hipLaunchKernelGGL((dequantize_kernel<true, TILED>), dim3((unsigned)blocks), dim3(256), 0, stream, q, s, rows,
                            cols, static_cast<uint8_t *>(dst), ld * 2);
     else
-        hipLaunchKernelGGL(dequantize_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, q, s, rows,
+        hipLaunchKernelGGL((dequantize_kernel<false, TILED>), dim3((unsigned)blocks), dim3(256), 0, stream, q, s, rows,
                            cols, static_cast<uint8_t *>(dst), ld * 4);
     return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
+                             bool bf16, bool tiled_scales, int64_t ld, hipStream_t stream)
+{
+    return tiled_scales ? launch_dequantize_t<true>(q, s, rows, cols, dst, bf16, ld, stream)
+                        : launch_dequantize_t<false>(q, s, rows, cols, dst, bf16, ld, stream);
 }
 
 }  // namespace mxfp8

@@ -74,7 +74,7 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
 
 // The kernel. LDS holds two A buffers, two B buffers and their scale dwords; the software pipeline
 // is described at the step lambda below.
-template <class Cfg, bool OUT_BF16>
+template <class Cfg, bool OUT_BF16, bool TILED>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
@@ -120,6 +120,18 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         bs_goff[i] = (uint32_t)min(((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 64 + lane, N - 1 - n0) * (uint32_t)nkb;
     const uint8_t *a_tile = a_q + (int64_t)m0 * K, *b_tile = b_q + (int64_t)n0 * K;
     const uint8_t *as_tile = a_s + (int64_t)m0 * nkb, *bs_tile = b_s + (int64_t)n0 * nkb;
+    // Tiled scales: the 64 dwords of a (64-row group, K step) are contiguous, so the instruction that
+    // reads one cache line per lane from row-major scales reads 256 consecutive bytes here. A ragged
+    // last tile re-reads the last valid group: its rows are never stored.
+    const uint8_t *as_grp[Cfg::SA_LOADS], *bs_grp[Cfg::SB_LOADS];
+    if constexpr (TILED) {
+#pragma unroll
+        for (int i = 0; i < Cfg::SA_LOADS; ++i)
+            as_grp[i] = a_s + (int64_t)min(m0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BM / 64), (M + 63) / 64 - 1) * KT * 256;
+#pragma unroll
+        for (int i = 0; i < Cfg::SB_LOADS; ++i)
+            bs_grp[i] = b_s + (int64_t)min(n0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BN / 64), (N + 63) / 64 - 1) * KT * 256;
+    }
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
 
     // DMA slot t (compile-time after unrolling) of the A / B loads of K step kt into buffer buf
@@ -131,8 +143,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
             const int i = t - Cfg::A_LOADS;
             // every wavefront issues the same number of requests (the wait counts rely on it):
             // with fewer 64-row groups than wavefronts some groups are simply fetched twice
-            dma_load<4>(as_tile + kt * 4, as_goff[i],
-                        lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);
+            if constexpr (TILED)
+                dma_load<4>(as_grp[i] + (int64_t)kt * 256, lane * 4,
+                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);
+            else
+                dma_load<4>(as_tile + kt * 4, as_goff[i],
+                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);
         }
     };
     auto issue_b = [&](int t, int kt, int buf) __attribute__((always_inline)) {
@@ -141,8 +157,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
                          lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
         } else if (t < Cfg::NB) {
             const int i = t - Cfg::B_LOADS;
-            dma_load<4>(bs_tile + kt * 4, bs_goff[i],
-                        lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 256);
+            if constexpr (TILED)
+                dma_load<4>(bs_grp[i] + (int64_t)kt * 256, lane * 4,
+                            lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 256);
+            else
+                dma_load<4>(bs_tile + kt * 4, bs_goff[i],
+                            lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 256);
         }
     };
 
@@ -297,12 +317,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     }
 }
 
-template <class Cfg, bool OUT_BF16>
+template <class Cfg, bool OUT_BF16, bool TILED>
 static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
                              int M, int N, int K, void *c, int64_t ldc, hipStream_t stream)
 {
     const int tiles_m = (M + Cfg::BM - 1) / Cfg::BM, tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
-    auto kern = gemm_kernel<Cfg, OUT_BF16>;
+    auto kern = gemm_kernel<Cfg, OUT_BF16, TILED>;
     const int64_t ldc_bytes = ldc * (OUT_BF16 ? 2 : 4);
     // 128-bit (FP32) / 64-bit (BF16) stores need every row start aligned; otherwise element stores
     const bool vec_store = (reinterpret_cast<uintptr_t>(c) % 16 == 0) && (ldc_bytes % 16 == 0);
@@ -315,18 +335,28 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
     return hipGetLastError();
 }
 
+template <class Cfg>
+static hipError_t launch_any(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int M,
+                             int N, int K, void *c, bool c_bf16, bool tiled, int64_t ldc, hipStream_t stream)
+{
+    if (tiled)
+        return c_bf16 ? launch_cfg<Cfg, true, true>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream)
+                      : launch_cfg<Cfg, false, true>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream);
+    return c_bf16 ? launch_cfg<Cfg, true, false>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream)
+                  : launch_cfg<Cfg, false, false>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream);
+}
+
 hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
-                       int64_t N, int64_t K, void *c, bool c_bf16, int64_t ldc, hipStream_t stream)
+                       int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                       hipStream_t stream)
 {
     using Big = GemmCfg<256, 256, 2, 2>;
     using Small = GemmCfg<128, 128, 2, 2>;
     // Small problems cannot fill 256 compute units with 256x256 tiles.
     const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
     if (big)
-        return c_bf16 ? launch_cfg<Big, true>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, stream)
-                      : launch_cfg<Big, false>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, stream);
-    return c_bf16 ? launch_cfg<Small, true>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, stream)
-                  : launch_cfg<Small, false>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, stream);
+        return launch_any<Big>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, stream);
+    return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, stream);
 }
 
 }  // namespace mxfp8

@@ -100,7 +100,7 @@ __device__ __forceinline__ uint32_t convert_down4(const uint4 (&x)[NROWS], int r
     return q;
 }
 
-template <bool BF16, bool ROW, bool COL>
+template <bool BF16, bool ROW, bool COL, bool TILED>
 __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     const uint8_t *__restrict__ src, int64_t rows, int64_t cols, int64_t ld_bytes,
     uint8_t *__restrict__ q_row, uint8_t *__restrict__ s_row, uint8_t *__restrict__ q_colT,
@@ -262,14 +262,22 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
             const int64_t r = wg_row0 + tid;
             if (r < rows) {
                 const uint32_t w = *reinterpret_cast<const uint32_t *>(lds_rs + tid * 4);
-                uint8_t *sp = s_row + r * nb_row + wg_col0 / kBlock;
-                if (wg_col0 + kTile <= cols && (nb_row & 3) == 0 && (reinterpret_cast<uintptr_t>(s_row) & 3) == 0) {
-                    *reinterpret_cast<uint32_t *>(sp) = w;
+                if constexpr (TILED) {
+                    // tiled scales: the dwords of 64 consecutive rows and one group of 4 blocks are
+                    // contiguous, so the 64 lanes write 256 consecutive bytes (blocks past `cols`
+                    // carry filler that nobody reads)
+                    const int64_t kt_row = (nb_row + 3) / 4;
+                    *reinterpret_cast<uint32_t *>(s_row + (((r >> 6) * kt_row + tile_x) * 64 + (r & 63)) * 4) = w;
                 } else {
+                    uint8_t *sp = s_row + r * nb_row + wg_col0 / kBlock;
+                    if (wg_col0 + kTile <= cols && (nb_row & 3) == 0 && (reinterpret_cast<uintptr_t>(s_row) & 3) == 0) {
+                        *reinterpret_cast<uint32_t *>(sp) = w;
+                    } else {
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        if (wg_col0 + b * kBlock < cols)
-                            sp[b] = (uint8_t)(w >> (8 * b));
+                        for (int b = 0; b < 4; ++b)
+                            if (wg_col0 + b * kBlock < cols)
+                                sp[b] = (uint8_t)(w >> (8 * b));
+                    }
                 }
             }
         }
@@ -291,21 +299,26 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
             const int64_t c = wg_col0 + col;
             if (c < cols) {
                 const uint32_t w = *reinterpret_cast<const uint32_t *>(lds_cs + col * 4);
-                uint8_t *sp = s_colT + c * nb_col + wg_row0 / kBlock;
-                if (wg_row0 + kTile <= rows && (nb_col & 3) == 0 && (reinterpret_cast<uintptr_t>(s_colT) & 3) == 0) {
-                    *reinterpret_cast<uint32_t *>(sp) = w;
+                if constexpr (TILED) {
+                    const int64_t kt_col = (nb_col + 3) / 4;
+                    *reinterpret_cast<uint32_t *>(s_colT + (((c >> 6) * kt_col + tile_y) * 64 + (c & 63)) * 4) = w;
                 } else {
+                    uint8_t *sp = s_colT + c * nb_col + wg_row0 / kBlock;
+                    if (wg_row0 + kTile <= rows && (nb_col & 3) == 0 && (reinterpret_cast<uintptr_t>(s_colT) & 3) == 0) {
+                        *reinterpret_cast<uint32_t *>(sp) = w;
+                    } else {
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        if (wg_row0 + b * kBlock < rows)
-                            sp[b] = (uint8_t)(w >> (8 * b));
+                        for (int b = 0; b < 4; ++b)
+                            if (wg_row0 + b * kBlock < rows)
+                                sp[b] = (uint8_t)(w >> (8 * b));
+                    }
                 }
             }
         }
     }
 }
 
-template <bool BF16>
+template <bool BF16, bool TILED>
 static hipError_t launch_quantize_t(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis,
                                     uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
                                     hipStream_t stream)
@@ -319,23 +332,26 @@ static hipError_t launch_quantize_t(const void *src, int64_t rows, int64_t cols,
     const uint8_t *s = static_cast<const uint8_t *>(src);
     const int64_t ldb = ld * (BF16 ? 2 : 4);
     if (axis == 1)
-        hipLaunchKernelGGL((quantize_kernel<BF16, true, false>), grid, block, 0, stream, s, rows, cols, ldb,
+        hipLaunchKernelGGL((quantize_kernel<BF16, true, false, TILED>), grid, block, 0, stream, s, rows, cols, ldb,
                            q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x);
     else if (axis == 2)
-        hipLaunchKernelGGL((quantize_kernel<BF16, false, true>), grid, block, 0, stream, s, rows, cols, ldb,
+        hipLaunchKernelGGL((quantize_kernel<BF16, false, true, TILED>), grid, block, 0, stream, s, rows, cols, ldb,
                            q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x);
     else
-        hipLaunchKernelGGL((quantize_kernel<BF16, true, true>), grid, block, 0, stream, s, rows, cols, ldb,
+        hipLaunchKernelGGL((quantize_kernel<BF16, true, true, TILED>), grid, block, 0, stream, s, rows, cols, ldb,
                            q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
-                           uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                           uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales,
                            hipStream_t stream)
 {
-    return bf16 ? launch_quantize_t<true>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream)
-                : launch_quantize_t<false>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream);
+    if (tiled_scales)
+        return bf16 ? launch_quantize_t<true, true>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream)
+                    : launch_quantize_t<false, true>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream);
+    return bf16 ? launch_quantize_t<true, false>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream)
+                : launch_quantize_t<false, false>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream);
 }
 
 }  // namespace mxfp8

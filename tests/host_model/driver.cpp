@@ -3,9 +3,10 @@
 // Every buffer is an exact-size heap block (AddressSanitizer guards its ends), outputs start out
 // filled with 0xA5, and inputs are checked to be unchanged after the call.
 //
-//   quantize   <f32|bf16> <rows> <cols> <ld> <axis 1|2|3> <src.bin> <out-prefix>
-//   gemm       <pass 0|1|2> <M> <N> <K> <f32|bf16> <ldc> <a_q> <a_s> <b_q> <b_s> <c.bin>
-//   dequantize <rows> <cols> <f32|bf16> <ld> <q.bin> <s.bin> <out.bin>
+//   quantize   <f32|bf16> <rows> <cols> <ld> <axis 1|2|3> <src.bin> <out-prefix> [tiled]
+//   gemm       <pass 0|1|2> <M> <N> <K> <f32|bf16> <ldc> <a_q> <a_s> <b_q> <b_s> <c.bin> [tiled]
+//   dequantize <rows> <cols> <f32|bf16> <ld> <q.bin> <s.bin> <out.bin> [tiled]
+// "tiled" selects MXFP8_SCALES_TILED for every scale buffer of the call (sizes from mxfp8_scale_bytes).
 // Each call prints "status <code> blocks <ids of the simulated workgroups...>".
 #include <cstdint>
 #include <cstdio>
@@ -105,6 +106,17 @@ mxfp8_dtype dtype_of(const std::string &s)
     exit(2);
 }
 
+mxfp8_scale_layout layout_of(std::istringstream &ls)
+{
+    std::string tok;
+    if (!(ls >> tok))
+        return MXFP8_SCALES_ROWMAJOR;
+    if (tok == "tiled")
+        return MXFP8_SCALES_TILED;
+    fprintf(stderr, "unknown trailing token %s\n", tok.c_str());
+    exit(2);
+}
+
 void report(int status)
 {
     printf("status %d blocks", status);
@@ -137,13 +149,15 @@ int main(int argc, char **argv)
             long rows, cols, ld;
             int axis;
             ls >> dt >> rows >> cols >> ld >> axis >> src >> prefix;
+            const mxfp8_scale_layout lay = layout_of(ls);
             const size_t es = dt == "bf16" ? 2 : 4;
             // the source spans (rows-1)*ld + cols elements: no padding after the last row
             Buf s = load(src, rows > 0 ? ((size_t)(rows - 1) * ld + cols) * es : 0);
             const bool r = axis & 1, c = axis & 2;
-            Buf qr = output(r ? (size_t)rows * cols : 0), sr = output(r ? (size_t)rows * cols / 32 : 0);
-            Buf qc = output(c ? (size_t)rows * cols : 0), sc = output(c ? (size_t)rows * cols / 32 : 0);
-            const int st = mxfp8_quantize(s.p, dtype_of(dt), rows, cols, ld, (mxfp8_axis)axis, qr.p, sr.p, qc.p, sc.p, nullptr);
+            Buf qr = output(r ? (size_t)rows * cols : 0), sr = output(r ? (size_t)mxfp8_scale_bytes(rows, cols, lay) : 0);
+            Buf qc = output(c ? (size_t)rows * cols : 0), sc = output(c ? (size_t)mxfp8_scale_bytes(cols, rows, lay) : 0);
+            const int st = mxfp8_quantize_ex(s.p, dtype_of(dt), rows, cols, ld, (mxfp8_axis)axis, qr.p, sr.p, qc.p, sc.p,
+                                             lay, nullptr);
             unchanged(s, "src");
             report(st);
             if (r) {
@@ -159,11 +173,12 @@ int main(int argc, char **argv)
             long M, N, K, ldc;
             std::string dt, aq, as, bq, bs, cout;
             ls >> pass >> M >> N >> K >> dt >> ldc >> aq >> as >> bq >> bs >> cout;
+            const mxfp8_scale_layout lay = layout_of(ls);
             const size_t es = dt == "bf16" ? 2 : 4;
-            Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)M * K / 32);
-            Buf b = load(bq, (size_t)N * K), sb = load(bs, (size_t)N * K / 32);
+            Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)mxfp8_scale_bytes(M, K, lay));
+            Buf b = load(bq, (size_t)N * K), sb = load(bs, (size_t)mxfp8_scale_bytes(N, K, lay));
             Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * es : 0);
-            const int st = mxfp8_gemm((mxfp8_pass)pass, a.p, sa.p, b.p, sb.p, M, N, K, c.p, dtype_of(dt), ldc, nullptr);
+            const int st = mxfp8_gemm_ex((mxfp8_pass)pass, a.p, sa.p, b.p, sb.p, M, N, K, c.p, dtype_of(dt), ldc, lay, nullptr);
             unchanged(a, "a_q");
             unchanged(sa, "a_s");
             unchanged(b, "b_q");
@@ -174,10 +189,11 @@ int main(int argc, char **argv)
             long rows, cols, ld;
             std::string dt, q, s, out;
             ls >> rows >> cols >> dt >> ld >> q >> s >> out;
+            const mxfp8_scale_layout lay = layout_of(ls);
             const size_t es = dt == "bf16" ? 2 : 4;
-            Buf qb = load(q, (size_t)rows * cols), sb = load(s, (size_t)rows * cols / 32);
+            Buf qb = load(q, (size_t)rows * cols), sb = load(s, (size_t)mxfp8_scale_bytes(rows, cols, lay));
             Buf o = output(rows > 0 ? ((size_t)(rows - 1) * ld + cols) * es : 0);
-            const int st = mxfp8_dequantize(qb.p, sb.p, rows, cols, o.p, dtype_of(dt), ld, nullptr);
+            const int st = mxfp8_dequantize_ex(qb.p, sb.p, rows, cols, o.p, dtype_of(dt), ld, lay, nullptr);
             unchanged(qb, "q");
             unchanged(sb, "s");
             report(st);

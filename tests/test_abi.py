@@ -20,6 +20,10 @@ def lib():
     return ctypes.CDLL(binding.LIB_PATH)
 
 
+I64, P = ctypes.c_int64, ctypes.c_void_p
+FAKE = P(0x1000)          # 16-byte aligned and never dereferenced: every call made with it fails validation first
+
+
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "mxfp8.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
@@ -27,7 +31,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mxfp8_dequantize", "mxfp8_gemm", "mxfp8_quantize", "mxfp8_status_string"]
+    assert declared_functions() == ["mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_gemm", "mxfp8_gemm_ex",
+                                    "mxfp8_quantize", "mxfp8_quantize_ex", "mxfp8_scale_bytes", "mxfp8_status_string"]
 
 
 def test_library_exports_every_declared_function(lib):
@@ -40,8 +45,36 @@ def test_binding_mirrors_the_header():
     for name in declared_functions():
         if name != "mxfp8_status_string":
             assert callable(getattr(mx, name)), name
+    assert callable(mx.status_string)
     assert (mx.ROWWISE, mx.COLWISE, mx.BOTH) == (1, 2, 3)
     assert (mx.FPROP, mx.DGRAD, mx.WGRAD) == (0, 1, 2)
+    assert (mx.SCALES_ROWMAJOR, mx.SCALES_TILED) == (0, 1)
+
+
+def test_scale_bytes_is_host_arithmetic(lib):
+    f = lib.mxfp8_scale_bytes
+    f.restype = ctypes.c_int64
+    f.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+    assert f(8192, 4096, 0) == 8192 * 128 and f(8192, 4096, 1) == 8192 * 128
+    assert f(100, 96, 0) == 300 and f(100, 96, 1) == 2 * 1 * 256        # 2 groups of 64 rows, 1 group of 4 blocks
+    assert f(64, 160, 1) == 1 * 2 * 256 and f(0, 128, 1) == 0
+    assert f(64, 100, 1) == -1 and f(-1, 128, 0) == -1 and f(64, 128, 2) == -1
+
+
+def test_ex_entry_points_validate_the_layout(lib):
+    q = lib.mxfp8_quantize_ex
+    q.argtypes = [P, ctypes.c_int, I64, I64, I64, ctypes.c_int, P, P, P, P, ctypes.c_int, P]
+    assert q(FAKE, 0, 32, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, 2, None) == 5
+    assert q(FAKE, 0, 32, 32, 32, 1, FAKE, P(0x1004), None, None, 1, None) == 3     # tiled scales: 16-byte aligned
+    assert q(FAKE, 0, 33, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, 1, None) == 2
+    g = lib.mxfp8_gemm_ex
+    g.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, P]
+    assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, 9, None) == 5
+    assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 96, FAKE, 0, 64, 1, None) == 2
+    d = lib.mxfp8_dequantize_ex
+    d.argtypes = [P, P, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, P]
+    assert d(FAKE, FAKE, 4, 64, FAKE, 0, 64, -1, None) == 5
+    assert d(FAKE, FAKE, 4, 48, FAKE, 0, 48, 1, None) == 2
 
 
 def test_status_strings(lib):
@@ -52,8 +85,6 @@ def test_status_strings(lib):
     assert lib.mxfp8_status_string(99)  # never NULL
 
 
-I64, P = ctypes.c_int64, ctypes.c_void_p
-FAKE = P(0x1000)          # 16-byte aligned and never dereferenced: every call below fails validation first
 
 
 def test_quantize_validation_needs_no_gpu(lib):

@@ -22,6 +22,7 @@ import numpy as np
 import pytest
 
 import oracle
+import scale_layout as sl
 from paper_2506_08027_amd import synth_inputs as si
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -63,7 +64,22 @@ def get(path, dtype, shape):
 
 
 # ---- quantize -------------------------------------------------------------------------------------
-def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None):
+def _compare_scales(path, want, tiled):
+    """Row-major: byte for byte. Tiled: every (row, block) byte at its tiled position; of the filler
+    positions only those inside a written dword may have changed (rows past the end are never written)."""
+    rows, nb = want.shape
+    if not tiled:
+        assert np.array_equal(get(path, np.uint8, want.shape), want)
+        return
+    flat = np.fromfile(path, np.uint8)
+    assert flat.size == sl.tiled_bytes(rows, nb)
+    assert np.array_equal(sl.untile(flat, rows, nb), want)
+    dwords = flat.reshape(-1, 64, 4)                                  # [group * K step][row in group][block]
+    row_of = (np.arange(dwords.shape[0]) // ((nb + 3) // 4))[:, None] * 64 + np.arange(64)[None, :]
+    assert (dwords[row_of >= rows] == SENTINEL).all(), "scale dwords of rows past the end were written"
+
+
+def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None, tiled=False):
     rows, cols = x.shape
     ld = ld or cols
     stored = np.zeros((rows, ld), x.dtype)
@@ -72,7 +88,8 @@ def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None):
     src = put(tmp_path, "x.bin", flat)
     prefix = str(tmp_path / "out")
     _, calls = run_case(hostmodel, tmp_path,
-                        [f"quantize {'bf16' if bf16 else 'f32'} {rows} {cols} {ld} {axis} {src} {prefix}"])
+                        [f"quantize {'bf16' if bf16 else 'f32'} {rows} {cols} {ld} {axis} {src} {prefix}"
+                         + (" tiled" if tiled else "")])
     assert calls[0][0] == 0
     tiles = ((rows + 127) // 128) * ((cols + 127) // 128)
     assert calls[0][1] == list(range(tiles))
@@ -80,11 +97,11 @@ def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None):
     if axis & 1:
         q, s = oracle.quantize_rowwise(xin)
         assert np.array_equal(get(prefix + ".q_row", np.uint8, q.shape), q)
-        assert np.array_equal(get(prefix + ".s_row", np.uint8, s.shape), s)
+        _compare_scales(prefix + ".s_row", s, tiled)
     if axis & 2:
         q, s = oracle.quantize_colwise(xin)
         assert np.array_equal(get(prefix + ".q_colT", np.uint8, q.shape), q)
-        assert np.array_equal(get(prefix + ".s_colT", np.uint8, s.shape), s)
+        _compare_scales(prefix + ".s_colT", s, tiled)
 
 
 @pytest.mark.parametrize("axis", [1, 2, 3])
@@ -110,6 +127,18 @@ def test_quantize_ragged_tiles_and_leading_dimension(hostmodel, tmp_path, bf16, 
     else:
         ld = (ld + 3) // 4 * 4
     _quantize_and_compare(hostmodel, tmp_path, x, bf16, 3, ld)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", [(256, 256), (160, 96), (32, 288), (288, 32)])
+def test_quantize_tiled_scales(hostmodel, tmp_path, bf16, shape):
+    """Same values, scale bytes stored in the tiled layout (both copies)."""
+    x = si.tiny_with_specials(256, seed=2)[: shape[0], : shape[1]] if shape == (256, 256) else \
+        (np.random.default_rng(9).standard_normal(shape) * 3).astype(np.float32)
+    x = np.ascontiguousarray(x)
+    if bf16:
+        x = si.to_bf16_bits(x)
+    _quantize_and_compare(hostmodel, tmp_path, x, bf16, 3, tiled=True)
 
 
 # ---- dequantize -----------------------------------------------------------------------------------
@@ -153,12 +182,15 @@ def _operands(M, N, K, seed, spikes=False):
     return oracle.quantize_rowwise(np.asarray(a, np.float32)) + oracle.quantize_rowwise(np.asarray(b, np.float32))
 
 
-def _gemm_case(tmp_path, M, N, K, ops, bf16=False, ldc=None, tag=""):
+def _gemm_case(tmp_path, M, N, K, ops, bf16=False, ldc=None, tag="", tiled=False):
     a_q, a_s, b_q, b_s = ops
     ldc = ldc or N
+    if tiled:   # filler bytes are 0xFF (a NaN scale): a kernel that read one as a scale would show it
+        a_s, b_s = sl.tile(a_s, filler=0xFF), sl.tile(b_s, filler=0xFF)
     names = [put(tmp_path, f"{n}{tag}.bin", v) for n, v in (("aq", a_q), ("as", a_s), ("bq", b_q), ("bs", b_s))]
     out = str(tmp_path / f"c{tag}.bin")
-    return f"gemm 0 {M} {N} {K} {'bf16' if bf16 else 'f32'} {ldc} {' '.join(names)} {out}", out
+    return (f"gemm 0 {M} {N} {K} {'bf16' if bf16 else 'f32'} {ldc} {' '.join(names)} {out}"
+            + (" tiled" if tiled else "")), out
 
 
 def _check_gemm(out, M, N, ldc, ops, bf16, expect_full=True):
@@ -228,6 +260,47 @@ def test_gemm_large_tiles_sampled_workgroups(hostmodel, tmp_path, mode):
     # two interior tiles, plus the two corner tiles of the XCD-aware order, whatever their raggedness:
     # every simulated workgroup wrote a disjoint tile
     assert 2 * 256 * 256 < n_written <= 4 * 256 * 256
+
+
+@pytest.mark.parametrize("mode", [MODES[0], MODES[3]], ids=["lazy-up", "eager-down"])
+def test_gemm_tiled_scales_small_tiles(hostmodel, tmp_path, mode):
+    """Tiled scale operands, 128x128 configuration, ragged shapes whose last 64-row group is partial."""
+    lines, checks = [], []
+    for i, (M, N, K, bf16, ldc) in enumerate([(200, 136, 384, False, 136), (130, 129, 128, True, 136),
+                                               (30, 250, 256, False, 252)]):
+        ops = _operands(M, N, K, seed=60 + i)
+        line, out = _gemm_case(tmp_path, M, N, K, ops, bf16, ldc, tag=str(i), tiled=True)
+        lines.append(line)
+        checks.append((out, M, N, ldc, ops, bf16))
+    _, calls = run_case(hostmodel, tmp_path, lines, **mode)
+    assert [c[0] for c in calls] == [0, 0, 0]
+    for c in checks:
+        _check_gemm(*c)
+
+
+def test_gemm_tiled_scales_large_tiles_sampled_workgroups(hostmodel, tmp_path):
+    M, N, K = 2048 + 72, 4096 - 100, 384
+    ops = _operands(M, N, K, seed=21, spikes=True)
+    line, out = _gemm_case(tmp_path, M, N, K, ops, bf16=False, tiled=True)
+    _, calls = run_case(hostmodel, tmp_path, [line], WAVESIM_BLOCKS=4)
+    assert calls[0] == (0, [0, 47, 95, 143])
+    n_written = _check_gemm(out, M, N, N, ops, False, expect_full=False)
+    assert 2 * 256 * 256 < n_written <= 4 * 256 * 256
+
+
+def test_dequantize_tiled_scales(hostmodel, tmp_path):
+    rng = np.random.default_rng(3)
+    rows, cols = 100, 96                                   # partial last group, blocks not a multiple of 4
+    q = rng.integers(0, 256, (rows, cols), dtype=np.uint8)
+    s = rng.integers(100, 150, (rows, cols // 32), dtype=np.uint8)
+    out = str(tmp_path / "d.bin")
+    _, calls = run_case(hostmodel, tmp_path, [
+        f"dequantize {rows} {cols} f32 {cols} {put(tmp_path, 'q.bin', q)} {put(tmp_path, 's.bin', sl.tile(s))} {out} tiled"])
+    assert calls[0][0] == 0
+    got = np.fromfile(out, np.float32).reshape(rows, cols)
+    want = np.asarray(oracle.dequantize(q, s, "f32"), np.float32)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(got[~np.isnan(want)], want[~np.isnan(want)])
 
 
 def test_gemm_unaligned_c_takes_element_stores(hostmodel, tmp_path):
