@@ -23,6 +23,8 @@
 // fetches the chunk that belongs at its slot.
 #include "mxfp8_device.h"
 
+#include <stdlib.h>
+
 namespace mxfp8 {
 
 constexpr int BK = 128;  // K bytes per step = 4 scale blocks = one MFMA
@@ -317,15 +319,273 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     }
 }
 
+// ---- persistent variant --------------------------------------------------------------------------
+// One workgroup per compute unit walks over several output tiles and keeps the K pipeline running
+// across tile boundaries: the prefetches of the last two K steps of a tile, which the kernel above
+// spends on re-reading the last step, fetch the first steps of the workgroup's next tile instead, so
+// only the first tile of a workgroup has a prologue, and the epilogue stores of a tile drain while
+// the operands of the next one are already in flight. Restricted to problems made of full tiles
+// (M % BM == 0, N % BN == 0: every 8B-class layer shape) with K >= 2 steps and vector-storable C;
+// without ragged tiles the DMA offsets inside a tile are the same for every tile.
+// Wait counts: the epilogue's stores also count in vmcnt. Loads complete in order among themselves,
+// so "at most n operations outstanding" still implies that all but the last n loads have landed,
+// whatever the stores do; the immediates of the K step stay valid (they can only wait longer).
+template <class Cfg, bool OUT_BF16, bool TILED>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
+    const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
+    const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
+    int tiles_m, int tiles_n)
+{
+    static_assert(Cfg::SA_LOADS == 1 && Cfg::SB_LOADS == 1, "one scale request per wavefront and operand");
+    MXFP8_DYNAMIC_LDS(lds);
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int nkb = K / kBlock;
+    const int KT = K / BK;
+    const int ntiles = tiles_m * tiles_n;
+    const int stride = gridDim.x;
+    const int my_tiles = (ntiles - (int)blockIdx.x + stride - 1) / stride;  // >= 1: the grid has at most ntiles workgroups
+
+    // ---- DMA offsets inside an operand tile (see the kernel above; no ragged rows here)
+    const int ld_r = lane >> 3, ld_c = lane & 7;
+    uint32_t a_goff[Cfg::A_LOADS], b_goff[Cfg::B_LOADS];
+#pragma unroll
+    for (int i = 0; i < Cfg::A_LOADS; ++i) {
+        const int row = (wave * Cfg::A_LOADS + i) * 8 + ld_r;
+        a_goff[i] = (uint32_t)row * (uint32_t)K + (ld_c ^ ((row >> 1) & 7)) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < Cfg::B_LOADS; ++i) {
+        const int row = (wave * Cfg::B_LOADS + i) * 8 + ld_r;
+        b_goff[i] = (uint32_t)row * (uint32_t)K + (ld_c ^ ((row >> 1) & 7)) * 16;
+    }
+    const int a_grp = wave % (Cfg::BM / 64), b_grp = wave % (Cfg::BN / 64);  // 64-row group whose scales this wavefront fetches
+    const uint32_t as_goff = TILED ? lane * 4 : (uint32_t)(a_grp * 64 + lane) * (uint32_t)nkb;
+    const uint32_t bs_goff = TILED ? lane * 4 : (uint32_t)(b_grp * 64 + lane) * (uint32_t)nkb;
+    const int s_step = TILED ? 256 : 4;  // bytes from the scale dwords of one K step to the next
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
+
+    // operand pointers of a tile at K step 0 (wavefront-uniform)
+    struct Tile {
+        const uint8_t *a, *b, *as, *bs;
+        int m0, n0;
+    };
+    auto tile_at = [&](int index) __attribute__((always_inline)) {
+        int tm, tn;
+        tile_of_block((int)blockIdx.x + index * stride, ntiles, tiles_m, tiles_n, tm, tn);
+        Tile t;
+        t.m0 = tm * Cfg::BM;
+        t.n0 = tn * Cfg::BN;
+        t.a = a_q + (int64_t)t.m0 * K;
+        t.b = b_q + (int64_t)t.n0 * K;
+        if constexpr (TILED) {
+            t.as = a_s + (int64_t)(t.m0 / 64 + a_grp) * KT * 256;
+            t.bs = b_s + (int64_t)(t.n0 / 64 + b_grp) * KT * 256;
+        } else {
+            t.as = a_s + (int64_t)t.m0 * nkb;
+            t.bs = b_s + (int64_t)t.n0 * nkb;
+        }
+        return t;
+    };
+
+    // DMA slot t of the A / B requests of one K step, from the step's source pointers into buffer buf
+    auto issue_a = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
+        if (t < Cfg::A_LOADS)
+            dma_load<16>(src, a_goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
+        else if (t < Cfg::NA)
+            dma_load<4>(ssrc, as_goff, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + a_grp * 256);
+    };
+    auto issue_b = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
+        if (t < Cfg::B_LOADS)
+            dma_load<16>(src, b_goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
+        else if (t < Cfg::NB)
+            dma_load<4>(ssrc, bs_goff, lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + b_grp * 256);
+    };
+
+    const int a_row = wm * Cfg::WM + r16, b_row = wn * Cfg::WN + r16;
+    const int a_off0 = a_row * BK + ((g ^ ((a_row >> 1) & 7)) << 4), a_off1 = a_row * BK + (((4 + g) ^ ((a_row >> 1) & 7)) << 4);
+    const int b_off0 = b_row * BK + ((g ^ ((b_row >> 1) & 7)) << 4), b_off1 = b_row * BK + (((4 + g) ^ ((b_row >> 1) & 7)) << 4);
+    const int a_soff = a_row * 4 + g, b_soff = b_row * 4 + g;
+    auto read_frag = [&](const uint8_t *base, int off0, int off1) __attribute__((always_inline)) {
+        const v4i lo = *reinterpret_cast<const v4i *>(base + off0);
+        const v4i hi = *reinterpret_cast<const v4i *>(base + off1);
+        return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    };
+
+    v4f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+    v8i fa[TM];
+    int sa[TM];
+
+    // One K step, same schedule as in the kernel above; the requests go to the sources handed in:
+    // (b_src, bs_src) = B tile and scales of the workgroup's NEXT step, (a_src, as_src) = A tile and
+    // scales of the step after that, either of which may belong to the next output tile.
+    constexpr int A_LO = (TN - 2) * (TM - TM / 2) >= Cfg::NA ? TM / 2 : 0;
+    static_assert((TN - 2) * (TM - A_LO) >= Cfg::NA, "A requests fit into columns 1..TN-2");
+    auto step = [&](int cur, const uint8_t *b_src, const uint8_t *bs_src, const uint8_t *a_src,
+                    const uint8_t *as_src) __attribute__((always_inline)) {
+        const int nxt = cur ^ 1;
+        const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
+        const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::BM * 4;
+        constexpr int NFB = 3;
+        v8i fb[NFB];
+        int sb[NFB];
+#pragma unroll
+        for (int j = 0; j < NFB - 1 && j < TN; ++j) {
+            fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
+            sb[j] = sbbuf[b_soff + j * 64];
+        }
+        MXFP8_PIN();
+        int a_slot = 0;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (j + NFB - 1 < TN) {
+                fb[(j + NFB - 1) % NFB] = read_frag(bbuf, b_off0 + (j + NFB - 1) * 2048, b_off1 + (j + NFB - 1) * 2048);
+                sb[(j + NFB - 1) % NFB] = sbbuf[b_soff + (j + NFB - 1) * 64];
+            }
+            if (j == TN - 1) {
+                MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);
+                __syncthreads();
+            }
+            MXFP8_PIN();
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j % NFB], fa[i], acc[i][j], 0, 0, 0,
+                                                                             sb[j % NFB], 0, sa[i]);
+                MXFP8_PIN();
+                if (j == 0) {
+                    issue_b(i, b_src, bs_src, nxt);
+                    if (i + TM < Cfg::NB)
+                        issue_b(i + TM, b_src, bs_src, nxt);
+                } else if (j < TN - 1 && i >= A_LO) {
+                    if (a_slot < Cfg::NA)
+                        issue_a(a_slot, a_src, as_src, cur);
+                    ++a_slot;
+                }
+                if (j == TN - 1) {
+                    fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
+                    sa[i] = sanext[a_soff + i * 64];
+                }
+                MXFP8_PIN();
+            }
+        }
+        MXFP8_WAIT_VMCNT(Cfg::NA);
+        __syncthreads();
+    };
+
+    Tile cur_tile = tile_at(0);
+    // prologue of the workgroup's first tile: A(0), B(0) into buffers 0, A(1) into A buffer 1
+#pragma unroll
+    for (int t = 0; t < Cfg::NA; ++t)
+        issue_a(t, cur_tile.a, cur_tile.as, 0);
+#pragma unroll
+    for (int t = 0; t < Cfg::NB; ++t)
+        issue_b(t, cur_tile.b, cur_tile.bs, 0);
+#pragma unroll
+    for (int t = 0; t < Cfg::NA; ++t)
+        issue_a(t, cur_tile.a + BK, cur_tile.as + s_step, 1);
+    MXFP8_WAIT_VMCNT(0);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
+        sa[i] = (lds + Cfg::SA_OFF)[a_soff + i * 64];
+    }
+    __syncthreads();
+
+    int par = 0;  // LDS buffer parity of the workgroup's running step count
+    for (int ti = 0; ti < my_tiles; ++ti) {
+        const bool has_next = ti + 1 < my_tiles;
+        const Tile next_tile = has_next ? tile_at(ti + 1) : cur_tile;
+        for (int kt = 0; kt < KT; ++kt) {
+            // source of the step after this one (B) and of the one after that (A): this tile, else the
+            // first steps of the next tile, else (last tile) this tile's last step once more
+            const uint8_t *b_src, *bs_src, *a_src, *as_src;
+            if (kt + 1 < KT) {
+                b_src = cur_tile.b + (int64_t)(kt + 1) * BK;
+                bs_src = cur_tile.bs + (int64_t)(kt + 1) * s_step;
+            } else if (has_next) {
+                b_src = next_tile.b;
+                bs_src = next_tile.bs;
+            } else {
+                b_src = cur_tile.b + (int64_t)(KT - 1) * BK;
+                bs_src = cur_tile.bs + (int64_t)(KT - 1) * s_step;
+            }
+            if (kt + 2 < KT) {
+                a_src = cur_tile.a + (int64_t)(kt + 2) * BK;
+                as_src = cur_tile.as + (int64_t)(kt + 2) * s_step;
+            } else if (has_next) {
+                a_src = next_tile.a + (int64_t)(kt + 2 - KT) * BK;
+                as_src = next_tile.as + (int64_t)(kt + 2 - KT) * s_step;
+            } else {
+                a_src = cur_tile.a + (int64_t)(KT - 1) * BK;
+                as_src = cur_tile.as + (int64_t)(KT - 1) * s_step;
+            }
+            step(par, b_src, bs_src, a_src, as_src);
+            par ^= 1;
+        }
+        // ---- epilogue of this tile; the A requests of the next tile's second step are in flight
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            uint8_t *crow = c + (int64_t)(cur_tile.m0 + wm * Cfg::WM + i * 16 + r16) * ldc_bytes;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = cur_tile.n0 + wn * Cfg::WN + j * 16 + 4 * g;
+                const v4f v = acc[i][j];
+                if constexpr (OUT_BF16) {
+                    v2bf p0 = {(__bf16)v[0], (__bf16)v[1]}, p1 = {(__bf16)v[2], (__bf16)v[3]};
+                    *reinterpret_cast<uint2 *>(crow + (int64_t)n * 2) =
+                        make_uint2(__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1));
+                } else {
+                    *reinterpret_cast<float4 *>(crow + (int64_t)n * 4) = make_float4(v[0], v[1], v[2], v[3]);
+                }
+                acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        cur_tile = next_tile;
+    }
+    MXFP8_WAIT_VMCNT(0);  // the redundant prefetches of the last steps must land before LDS is released
+}
+
+// The persistent kernel is opt-in until it has been timed against the one-tile-per-workgroup kernel:
+// MXFP8_GEMM_PERSISTENT=<workgroups> in the environment (256 = one per compute unit of an MI355X)
+// selects it for the shapes it supports; unset or 0 leaves it off.
+static int persistent_workgroups()
+{
+    const char *e = getenv("MXFP8_GEMM_PERSISTENT");
+    const long n = e ? strtol(e, nullptr, 10) : 0;
+    return n > 0 && n <= 65536 ? (int)n : 0;
+}
+
 template <class Cfg, bool OUT_BF16, bool TILED>
 static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
                              int M, int N, int K, void *c, int64_t ldc, hipStream_t stream)
 {
     const int tiles_m = (M + Cfg::BM - 1) / Cfg::BM, tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
-    auto kern = gemm_kernel<Cfg, OUT_BF16, TILED>;
     const int64_t ldc_bytes = ldc * (OUT_BF16 ? 2 : 4);
     // 128-bit (FP32) / 64-bit (BF16) stores need every row start aligned; otherwise element stores
     const bool vec_store = (reinterpret_cast<uintptr_t>(c) % 16 == 0) && (ldc_bytes % 16 == 0);
+    const int workgroups = persistent_workgroups();
+    if (workgroups > 0 && M % Cfg::BM == 0 && N % Cfg::BN == 0 && K >= 2 * BK && vec_store) {
+        auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+        if (e != hipSuccess)
+            return e;
+        const int ntiles = tiles_m * tiles_n;
+        hipLaunchKernelGGL(kern, dim3((unsigned)min(ntiles, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
+                           stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n);
+        return hipGetLastError();
+    }
+    auto kern = gemm_kernel<Cfg, OUT_BF16, TILED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess)

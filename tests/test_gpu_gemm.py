@@ -298,3 +298,30 @@ def test_full_size_layer_on_sampled_rows(pass_):
     extra = hw_tolerance(*host_a, *host_b, rows=rows)
     _compare(got, ref, absref, TARGET_ELEM, None, f"full-size {pass_} ({len(rows)} rows)", extra=extra)
     assert torch.isfinite(c).all()
+
+
+@pytest.mark.parametrize("name,H,O", [("qkv", 4096, 6144), ("attn_out", 4096, 4096), ("gate_up", 4096, 28672),
+                                      ("down", 14336, 4096)])
+def test_transformer_layer_linear_set_forward_on_sampled_rows(name, H, O):
+    """The four linear layers of an 8B-class transformer block at 16384 tokens (QKV with 32 query and
+    8 key/value heads of 128, attention output, fused gate+up, down projection): forward product from
+    BF16 tensors quantized on the GPU, BF16 output, checked on sampled rows against the oracle, which
+    quantizes only what it needs (the sampled token rows and the whole weight)."""
+    T = 16384
+    x = si.activations(T, H, seed=6)
+    w = si.weights(O, H, seed=7)
+    to = lambda t: _dev(t.view(np.int16)).view(torch.bfloat16)
+    A, B = mx.quantize(to(x), "rowwise"), mx.quantize(to(w), "rowwise")
+    c = mx.gemm("fprop", A["q_row"], A["s_row"], B["q_row"], B["s_row"], torch.bfloat16)
+    torch.cuda.synchronize()
+    rows = np.array(sorted({0, 17, 255, 256, T // 2 - 1, T // 2, T - 257, T - 1}))
+    a_q, a_s = oracle.quantize_rowwise(np.ascontiguousarray(x[rows]))
+    b_q, b_s = oracle.quantize_rowwise(w)
+    # element bytes of the sampled rows are the quantizer's own parity again, at this shape
+    assert np.array_equal(A["q_row"][torch.from_numpy(rows).cuda()].cpu().numpy(), a_q)
+    ref, absref = oracle.gemm_rows(a_q, a_s, b_q, b_s, np.arange(len(rows)))
+    got = si.bf16_bits_to_f32(c[torch.from_numpy(rows).cuda()].view(torch.int16).cpu().numpy().view(np.uint16))
+    extra = hw_tolerance(a_q, a_s, b_q, b_s)
+    _compare(got.astype(np.float64), ref, absref, TARGET_ELEM, None, f"16384-token {name} {H}->{O}", bf16=True,
+             extra=extra)
+    assert torch.isfinite(c.float()).all()

@@ -1,8 +1,12 @@
-"""GPU parity of the tiled scale layout (MXFP8_SCALES_TILED): mxfp8_quantize_ex, mxfp8_gemm_ex and
+"""GPU parity of the opt-in paths: the tiled scale layout (MXFP8_SCALES_TILED): mxfp8_quantize_ex, mxfp8_gemm_ex and
 mxfp8_dequantize_ex through the C ABI against the CPU oracle. The layout only moves scale bytes, so
 every value must equal what the row-major entry points are held to: quantized bytes bit-exact,
 products within the tolerance of test_gpu_gemm (and, on identical operands, identical to the
-row-major product bit for bit, since the same instructions add the same numbers in the same order)."""
+row-major product bit for bit, since the same instructions add the same numbers in the same order).
+The persistent GEMM kernel (MXFP8_GEMM_PERSISTENT=<workgroups>) is held to the same: it runs the same
+K steps in the same order, so its output equals the ordinary kernel's bit for bit."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -154,3 +158,56 @@ def test_tiled_error_codes():
     assert e.value.code == 3
     assert mx.mxfp8_scale_bytes(8192, 4096, TILED) == 8192 * 128
     assert mx.mxfp8_scale_bytes(100, 96, TILED) == 2 * 1 * 256
+
+
+# ---- persistent GEMM kernel ---------------------------------------------------------------------------
+class _persistent:
+    def __init__(self, workgroups):
+        self.n = str(workgroups)
+
+    def __enter__(self):
+        os.environ["MXFP8_GEMM_PERSISTENT"] = self.n
+
+    def __exit__(self, *exc):
+        os.environ.pop("MXFP8_GEMM_PERSISTENT", None)
+
+
+@pytest.mark.parametrize("shape,workgroups", [((256, 384, 384), 2), ((384, 256, 256), 6), ((2048, 4096, 512), 64),
+                                              ((2048, 4096, 512), 256)])
+@pytest.mark.parametrize("tiled", [False, True])
+def test_persistent_gemm_matches_oracle_and_ordinary_kernel(shape, workgroups, tiled):
+    M, N, K = shape
+    ops = _operands(M, N, K, seed=100 + M + K)
+    a_q, a_s, b_q, b_s = ops
+    lay = TILED if tiled else mx.SCALES_ROWMAJOR
+    sc = (lambda s: _dev(sl.tile(s, filler=0xFF))) if tiled else _dev
+    args = ("fprop", _dev(a_q), sc(a_s), _dev(b_q), sc(b_s))
+    for dtype in (torch.float32, torch.bfloat16):
+        plain = mx.gemm(*args, dtype, scale_layout=lay)
+        with _persistent(workgroups):
+            pers = mx.gemm(*args, dtype, scale_layout=lay)
+        torch.cuda.synchronize()
+        assert torch.equal(plain.view(torch.int32 if dtype == torch.float32 else torch.int16),
+                           pers.view(torch.int32 if dtype == torch.float32 else torch.int16))
+    rows = np.unique(np.linspace(0, M - 1, min(M, 32)).astype(int))
+    ref, absref = oracle.gemm_rows(*ops, rows)
+    with _persistent(workgroups):
+        got = mx.gemm(*args, torch.float32, scale_layout=lay)
+    torch.cuda.synchronize()
+    _compare(got.cpu().numpy().astype(np.float64)[rows], ref, absref, TARGET_ELEM, None,
+             f"persistent {shape} x{workgroups}", extra=hw_tolerance(*ops, rows=rows))
+
+
+def test_persistent_gemm_full_size_equals_ordinary_kernel():
+    """The benchmark's forward product with 256 persistent workgroups (7 tiles each), both layouts."""
+    T, H, O = 8192, 4096, 14336
+    X = _dev(si.activations(T, H, seed=2).view(np.int16)).view(torch.bfloat16)
+    W = _dev(si.weights(O, H, seed=4).view(np.int16)).view(torch.bfloat16)
+    for lay in (mx.SCALES_ROWMAJOR, TILED):
+        x, w = mx.quantize(X, "rowwise", scale_layout=lay), mx.quantize(W, "rowwise", scale_layout=lay)
+        args = ("fprop", x["q_row"], x["s_row"], w["q_row"], w["s_row"], torch.bfloat16)
+        plain = mx.gemm(*args, scale_layout=lay)
+        with _persistent(256):
+            pers = mx.gemm(*args, scale_layout=lay)
+        torch.cuda.synchronize()
+        assert torch.equal(plain.view(torch.int16), pers.view(torch.int16))

@@ -303,6 +303,41 @@ def test_dequantize_tiled_scales(hostmodel, tmp_path):
     assert np.array_equal(got[~np.isnan(want)], want[~np.isnan(want)])
 
 
+# ---- persistent GEMM kernel (opt-in through MXFP8_GEMM_PERSISTENT=<workgroups>) -------------------------
+@pytest.mark.parametrize("mode", [MODES[0], MODES[3]], ids=["lazy-up", "eager-down"])
+@pytest.mark.parametrize("tiled", [False, True], ids=["rowmajor", "tiled"])
+def test_gemm_persistent_small_tiles(hostmodel, tmp_path, mode, tiled):
+    """Workgroups that walk over 3, 2 and 1 tiles (6 tiles of 128x128 on 2, 4 and 6 workgroups), K of
+    2 and 3 steps: the K pipeline runs across tile boundaries, each tile is stored once."""
+    lines, checks, envs = [], [], []
+    for i, (M, N, K, bf16, wgs) in enumerate([(256, 384, 384, False, 2), (256, 384, 256, True, 4),
+                                               (384, 256, 384, False, 6)]):
+        ops = _operands(M, N, K, seed=80 + i)
+        line, out = _gemm_case(tmp_path, M, N, K, ops, bf16, tag=str(i), tiled=tiled)
+        _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=wgs, **mode)
+        assert calls[0] == (0, list(range(wgs)))
+        _check_gemm(out, M, N, N, ops, bf16)
+
+
+def test_gemm_persistent_large_tiles_sampled_workgroups(hostmodel, tmp_path):
+    """256x256 configuration: 128 tiles on 64 workgroups (2 tiles each); first and last workgroup."""
+    M, N, K = 2048, 4096, 256
+    ops = _operands(M, N, K, seed=90, spikes=True)
+    line, out = _gemm_case(tmp_path, M, N, K, ops, bf16=True, tiled=True)
+    _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=64, WAVESIM_BLOCKS=2)
+    assert calls[0] == (0, [0, 63])
+    assert _check_gemm(out, M, N, N, ops, True, expect_full=False) == 4 * 256 * 256
+
+
+def test_gemm_persistent_falls_back_for_ragged_shapes(hostmodel, tmp_path):
+    M, N, K = 200, 136, 384
+    ops = _operands(M, N, K, seed=91)
+    line, out = _gemm_case(tmp_path, M, N, K, ops)
+    _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=2)
+    assert calls[0] == (0, [0, 1, 2, 3])                 # one workgroup per tile: the ordinary kernel ran
+    _check_gemm(out, M, N, N, ops, False)
+
+
 def test_gemm_unaligned_c_takes_element_stores(hostmodel, tmp_path):
     M, N, K = 40, 37, 128
     ops = _operands(M, N, K, seed=30)
