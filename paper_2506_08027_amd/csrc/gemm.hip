@@ -350,22 +350,18 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const int stride = gridDim.x;
     const int my_tiles = (ntiles - (int)blockIdx.x + stride - 1) / stride;  // >= 1: the grid has at most ntiles workgroups
 
-    // ---- DMA offsets inside an operand tile (see the kernel above; no ragged rows here)
+    // ---- DMA offsets inside an operand tile (see the kernel above). Without ragged rows they do not
+    // depend on the tile, and with square tiles the A and the B tile use the same ones.
+    static_assert(Cfg::BM == Cfg::BN, "A and B tiles share their DMA offsets");
     const int ld_r = lane >> 3, ld_c = lane & 7;
-    uint32_t a_goff[Cfg::A_LOADS], b_goff[Cfg::B_LOADS];
+    uint32_t goff[Cfg::A_LOADS];
 #pragma unroll
     for (int i = 0; i < Cfg::A_LOADS; ++i) {
         const int row = (wave * Cfg::A_LOADS + i) * 8 + ld_r;
-        a_goff[i] = (uint32_t)row * (uint32_t)K + (ld_c ^ ((row >> 1) & 7)) * 16;
+        goff[i] = (uint32_t)row * (uint32_t)K + (ld_c ^ ((row >> 1) & 7)) * 16;
     }
-#pragma unroll
-    for (int i = 0; i < Cfg::B_LOADS; ++i) {
-        const int row = (wave * Cfg::B_LOADS + i) * 8 + ld_r;
-        b_goff[i] = (uint32_t)row * (uint32_t)K + (ld_c ^ ((row >> 1) & 7)) * 16;
-    }
-    const int a_grp = wave % (Cfg::BM / 64), b_grp = wave % (Cfg::BN / 64);  // 64-row group whose scales this wavefront fetches
-    const uint32_t as_goff = TILED ? lane * 4 : (uint32_t)(a_grp * 64 + lane) * (uint32_t)nkb;
-    const uint32_t bs_goff = TILED ? lane * 4 : (uint32_t)(b_grp * 64 + lane) * (uint32_t)nkb;
+    const int grp = wave % (Cfg::BM / 64);  // 64-row group of each tile whose scale dwords this wavefront fetches
+    const uint32_t sgoff = TILED ? lane * 4 : (uint32_t)(grp * 64 + lane) * (uint32_t)nkb;
     const int s_step = TILED ? 256 : 4;  // bytes from the scale dwords of one K step to the next
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
 
@@ -383,8 +379,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         t.a = a_q + (int64_t)t.m0 * K;
         t.b = b_q + (int64_t)t.n0 * K;
         if constexpr (TILED) {
-            t.as = a_s + (int64_t)(t.m0 / 64 + a_grp) * KT * 256;
-            t.bs = b_s + (int64_t)(t.n0 / 64 + b_grp) * KT * 256;
+            t.as = a_s + (int64_t)(t.m0 / 64 + grp) * KT * 256;
+            t.bs = b_s + (int64_t)(t.n0 / 64 + grp) * KT * 256;
         } else {
             t.as = a_s + (int64_t)t.m0 * nkb;
             t.bs = b_s + (int64_t)t.n0 * nkb;
@@ -395,15 +391,15 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     // DMA slot t of the A / B requests of one K step, from the step's source pointers into buffer buf
     auto issue_a = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::A_LOADS)
-            dma_load<16>(src, a_goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
+            dma_load<16>(src, goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
         else if (t < Cfg::NA)
-            dma_load<4>(ssrc, as_goff, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + a_grp * 256);
+            dma_load<4>(ssrc, sgoff, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + grp * 256);
     };
     auto issue_b = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::B_LOADS)
-            dma_load<16>(src, b_goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
+            dma_load<16>(src, goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
         else if (t < Cfg::NB)
-            dma_load<4>(ssrc, bs_goff, lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + b_grp * 256);
+            dma_load<4>(ssrc, sgoff, lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + grp * 256);
     };
 
     const int a_row = wm * Cfg::WM + r16, b_row = wn * Cfg::WN + r16;
@@ -532,24 +528,40 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             step(par, b_src, bs_src, a_src, as_src);
             par ^= 1;
         }
-        // ---- epilogue of this tile; the A requests of the next tile's second step are in flight
+        // ---- epilogue of this tile; the A requests of the next tile's second step are in flight.
+        // Every store of a lane has the same 32-bit offset from a wavefront-uniform base (row group i)
+        // plus a constant (column tile j): no per-store address arithmetic, few live registers next to
+        // the A fragments of the next tile. Rows are finished one after the other (pinned) so that the
+        // converted values of only one row group are live at a time.
+        constexpr int ESZ = OUT_BF16 ? 2 : 4;
+        uint8_t *ctile = c + (int64_t)cur_tile.m0 * ldc_bytes + (int64_t)cur_tile.n0 * ESZ;
+        const uint32_t lane_off = (uint32_t)(wm * Cfg::WM + r16) * (uint32_t)ldc_bytes + (uint32_t)(wn * Cfg::WN + 4 * g) * ESZ;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            uint8_t *crow = c + (int64_t)(cur_tile.m0 + wm * Cfg::WM + i * 16 + r16) * ldc_bytes;
+            uint8_t *crow = ctile + (int64_t)(i * 16) * ldc_bytes;
+            // the values of this row group are still in accumulator registers at this point: keeps the
+            // compiler from moving all 256 of them into ordinary registers at the top of the epilogue
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                MXFP8_KEEP_IN_ACC(acc[i][j]);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int n = cur_tile.n0 + wn * Cfg::WN + j * 16 + 4 * g;
                 const v4f v = acc[i][j];
                 if constexpr (OUT_BF16) {
                     v2bf p0 = {(__bf16)v[0], (__bf16)v[1]}, p1 = {(__bf16)v[2], (__bf16)v[3]};
-                    *reinterpret_cast<uint2 *>(crow + (int64_t)n * 2) =
+                    *reinterpret_cast<uint2 *>(crow + lane_off + j * 16 * ESZ) =
                         make_uint2(__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1));
                 } else {
-                    *reinterpret_cast<float4 *>(crow + (int64_t)n * 4) = make_float4(v[0], v[1], v[2], v[3]);
+                    *reinterpret_cast<float4 *>(crow + lane_off + j * 16 * ESZ) = make_float4(v[0], v[1], v[2], v[3]);
                 }
-                acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
             }
+            MXFP8_PIN();
         }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
         cur_tile = next_tile;
     }
     MXFP8_WAIT_VMCNT(0);  // the redundant prefetches of the last steps must land before LDS is released
@@ -574,7 +586,9 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
     // 128-bit (FP32) / 64-bit (BF16) stores need every row start aligned; otherwise element stores
     const bool vec_store = (reinterpret_cast<uintptr_t>(c) % 16 == 0) && (ldc_bytes % 16 == 0);
     const int workgroups = persistent_workgroups();
-    if (workgroups > 0 && M % Cfg::BM == 0 && N % Cfg::BN == 0 && K >= 2 * BK && vec_store) {
+    // (its epilogue addresses a tile's rows with 32-bit offsets from the tile origin)
+    if (workgroups > 0 && M % Cfg::BM == 0 && N % Cfg::BN == 0 && K >= 2 * BK && vec_store &&
+        ldc_bytes * Cfg::BM < (int64_t(1) << 31)) {
         auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);

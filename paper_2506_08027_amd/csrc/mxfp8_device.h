@@ -108,10 +108,12 @@ __device__ __forceinline__ uint32_t inf_byte_bf16(uint32_t bits16, uint32_t q)
 
 // ---- what exists only on the GPU --------------------------------------------------------------
 // The CPU tests compile these kernel sources as host C++ against an execution model of their own;
-// that build defines MXFP8_HOST_MODEL and brings its own versions of the two items below.
+// that build defines MXFP8_HOST_MODEL and brings its own versions of the items below.
 #ifndef MXFP8_HOST_MODEL
 // The workgroup's dynamically sized LDS block (size given at launch).
 #define MXFP8_DYNAMIC_LDS(name) extern __shared__ __attribute__((aligned(1024))) uint8_t name[]
+// States that x lives in accumulator registers (AGPRs) at this point of the program.
+#define MXFP8_KEEP_IN_ACC(x) asm volatile("" : "+a"(x))
 
 // Global memory -> LDS without passing through registers: lane l of the wavefront fetches BYTES
 // bytes from base + voff (its own address) and the hardware writes them to LDS address

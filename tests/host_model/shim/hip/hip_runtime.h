@@ -75,7 +75,8 @@ inline hipError_t hipGetLastError() { return hipSuccess; }
         ::wavesim::launch((grid), (block), (shmem), [=]() { kern(__VA_ARGS__); });           \
     } while (0)
 
-// ---- the two pieces of mxfp8_device.h that exist only on the GPU ------------------------------
+// ---- the pieces of mxfp8_device.h that exist only on the GPU -----------------------------------
+#define MXFP8_KEEP_IN_ACC(x) ((void)0)  // a register-allocation hint
 // dynamic LDS: the block allocated for this launch
 #define MXFP8_DYNAMIC_LDS(name) uint8_t *const name = ::wavesim::g.lds
 namespace mxfp8 {
