@@ -69,7 +69,7 @@ typedef enum { MXFP8_FPROP = 0, MXFP8_DGRAD = 1, MXFP8_WGRAD = 2 } mxfp8_pass;
 typedef enum { MXFP8_SCALES_ROWMAJOR = 0, MXFP8_SCALES_TILED = 1 } mxfp8_scale_layout;
 
 /* Size in bytes of the scale buffer of a [rows x cols] operand in `layout` (host arithmetic only);
- * -1 for negative sizes, cols not a multiple of 32 or an unknown layout. */
+ * -1 for negative sizes, sizes beyond 2^31 - 1, cols not a multiple of 32 or an unknown layout. */
 int64_t mxfp8_scale_bytes(int64_t rows, int64_t cols, mxfp8_scale_layout layout);
 
 /*

@@ -108,7 +108,7 @@ def _check_scales(s, rows, cols, scale_layout, what):
     if scale_layout == SCALES_ROWMAJOR:
         if tuple(s.shape) != (rows, cols // K_BLOCK):
             raise ValueError(f"{what} must be [{rows} x {cols // K_BLOCK}]")
-    elif s.numel() < mxfp8_scale_bytes(rows, cols, scale_layout):
+    elif scale_layout == SCALES_TILED and s.numel() < mxfp8_scale_bytes(rows, cols, scale_layout):
         raise ValueError(f"{what} holds {s.numel()} bytes, the tiled layout needs "
                          f"{mxfp8_scale_bytes(rows, cols, scale_layout)}")
 
@@ -127,7 +127,7 @@ def mxfp8_quantize_ex(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=Non
         raise ValueError("src must be 2-D with contiguous rows")
     rows, cols = src.shape
     ld = src.stride(0) if rows > 1 else max(cols, 1)
-    if scale_layout != SCALES_ROWMAJOR:   # the library cannot see buffer sizes: check them here
+    if scale_layout == SCALES_TILED:      # the library cannot see buffer sizes: check them here
         if s_row is not None and _AXIS[axis] & ROWWISE:
             _check_scales(s_row, rows, cols, scale_layout, "s_row")
         if s_colT is not None and _AXIS[axis] & COLWISE:

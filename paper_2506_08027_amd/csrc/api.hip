@@ -31,7 +31,7 @@ extern "C" {
 
 int64_t mxfp8_scale_bytes(int64_t rows, int64_t cols, mxfp8_scale_layout layout)
 {
-    if (rows < 0 || cols < 0 || cols % 32 || !valid_layout(layout))
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || cols % 32 || !valid_layout(layout))
         return -1;
     const int64_t nb = cols / 32;
     return layout == MXFP8_SCALES_TILED ? ((rows + 63) / 64) * ((nb + 3) / 4) * 256 : rows * nb;

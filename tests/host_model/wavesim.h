@@ -427,6 +427,8 @@ inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp
 // ---- direct-to-LDS loads and their counter -------------------------------------------------------
 inline void check_global(const uint8_t *p, uint32_t bytes)
 {
+    if (g.buffers.empty())  // a host that registers nothing (not the test driver) gets no range check
+        return;
     for (const Buffer &b : g.buffers)
         if (p >= b.p && p + bytes <= b.p + b.n)
             return;
