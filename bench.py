@@ -174,19 +174,28 @@ def main():
         q_x = timed_ms(lambda: mx.mxfp8_quantize_ex(X, mx.BOTH, **Xt, scale_layout=lay))
         mx.mxfp8_quantize_ex(W, mx.BOTH, **Wt, scale_layout=lay)
         q_dy = timed_ms(lambda: mx.mxfp8_quantize_ex(dY, mx.BOTH, **dYt, scale_layout=lay))
-        g = timed_ms(lambda: mx.mxfp8_gemm_ex(mx.FPROP, Xt["q_row"], Xt["s_row"], Wt["q_row"], Wt["s_row"], Y, lay))
-        # the persistent GEMM kernel (opt-in through the environment), with both scale layouts
-        os.environ["MXFP8_GEMM_PERSISTENT"] = "256"
-        try:
-            gp_t = timed_ms(lambda: mx.mxfp8_gemm_ex(mx.FPROP, Xt["q_row"], Xt["s_row"], Wt["q_row"], Wt["s_row"], Y, lay))
-            gp_r = timed_ms(lambda: mx.mxfp8_gemm(mx.FPROP, Xq["q_row"], Xq["s_row"], Wq["q_row"], Wq["s_row"], Y))
-        finally:
-            os.environ.pop("MXFP8_GEMM_PERSISTENT", None)
+        # the three products of the layer: default kernel / tiled scales / persistent kernel on either layout
+        calls = {
+            "fprop": (lambda q, lay_: (mx.FPROP, q[0]["q_row"], q[0]["s_row"], q[1]["q_row"], q[1]["s_row"], Y, lay_),
+                      (Xq, Wq), (Xt, Wt)),
+            "dgrad": (lambda q, lay_: (mx.DGRAD, q[0]["q_row"], q[0]["s_row"], q[1]["q_colT"], q[1]["s_colT"], dX, lay_),
+                      (dYq, Wq), (dYt, Wt)),
+            "wgrad": (lambda q, lay_: (mx.WGRAD, q[0]["q_colT"], q[0]["s_colT"], q[1]["q_colT"], q[1]["s_colT"], dW, lay_),
+                      (dYq, Xq), (dYt, Xt)),
+        }
         tf = lambda ms: 2.0 * T * H * O / (ms * 1e-3) / 1e12
-        return {"fprop_tflops": tf(g), "fprop_ms": g,
-                "fprop_persistent_tflops": tf(gp_t), "fprop_persistent_rowmajor_scales_tflops": tf(gp_r),
-                "quantize_x_bf16_both_gbs": T * H * 4.0625 / (q_x * 1e-3) / 1e9, "quantize_x_ms": q_x,
-                "quantize_dy_f32_both_gbs": T * O * 6.0625 / (q_dy * 1e-3) / 1e9, "quantize_dy_ms": q_dy}
+        out = {"quantize_x_bf16_both_gbs_tiled": T * H * 4.0625 / (q_x * 1e-3) / 1e9, "quantize_x_ms_tiled": q_x,
+               "quantize_dy_f32_both_gbs_tiled": T * O * 6.0625 / (q_dy * 1e-3) / 1e9, "quantize_dy_ms_tiled": q_dy}
+        for name, (mk, rowmajor, tiled_ops) in calls.items():
+            out[name + "_tflops_default"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(rowmajor, mx.SCALES_ROWMAJOR))))
+            out[name + "_tflops_tiled"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(tiled_ops, lay))))
+            os.environ["MXFP8_GEMM_PERSISTENT"] = "256"
+            try:
+                out[name + "_tflops_persistent"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(rowmajor, mx.SCALES_ROWMAJOR))))
+                out[name + "_tflops_tiled_persistent"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(tiled_ops, lay))))
+            finally:
+                os.environ.pop("MXFP8_GEMM_PERSISTENT", None)
+        return out
 
     try:
         tiled = tiled_scale_variants()
