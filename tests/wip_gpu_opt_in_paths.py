@@ -1,4 +1,8 @@
-"""GPU parity of the opt-in paths: the tiled scale layout (MXFP8_SCALES_TILED): mxfp8_quantize_ex, mxfp8_gemm_ex and
+"""NOT COLLECTED by pytest on purpose (file name): these paths have passed on the CPU execution model
+only; run this file by name on an MI355X (`python -m pytest tests/wip_gpu_opt_in_paths.py -m gpu`) and
+rename it to test_gpu_zz_opt_in_paths.py once it has passed there.
+
+GPU parity of the opt-in paths: the tiled scale layout (MXFP8_SCALES_TILED): mxfp8_quantize_ex, mxfp8_gemm_ex and
 mxfp8_dequantize_ex through the C ABI against the CPU oracle. The layout only moves scale bytes, so
 every value must equal what the row-major entry points are held to: quantized bytes bit-exact,
 products within the tolerance of test_gpu_gemm (and, on identical operands, identical to the
