@@ -319,6 +319,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     }
 }
 
+// Workgroup barrier without the LDS fence of __syncthreads(): LDS reads issued before it may still be
+// in flight afterwards. The K step of the persistent kernel only hands DMA-written buffers from one
+// phase to the next (their arrival is tracked by vmcnt), and the fragment reads still in flight at its
+// barriers go to registers from a buffer whose next overwrite is requested hundreds of cycles later
+// and lands a global-memory latency after that, while this wavefront's next lgkmcnt wait (LDS reads
+// return in order) comes first.
+#define MXFP8_BARRIER() __builtin_amdgcn_s_barrier()
+
 // ---- persistent variant --------------------------------------------------------------------------
 // One workgroup per compute unit walks over several output tiles and keeps the K pipeline running
 // across tile boundaries: the prefetches of the last two K steps of a tile, which the kernel above
@@ -449,7 +457,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             }
             if (j == TN - 1) {
                 MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);
-                __syncthreads();
+                MXFP8_BARRIER();
             }
             MXFP8_PIN();
 #pragma unroll
@@ -474,7 +482,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             }
         }
         MXFP8_WAIT_VMCNT(Cfg::NA);
-        __syncthreads();
+        MXFP8_BARRIER();
     };
 
     Tile cur_tile = tile_at(0);
