@@ -1,12 +1,21 @@
 #!/bin/bash
-# Builds the CPU execution model of the library: the kernel sources, unchanged, as host C++ with
-# AddressSanitizer and alignment checks. Usage: tests/host_model/build.sh [output path]
+# Builds the CPU execution model of the library: the kernel sources, unchanged, as host C++.
+#   tests/host_model/build.sh [output]            the test driver, with AddressSanitizer and alignment checks
+#   tests/host_model/build.sh --shared [output]   the C ABI as a shared library (optimised, no sanitizer),
+#                                                 loadable in place of libmxfp8.so
 set -e
 here="$(cd "$(dirname "$0")" && pwd)"
-out="${1:-$here/_build/hostmodel}"
 csrc="$here/../../paper_2506_08027_amd/csrc"
-mkdir -p "$(dirname "$out")"
 CXX="${HOST_CLANG:-/opt/rocm/llvm/bin/clang++}"
-"$CXX" -std=c++17 -O1 -g -fsanitize=address,alignment -fno-sanitize-recover=all -fno-omit-frame-pointer \
-    -x c++ -I "$here/shim" -Wall -Wno-unknown-pragmas -Wno-unused-function -Wno-psabi \
-    -o "$out" "$here/driver.cpp" "$csrc/api.hip" "$csrc/quantize.hip" "$csrc/dequantize.hip" "$csrc/gemm.hip"
+common=(-std=c++17 -x c++ -I "$here/shim" -Wall -Wno-unknown-pragmas -Wno-unused-function -Wno-psabi)
+kernels=("$csrc/api.hip" "$csrc/quantize.hip" "$csrc/dequantize.hip" "$csrc/gemm.hip")
+if [ "$1" = "--shared" ]; then
+    out="${2:-$here/_build/libmxfp8_hostmodel.so}"
+    mkdir -p "$(dirname "$out")"
+    "$CXX" "${common[@]}" -O2 -fPIC -shared -o "$out" "${kernels[@]}"
+else
+    out="${1:-$here/_build/hostmodel}"
+    mkdir -p "$(dirname "$out")"
+    "$CXX" "${common[@]}" -O1 -g -fsanitize=address,alignment -fno-sanitize-recover=all -fno-omit-frame-pointer \
+        -o "$out" "$here/driver.cpp" "${kernels[@]}"
+fi
