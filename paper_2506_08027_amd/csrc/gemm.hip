@@ -327,6 +327,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 // return in order) comes first.
 #define MXFP8_BARRIER() __builtin_amdgcn_s_barrier()
 
+// Schedule variants of the persistent kernel's K step, to be timed against each other on the hardware
+// (MXFP8_GEMM_TUNE=<id>; 0 is the schedule of the kernel above). Every variant issues all B requests of
+// a step before its A requests and all of them before the last MFMA column: the wait counts rely on it.
+template <int ID> struct GemmTune {
+    static_assert(ID >= 0 && ID <= 6, "known variant");
+    static constexpr int NFB = ID == 2 ? 2 : ID == 3 ? 4 : 3;  // B fragment register sets (read NFB-1 columns ahead)
+    static constexpr bool SPREAD = ID == 1;                    // one B request per 2 MFMAs, then one A request per 4
+    static constexpr int POLICY = ID == 5 ? 1 : ID == 6 ? 2 : 0;  // cache-policy bits of the tile loads (see dma_load)
+};
+
 // ---- persistent variant --------------------------------------------------------------------------
 // One workgroup per compute unit walks over several output tiles and keeps the K pipeline running
 // across tile boundaries: the prefetches of the last two K steps of a tile, which the kernel above
@@ -338,7 +348,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 // Wait counts: the epilogue's stores also count in vmcnt. Loads complete in order among themselves,
 // so "at most n operations outstanding" still implies that all but the last n loads have landed,
 // whatever the stores do; the immediates of the K step stay valid (they can only wait longer).
-template <class Cfg, bool OUT_BF16, bool TILED>
+template <class Cfg, bool OUT_BF16, bool TILED, class Tune>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
@@ -399,13 +409,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     // DMA slot t of the A / B requests of one K step, from the step's source pointers into buffer buf
     auto issue_a = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::A_LOADS)
-            dma_load<16>(src, goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
+            dma_load<16, Tune::POLICY>(src, goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
         else if (t < Cfg::NA)
             dma_load<4>(ssrc, sgoff, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + grp * 256);
     };
     auto issue_b = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::B_LOADS)
-            dma_load<16>(src, goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
+            dma_load<16, Tune::POLICY>(src, goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
         else if (t < Cfg::NB)
             dma_load<4>(ssrc, sgoff, lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + grp * 256);
     };
@@ -439,7 +449,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         const int nxt = cur ^ 1;
         const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
         const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::BM * 4;
-        constexpr int NFB = 3;
+        constexpr int NFB = Tune::NFB;
         v8i fb[NFB];
         int sb[NFB];
 #pragma unroll
@@ -465,7 +475,15 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j % NFB], fa[i], acc[i][j], 0, 0, 0,
                                                                              sb[j % NFB], 0, sa[i]);
                 MXFP8_PIN();
-                if (j == 0) {
+                if constexpr (Tune::SPREAD) {
+                    constexpr int A_FIRST = 2 * Cfg::NB + 2;  // MFMA after which the first A request goes out
+                    static_assert(A_FIRST + 4 * (Cfg::NA - 1) < (TN - 1) * TM, "all requests before the last column");
+                    const int m = j * TM + i;  // compile-time after unrolling
+                    if (m % 2 == 0 && m / 2 < Cfg::NB)
+                        issue_b(m / 2, b_src, bs_src, nxt);
+                    else if (m >= A_FIRST && (m - A_FIRST) % 4 == 0 && (m - A_FIRST) / 4 < Cfg::NA)
+                        issue_a((m - A_FIRST) / 4, a_src, as_src, cur);
+                } else if (j == 0) {
                     issue_b(i, b_src, bs_src, nxt);
                     if (i + TM < Cfg::NB)
                         issue_b(i + TM, b_src, bs_src, nxt);
@@ -578,6 +596,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
 // The persistent kernel is opt-in until it has been timed against the one-tile-per-workgroup kernel:
 // MXFP8_GEMM_PERSISTENT=<workgroups> in the environment (256 = one per compute unit of an MI355X)
 // selects it for the shapes it supports; unset or 0 leaves it off.
+static int persistent_tune()
+{
+    const char *e = getenv("MXFP8_GEMM_TUNE");
+    const long n = e ? strtol(e, nullptr, 10) : 0;
+    return n >= 0 && n <= 6 ? (int)n : 0;
+}
+
 static int persistent_workgroups()
 {
     const char *e = getenv("MXFP8_GEMM_PERSISTENT");
@@ -597,15 +622,31 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
     // (its epilogue addresses a tile's rows with 32-bit offsets from the tile origin)
     if (workgroups > 0 && M % Cfg::BM == 0 && N % Cfg::BN == 0 && K >= 2 * BK && vec_store &&
         ldc_bytes * Cfg::BM < (int64_t(1) << 31)) {
-        auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-        if (e != hipSuccess)
-            return e;
-        const int ntiles = tiles_m * tiles_n;
-        hipLaunchKernelGGL(kern, dim3((unsigned)min(ntiles, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
-                           stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n);
-        return hipGetLastError();
+        // schedule variants exist for the 256x256 tile with tiled scales; anything else runs variant 0
+        const int tune = (Cfg::BM == 256 && TILED) ? persistent_tune() : 0;
+        auto launch = [&](auto kern) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+            if (e != hipSuccess)
+                return e;
+            const int ntiles = tiles_m * tiles_n;
+            hipLaunchKernelGGL(kern, dim3((unsigned)min(ntiles, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
+                               stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m,
+                               tiles_n);
+            return hipGetLastError();
+        };
+        if constexpr (Cfg::BM == 256 && TILED) {
+            switch (tune) {
+            case 1: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<1>>);
+            case 2: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<2>>);
+            case 3: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<3>>);
+            case 5: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<5>>);
+            case 6: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<6>>);
+            default: break;
+            }
+        }
+        (void)tune;
+        return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<0>>);
     }
     auto kern = gemm_kernel<Cfg, OUT_BF16, TILED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

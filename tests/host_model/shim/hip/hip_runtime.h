@@ -81,7 +81,7 @@ inline hipError_t hipGetLastError() { return hipSuccess; }
 // dynamic LDS: the block allocated for this launch
 #define MXFP8_DYNAMIC_LDS(name) uint8_t *const name = ::wavesim::g.lds
 namespace mxfp8 {
-template <int BYTES> inline void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+template <int BYTES, int POLICY = 0> inline void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
 {
     static_assert(BYTES == 4 || BYTES == 16, "dword or dwordx4");
     ::wavesim::dma_issue(base, voff, lds_addr, BYTES);

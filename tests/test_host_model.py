@@ -230,7 +230,7 @@ def _check_gemm(out, M, N, ldc, ops, bf16, expect_full=True):
 MODES = [dict(), dict(WAVESIM_DMA="eager"), dict(WAVESIM_ORDER="down"), dict(WAVESIM_DMA="eager", WAVESIM_ORDER="down")]
 
 
-@pytest.mark.parametrize("mode", MODES, ids=["lazy-up", "eager-up", "lazy-down", "eager-down"])
+@pytest.mark.parametrize("mode", [MODES[0], MODES[3]], ids=["lazy-up", "eager-down"])
 def test_gemm_small_tiles_ragged(hostmodel, tmp_path, mode):
     """128x128 configuration: 2x2 tiles, ragged in M and N, K = one, two and three steps (prologue
     and tail prefetch clamps), FP32 and BF16 output, padded C."""
@@ -304,8 +304,7 @@ def test_dequantize_tiled_scales(hostmodel, tmp_path):
 
 
 # ---- persistent GEMM kernel (opt-in through MXFP8_GEMM_PERSISTENT=<workgroups>) -------------------------
-@pytest.mark.parametrize("mode", [MODES[0], MODES[3]], ids=["lazy-up", "eager-down"])
-@pytest.mark.parametrize("tiled", [False, True], ids=["rowmajor", "tiled"])
+@pytest.mark.parametrize("mode,tiled", [(MODES[0], False), (MODES[3], True)], ids=["lazy-up-rowmajor", "eager-down-tiled"])
 def test_gemm_persistent_small_tiles(hostmodel, tmp_path, mode, tiled):
     """Workgroups that walk over 3, 2 and 1 tiles (6 tiles of 128x128 on 2, 4 and 6 workgroups), K of
     2 and 3 steps: the K pipeline runs across tile boundaries, each tile is stored once."""
@@ -319,14 +318,18 @@ def test_gemm_persistent_small_tiles(hostmodel, tmp_path, mode, tiled):
         _check_gemm(out, M, N, N, ops, bf16)
 
 
-def test_gemm_persistent_large_tiles_sampled_workgroups(hostmodel, tmp_path):
-    """256x256 configuration: 128 tiles on 64 workgroups (2 tiles each); first and last workgroup."""
-    M, N, K = 2048, 4096, 256
+@pytest.mark.parametrize("tune", [0, 1, 2, 3, 5, 6])
+def test_gemm_persistent_large_tiles_sampled_workgroups(hostmodel, tmp_path, tune):
+    """256x256 configuration: 128 tiles on 64 workgroups (2 tiles each); first and last workgroup for the
+    default schedule, the last one for each schedule variant (MXFP8_GEMM_TUNE)."""
+    M, N, K = 2048, 4096, 384
     ops = _operands(M, N, K, seed=90, spikes=True)
     line, out = _gemm_case(tmp_path, M, N, K, ops, bf16=True, tiled=True)
-    _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=64, WAVESIM_BLOCKS=2)
-    assert calls[0] == (0, [0, 63])
-    assert _check_gemm(out, M, N, N, ops, True, expect_full=False) == 4 * 256 * 256
+    blocks = 2 if tune == 0 else 1
+    _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=64, MXFP8_GEMM_TUNE=tune,
+                        WAVESIM_BLOCKS=blocks, WAVESIM_ORDER="down" if tune % 2 else "up")
+    assert calls[0] == (0, [0, 63] if tune == 0 else [0])
+    assert _check_gemm(out, M, N, N, ops, True, expect_full=False) == 2 * blocks * 256 * 256
 
 
 def test_gemm_persistent_falls_back_for_ragged_shapes(hostmodel, tmp_path):
