@@ -200,7 +200,7 @@ def test_encoder_ties_saturation_sign():
     assert enc(400.0) == 0x7C                # halfway between 384 (0x7C) and 416 (0x7D)
     for big in (448.0000001, 464.0, 480.0, 1e30, float("inf")):
         assert enc(big) == 0x7E and enc(-big) == 0xFE
-    assert enc(float("nan")) == 0x7F
+    assert enc(float("nan")) == 0x7F and enc(-float("nan")) == 0x7F   # one canonical NaN byte (reading R5)
     assert enc(1.0) == 0x38 and enc(1.0625) == 0x38 and enc(1.1875) == 0x3A  # ties to even mantissa
 
 
@@ -291,6 +291,10 @@ def test_leading_dimension_is_honoured():
     q, s = oracle.quantize_rowwise(view)
     q2, s2 = oracle.quantize_rowwise(np.ascontiguousarray(view))
     assert np.array_equal(q, q2) and np.array_equal(s, s2)
+    for v in (view, si.to_bf16_bits(x)[:, 32:96]):
+        qT, sT = oracle.quantize_colwise(v)
+        qT2, sT2 = oracle.quantize_colwise(np.ascontiguousarray(v))
+        assert np.array_equal(qT, qT2) and np.array_equal(sT, sT2)
 
 
 def test_special_blocks():
