@@ -196,7 +196,7 @@ def main():
             try:
                 out[name + "_tflops_persistent"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(rowmajor, mx.SCALES_ROWMAJOR))))
                 out[name + "_tflops_tiled_persistent"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(tiled_ops, lay))))
-                for tune in (1, 2, 3, 5, 6):          # schedule variants of the persistent K step
+                for tune in (1, 2, 3, 4, 5, 6):          # schedule variants of the persistent K step
                     os.environ["MXFP8_GEMM_TUNE"] = str(tune)
                     out[f"{name}_tflops_tiled_persistent_tune{tune}"] = tf(timed_ms(
                         lambda: mx.mxfp8_gemm_ex(*mk(tiled_ops, lay))))

@@ -332,6 +332,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 // a step before its A requests and all of them before the last MFMA column: the wait counts rely on it.
 template <int ID> struct GemmTune {
     static_assert(ID >= 0 && ID <= 6, "known variant");
+    // B(k+1) is awaited together with A(k+1) at the barrier before the last MFMA column, so that the first
+    // B fragments of the next step can be read during that column instead of after the end-of-step barrier
+    static constexpr bool EARLY_B = ID == 4;
     static constexpr int NFB = ID == 2 ? 2 : ID == 3 ? 4 : 3;  // B fragment register sets (read NFB-1 columns ahead)
     static constexpr bool SPREAD = ID == 1;                    // one B request per 2 MFMAs, then one A request per 4
     static constexpr int POLICY = ID == 5 ? 1 : ID == 6 ? 2 : 0;  // cache-policy bits of the tile loads (see dma_load)
@@ -438,6 +441,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
     v8i fa[TM];
     int sa[TM];
+    v8i fb_carry[2];  // Tune::EARLY_B: the first two B fragments of the next step, read during the last column
+    int sb_carry[2];
 
     // One K step, same schedule as in the kernel above; the requests go to the sources handed in:
     // (b_src, bs_src) = B tile and scales of the workgroup's NEXT step, (a_src, as_src) = A tile and
@@ -452,10 +457,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         constexpr int NFB = Tune::NFB;
         v8i fb[NFB];
         int sb[NFB];
+        static_assert(!Tune::EARLY_B || (NFB == 3 && TN >= 3), "two carried fragments");
 #pragma unroll
         for (int j = 0; j < NFB - 1 && j < TN; ++j) {
-            fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
-            sb[j] = sbbuf[b_soff + j * 64];
+            if constexpr (Tune::EARLY_B) {
+                fb[j] = fb_carry[j];
+                sb[j] = sb_carry[j];
+            } else {
+                fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
+                sb[j] = sbbuf[b_soff + j * 64];
+            }
         }
         MXFP8_PIN();
         int a_slot = 0;
@@ -466,7 +477,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 sb[(j + NFB - 1) % NFB] = sbbuf[b_soff + (j + NFB - 1) * 64];
             }
             if (j == TN - 1) {
-                MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);
+                MXFP8_WAIT_VMCNT(Tune::EARLY_B ? Cfg::NA : Cfg::NA + Cfg::NB);
                 MXFP8_BARRIER();
             }
             MXFP8_PIN();
@@ -495,12 +506,19 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 if (j == TN - 1) {
                     fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
                     sa[i] = sanext[a_soff + i * 64];
+                    if constexpr (Tune::EARLY_B) {
+                        if (i < 2) {  // B buffer nxt holds B(k+1) since the barrier above
+                            fb_carry[i] = read_frag(lds + Cfg::B_OFF + nxt * Cfg::B_BYTES, b_off0 + i * 2048, b_off1 + i * 2048);
+                            sb_carry[i] = (lds + Cfg::SB_OFF + nxt * Cfg::BN * 4)[b_soff + i * 64];
+                        }
+                    }
                 }
                 MXFP8_PIN();
             }
         }
-        MXFP8_WAIT_VMCNT(Cfg::NA);
-        MXFP8_BARRIER();
+        if constexpr (!Tune::EARLY_B)
+            MXFP8_WAIT_VMCNT(Cfg::NA);
+        MXFP8_BARRIER();  // (EARLY_B: nobody requests B(k+2) into a buffer that a slower wavefront still reads)
     };
 
     Tile cur_tile = tile_at(0);
@@ -520,6 +538,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     for (int i = 0; i < TM; ++i) {
         fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
         sa[i] = (lds + Cfg::SA_OFF)[a_soff + i * 64];
+    }
+    if constexpr (Tune::EARLY_B) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            fb_carry[j] = read_frag(lds + Cfg::B_OFF, b_off0 + j * 2048, b_off1 + j * 2048);
+            sb_carry[j] = (lds + Cfg::SB_OFF)[b_soff + j * 64];
+        }
     }
     __syncthreads();
 
@@ -640,6 +665,7 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
             case 1: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<1>>);
             case 2: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<2>>);
             case 3: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<3>>);
+            case 4: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<4>>);
             case 5: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<5>>);
             case 6: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<6>>);
             default: break;
