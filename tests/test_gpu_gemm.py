@@ -300,16 +300,16 @@ def test_full_size_layer_on_sampled_rows(pass_):
     assert torch.isfinite(c).all()
 
 
-@pytest.mark.parametrize("name,H,O", [("qkv", 4096, 6144), ("attn_out", 4096, 4096), ("gate_up", 4096, 28672),
-                                      ("down", 14336, 4096)])
-def test_transformer_layer_linear_set_forward_on_sampled_rows(name, H, O):
+@pytest.mark.parametrize("index,name,H,O", [(0, "qkv", 4096, 6144), (1, "attn_out", 4096, 4096),
+                                            (2, "gate_up", 4096, 28672), (3, "down", 14336, 4096)])
+def test_transformer_layer_linear_set_forward_on_sampled_rows(index, name, H, O):
     """The four linear layers of an 8B-class transformer block at 16384 tokens (QKV with 32 query and
     8 key/value heads of 128, attention output, fused gate+up, down projection): forward product from
     BF16 tensors quantized on the GPU, BF16 output, checked on sampled rows against the oracle, which
     quantizes only what it needs (the sampled token rows and the whole weight)."""
     T = 16384
-    x = si.activations(T, H, seed=6)
-    w = si.weights(O, H, seed=7)
+    x = si.activations(T, H, seed=10 + index)          # seeds 10 + layer index (activations), 20 + index (weights)
+    w = si.weights(O, H, seed=20 + index)
     to = lambda t: _dev(t.view(np.int16)).view(torch.bfloat16)
     A, B = mx.quantize(to(x), "rowwise"), mx.quantize(to(w), "rowwise")
     c = mx.gemm("fprop", A["q_row"], A["s_row"], B["q_row"], B["s_row"], torch.bfloat16)
