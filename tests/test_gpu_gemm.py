@@ -325,3 +325,33 @@ def test_transformer_layer_linear_set_forward_on_sampled_rows(index, name, H, O)
     _compare(got.astype(np.float64), ref, absref, TARGET_ELEM, None, f"16384-token {name} {H}->{O}", bf16=True,
              extra=extra)
     assert torch.isfinite(c.float()).all()
+
+
+@pytest.mark.parametrize("pass_", ["dgrad", "wgrad"])
+def test_transformer_layer_gate_up_backward_on_sampled_rows(pass_):
+    """Backward products of the widest layer of the 16384-token set (gate+up, 4096 -> 28672): the
+    activation gradient reduces over 28672, the weight gradient over the 16384 tokens. The oracle
+    quantizes the sampled rows of the first operand and the whole second operand itself."""
+    T, H, O, index = 16384, 4096, 28672, 2
+    to = lambda t: _dev(t.view(np.int16)).view(torch.bfloat16)
+    dy = si.gradients(T, O, seed=30 + index, spikes=True, bf16=True)
+    if pass_ == "dgrad":
+        w = si.weights(O, H, seed=20 + index)
+        A, B = mx.quantize(to(dy), "rowwise"), mx.quantize(to(w), "colwise")
+        c = mx.gemm("dgrad", A["q_row"], A["s_row"], B["q_colT"], B["s_colT"], torch.bfloat16)       # [T x H]
+        rows = np.array(sorted({0, 255, 256, T // 2, T - 257, T - 1}))
+        a_q, a_s = oracle.quantize_rowwise(np.ascontiguousarray(dy[rows]))
+        b_q, b_s = oracle.quantize_colwise(w)                                                        # [H x O]
+    else:
+        x = si.activations(T, H, seed=10 + index)
+        A, B = mx.quantize(to(dy), "colwise"), mx.quantize(to(x), "colwise")
+        c = mx.gemm("wgrad", A["q_colT"], A["s_colT"], B["q_colT"], B["s_colT"], torch.bfloat16)     # [O x H]
+        rows = np.array(sorted({0, 255, 256, O // 2, O - 257, O - 1}))
+        a_q, a_s = oracle.quantize_colwise(np.ascontiguousarray(dy[:, rows]))                        # [rows x T]
+        b_q, b_s = oracle.quantize_colwise(x)                                                        # [H x T]
+    torch.cuda.synchronize()
+    ref, absref = oracle.gemm_rows(a_q, a_s, b_q, b_s, np.arange(len(rows)))
+    got = si.bf16_bits_to_f32(c[torch.from_numpy(rows).cuda()].view(torch.int16).cpu().numpy().view(np.uint16))
+    _compare(got.astype(np.float64), ref, absref, TARGET_ELEM, None, f"16384-token gate+up {pass_}", bf16=True,
+             extra=hw_tolerance(a_q, a_s, b_q, b_s))
+    assert torch.isfinite(c.float()).all()
