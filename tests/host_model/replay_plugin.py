@@ -4,6 +4,7 @@ libmxfp8.so, and placing tensors on "cuda" becomes a no-op, so the very same tes
 same kernel sources on the CPU execution model. Used by tests/test_host_model_replay.py; it checks the
 test code and the kernels' logic, not the hardware (timing, the matrix instruction's internal rounding)."""
 import os
+import types
 
 import torch
 
@@ -14,6 +15,7 @@ binding._need_cuda = lambda *tensors: None
 binding._stream = lambda stream: None
 torch.Tensor.cuda = lambda self, *a, **k: self
 torch.cuda.synchronize = lambda *a, **k: None
+torch.cuda.current_stream = lambda *a, **k: types.SimpleNamespace(cuda_stream=0)
 
 
 def _on_cpu(fn):
