@@ -4,7 +4,8 @@ copy of the GEMM kernel source -- a removed barrier, a wait count that is one to
 a swizzle mismatch, a prefetch into the wrong buffer or of the wrong K step, a missing ragged-tile clamp,
 a wrong output row -- builds the host model from it and runs a few products against the oracle in all
 four scheduling modes (lazy / eager DMA completion, either wavefront running ahead). Every mutant must
-be caught, by a wrong or NaN result or by the model's range check."""
+be caught, by a wrong or NaN result or by the model's range check. Arguments, if any, select the mutants
+whose description contains one of them."""
 import os
 import shutil
 import subprocess
@@ -44,6 +45,23 @@ MUTANTS = [  # (description, old text, new text): first occurrence, i.e. in the 
     ("epilogue stores to the rows of another wavefront", "const int m = m0 + wm * Cfg::WM + i * 16 + r16;",
      "const int m = m0 + wn * Cfg::WM + i * 16 + r16;"),
 ]
+# the same kinds of mistake in the persistent kernel (last occurrence of the text; run with several tiles per workgroup)
+PERSISTENT_MUTANTS = [
+    ("persistent: barrier before the last MFMA column removed",
+     "                MXFP8_WAIT_VMCNT(Tune::EARLY_B ? Cfg::NA : Cfg::NA + Cfg::NB);\n                MXFP8_BARRIER();",
+     "                MXFP8_WAIT_VMCNT(Tune::EARLY_B ? Cfg::NA : Cfg::NA + Cfg::NB);"),
+    ("persistent: end-of-step wait one request too loose", "            MXFP8_WAIT_VMCNT(Cfg::NA);\n        MXFP8_BARRIER();",
+     "            MXFP8_WAIT_VMCNT(Cfg::NA + 1);\n        MXFP8_BARRIER();"),
+    ("persistent: barrier at the end of the K step removed",
+     "        MXFP8_BARRIER();  // (EARLY_B: nobody requests", "        // (EARLY_B: nobody requests"),
+    ("persistent: next tile's B fetched one K step late", "                b_src = next_tile.b;\n", "                b_src = next_tile.b + BK;\n"),
+    ("persistent: next tile's first A step fetched from the current tile",
+     "                a_src = next_tile.a + (int64_t)(kt + 2 - KT) * BK;", "                a_src = cur_tile.a + (int64_t)(kt + 2 - KT) * BK;"),
+    ("persistent: accumulators not cleared between tiles", "                acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};\n        cur_tile = next_tile;",
+     "                ;\n        cur_tile = next_tile;"),
+    ("persistent: buffer parity not carried across tiles", "            step(par, b_src, bs_src, a_src, as_src);\n            par ^= 1;",
+     "            step(kt & 1, b_src, bs_src, a_src, as_src);\n            par ^= 1;"),
+]
 MODES = [{}, {"WAVESIM_ORDER": "down"}, {"WAVESIM_DMA": "eager"}, {"WAVESIM_DMA": "eager", "WAVESIM_ORDER": "down"}]
 
 
@@ -64,8 +82,8 @@ def build(work, gemm_text):
     return binary
 
 
-def caught(binary, work):
-    for M, N, K in [(256, 256, 512), (200, 136, 384), (2048, 4096, 512)]:
+def caught(binary, work, persistent=0):
+    for M, N, K in ([(256, 384, 384), (2048, 4096, 384)] if persistent else [(256, 256, 512), (200, 136, 384), (2048, 4096, 512)]):
         rng = np.random.default_rng(M + N)
         a = rng.standard_normal((M, K)).astype(np.float32)
         b = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
@@ -78,7 +96,10 @@ def caught(binary, work):
         case = os.path.join(work, "case.txt")
         open(case, "w").write(f"gemm 0 {M} {N} {K} f32 {N} {' '.join(names)} {out}\n")
         for mode in MODES:
-            r = subprocess.run([binary, case], capture_output=True, text=True, env=dict(os.environ, WAVESIM_BLOCKS="2", **mode))
+            env = dict(os.environ, WAVESIM_BLOCKS="2", **mode)
+            if persistent:      # 6 small tiles on 2 workgroups, 128 large tiles on 64: K = 3 steps (odd: parity flips per tile)
+                env["MXFP8_GEMM_PERSISTENT"] = "2" if M == 256 else "64"
+            r = subprocess.run([binary, case], capture_output=True, text=True, env=env)
             if r.returncode != 0:
                 return f"model stopped: {r.stderr.strip().splitlines()[-1][:100]}"
             c = np.fromfile(out, np.uint32).reshape(M, N)
@@ -95,11 +116,23 @@ def caught(binary, work):
 def main():
     source = open(os.path.join(ROOT, "paper_2506_08027_amd", "csrc", "gemm.hip")).read()
     survivors = 0
-    for desc, old, new in [("(unmutated source: must pass)", "", "")] + MUTANTS:
+    todo = [("(unmutated source: must pass)", "", "", 0), ("(unmutated source, persistent kernel: must pass)", "", "", 1)]
+    todo += [m + (0,) for m in MUTANTS] + [m + (1,) for m in PERSISTENT_MUTANTS]
+    only = sys.argv[1:]
+    for desc, old, new, persistent in todo:
+        if only and not any(o in desc for o in only):
+            continue
         assert old == "" or old in source, desc
         work = tempfile.mkdtemp(prefix="kmut_")
         try:
-            how = caught(build(work, source.replace(old, new, 1) if old else source), work)
+            if old == "":
+                text = source
+            elif persistent:
+                at = source.rindex(old)
+                text = source[:at] + new + source[at + len(old):]
+            else:
+                text = source.replace(old, new, 1)
+            how = caught(build(work, text), work, persistent)
         finally:
             shutil.rmtree(work, ignore_errors=True)
         ok = (how is None) if old == "" else (how is not None)
