@@ -62,6 +62,16 @@ def _load():
     lib.mxo_dequantize_f32.argtypes = [u8p, u8p, i64, i64, vp, i64]
     lib.mxo_dequantize_bf16.restype = None
     lib.mxo_dequantize_bf16.argtypes = [u8p, u8p, i64, i64, vp, i64]
+    lib.mxo_e5m2_decode.restype = ctypes.c_double
+    lib.mxo_e5m2_decode.argtypes = [ctypes.c_uint8]
+    lib.mxo_e5m2_encode.restype = ctypes.c_uint8
+    lib.mxo_e5m2_encode.argtypes = [ctypes.c_double]
+    lib.mxo_scale_byte_mode.restype = ctypes.c_int
+    lib.mxo_scale_byte_mode.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_int]
+    lib.mxo_quantize_rowwise_mode_f32.restype = None
+    lib.mxo_quantize_rowwise_mode_f32.argtypes = [vp, i64, i64, i64, u8p, u8p, ctypes.c_int, ctypes.c_int]
+    lib.mxo_dequantize_mode_f64.restype = None
+    lib.mxo_dequantize_mode_f64.argtypes = [u8p, u8p, i64, i64, vp, ctypes.c_int]
     lib.mxo_gemm_rows_f64.restype = ctypes.c_int
     lib.mxo_gemm_rows_f64.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, i64, vp, vp]
     _lib = lib
@@ -181,3 +191,44 @@ def gemm_rows(a_q, a_s, b_q, b_s, rows):
 def gemm(a_q, a_s, b_q, b_s):
     """All of C = A * B^T (see gemm_rows)."""
     return gemm_rows(a_q, a_s, b_q, b_s, np.arange(np.asarray(a_q).shape[0]))
+
+
+# ---- ablation arms of the paper (E5M2 elements, OCP v1 scale rule): not part of the recipe ----------
+_FMT = {"e4m3": 0, "e5m2": 1}
+_RULE = {"up": 0, "ocp": 1}
+
+
+def e5m2_decode(code: int) -> float:
+    return _load().mxo_e5m2_decode(int(code))
+
+
+def e5m2_encode(t: float) -> int:
+    return _load().mxo_e5m2_encode(float(t))
+
+
+def scale_byte_mode(amax: float, fmt: str = "e4m3", rule: str = "up") -> int:
+    """Scale byte under the element format and the scale rule ('up' = Algorithm 1, 'ocp' = OCP v1)."""
+    return _load().mxo_scale_byte_mode(float(amax), _FMT[fmt], _RULE[rule])
+
+
+def quantize_rowwise_mode(src: np.ndarray, fmt: str = "e4m3", rule: str = "up"):
+    """Row-wise quantization of an FP32 tensor under (fmt, rule): (q, s) like quantize_rowwise."""
+    kind, ld = _check_src(src)
+    if kind != "f32":
+        raise TypeError("FP32 source only")
+    rows, cols = src.shape
+    if cols % K_BLOCK:
+        raise ValueError("cols must be a multiple of 32")
+    q = np.empty((rows, cols), np.uint8)
+    s = np.empty((rows, cols // K_BLOCK), np.uint8)
+    _load().mxo_quantize_rowwise_mode_f32(src.ctypes.data, rows, cols, ld, _u8(q), _u8(s), _FMT[fmt], _RULE[rule])
+    return q, s
+
+
+def dequantize_mode(q: np.ndarray, s: np.ndarray, fmt: str = "e4m3") -> np.ndarray:
+    """Decoded values under the element format, in double."""
+    _check_qs(q, s)
+    rows, cols = q.shape
+    out = np.empty((rows, cols), np.float64)
+    _load().mxo_dequantize_mode_f64(_u8(q), _u8(s), rows, cols, out.ctypes.data, _FMT[fmt])
+    return out

@@ -278,6 +278,126 @@ void mxo_dequantize_bf16(const uint8_t *q, const uint8_t *s, int64_t rows, int64
     }
 }
 
+/* ---- Ablation arms (Section 3.1 / Table 1: E5M2 elements; Section 3.3: the OCP v1 scale rule). ----
+ * Separate code paths on purpose: the functions above are the recipe and stay untouched. */
+
+/* E5M2 (Table 1): 1 sign, 5 exponent (bias 15), 2 mantissa bits, IEEE-style specials: exponent field
+ * 31 is Inf (mantissa 0) or NaN; max normal 1.75 * 2^15, min subnormal 2^-16. */
+double mxo_e5m2_decode(uint8_t code)
+{
+    int sign = code >> 7;
+    int e = (code >> 2) & 0x1F;
+    int m = code & 0x3;
+    double v;
+    if (e == 0x1F)
+        return m ? NAN : (sign ? -INFINITY : INFINITY);
+    if (e == 0)
+        v = ldexp((double)m, -16);
+    else
+        v = ldexp(1.0 + (double)m / 4.0, e - 15);
+    return sign ? -v : v;
+}
+
+/* Nearest finite E5M2 value, ties to the even code, saturating at +-57344 (code 0x7B); NaN -> 0x7F. */
+uint8_t mxo_e5m2_encode(double t)
+{
+    uint8_t sign = signbit(t) ? 0x80 : 0x00;
+    double a = fabs(t);
+    int best = 0;
+    double best_d;
+    int c;
+    if (isnan(t))
+        return 0x7F;
+    if (a > 57344.0)
+        return (uint8_t)(sign | 0x7B);
+    best_d = a;
+    for (c = 1; c <= 0x7B; ++c) {
+        double d = fabs(a - mxo_e5m2_decode((uint8_t)c));
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best_d = d;
+            best = c;
+        }
+    }
+    return (uint8_t)(sign | best);
+}
+
+static double fmt_max(int fmt) { return fmt ? 57344.0 : 448.0; }
+static int fmt_emax(int fmt) { return fmt ? 15 : 8; }
+
+/* Scale byte for element format fmt (0 = E4M3, 1 = E5M2) under rule 0 (Algorithm 1: smallest n with
+ * amax <= max * 2^n) or rule 1 (OCP v1: n = floor(log2(amax)) - emax of the element format, i.e. the
+ * ratio rounded DOWN to a power of two), clamped to [-127, 127]; found by loops, no logarithm. */
+int mxo_scale_byte_mode(double amax, int fmt, int rule)
+{
+    int n;
+    if (isnan(amax))
+        return 0xFF;
+    if (rule == 0) {
+        for (n = -127; n < 127; ++n)
+            if (amax <= ldexp(fmt_max(fmt), n))
+                break;
+    } else {
+        /* largest n with 2^(n + emax) <= amax */
+        for (n = 127; n > -127; --n)
+            if (ldexp(1.0, n + fmt_emax(fmt)) <= amax)
+                break;
+    }
+    return n + 127;
+}
+
+static uint8_t encode_fmt(double t, int fmt) { return fmt ? mxo_e5m2_encode(t) : mxo_e4m3_encode(t); }
+static double decode_fmt(uint8_t q, int fmt) { return fmt ? mxo_e5m2_decode(q) : mxo_e4m3_decode(q); }
+
+/* Row-wise quantization of an FP32 tensor under (fmt, rule); NaN blocks as in the recipe. */
+void mxo_quantize_rowwise_mode_f32(const float *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *q,
+                                   uint8_t *s, int fmt, int rule)
+{
+    int64_t nb = cols / MX_K;
+    int64_t r;
+#pragma omp parallel for schedule(static)
+    for (r = 0; r < rows; ++r) {
+        int64_t b;
+        for (b = 0; b < nb; ++b) {
+            const float *v = src + r * ld + b * MX_K;
+            uint8_t *qq = q + r * cols + b * MX_K;
+            double amax = 0.0;
+            int has_nan = 0, i, sb;
+            for (i = 0; i < MX_K; ++i) {
+                double a = fabs((double)v[i]);
+                if (isnan(a))
+                    has_nan = 1;
+                else if (a > amax)
+                    amax = a;
+            }
+            if (has_nan) {
+                s[r * nb + b] = 0xFF;
+                for (i = 0; i < MX_K; ++i)
+                    qq[i] = 0x7F;
+                continue;
+            }
+            sb = mxo_scale_byte_mode(amax, fmt, rule);
+            s[r * nb + b] = (uint8_t)sb;
+            for (i = 0; i < MX_K; ++i)
+                qq[i] = encode_fmt(ldexp((double)v[i], -(sb - 127)), fmt);
+        }
+    }
+}
+
+/* Decode under fmt to double. */
+void mxo_dequantize_mode_f64(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, double *dst, int fmt)
+{
+    int64_t nb = cols / MX_K;
+    int64_t r;
+#pragma omp parallel for schedule(static)
+    for (r = 0; r < rows; ++r) {
+        int64_t c;
+        for (c = 0; c < cols; ++c) {
+            uint8_t sb = s[r * nb + c / MX_K];
+            dst[r * cols + c] = sb == 0xFF ? NAN : ldexp(decode_fmt(q[r * cols + c], fmt), (int)sb - 127);
+        }
+    }
+}
+
 /* ---- Block-scaled matrix product (Section 2, Appendix A.3). -------------------------------- */
 
 /* C[m, n] = sum_k a[m, k] * b[n, k] over decoded operands (both K-contiguous), summed in plain k
