@@ -204,6 +204,11 @@ def main():
             finally:
                 os.environ.pop("MXFP8_GEMM_PERSISTENT", None)
                 os.environ.pop("MXFP8_GEMM_TUNE", None)
+        # forward product that also emits the row-wise MXFP8 copy of its BF16 output (next layer's operand)
+        Yq = torch.empty((T, O), **u8)
+        Ys = torch.empty(mx.mxfp8_scale_bytes(T, O, lay), **u8)
+        out["fprop_tflops_fused_output_quantize"] = tf(timed_ms(lambda: mx.mxfp8_gemm_quantize_ex(
+            mx.FPROP, Xt["q_row"], Xt["s_row"], Wt["q_row"], Wt["s_row"], Y, Yq, Ys, lay)))
         return out
 
     tiled = None

@@ -137,6 +137,22 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
                            void *hip_stream);
 
 /*
+ * mxfp8_gemm_ex with BF16 output AND, from the same pass, the row-wise MXFP8 copy of that output, i.e. the
+ * next layer's forward operand (Section 2: the FP32 result is re-quantized when it is needed in MX
+ * format; Section 3.3, Appendix A.1/A.2 for the conversion). c_bf16 [M x N] is the accumulator rounded
+ * to BF16 (RNE); cq_row [M x N], cs_row (scales of C as an [M x N] operand, `scale_layout`,
+ * mxfp8_scale_bytes(M, N)) are exactly what mxfp8_quantize_ex(c_bf16, BF16, M, N, ldc, ROWWISE) would
+ * give. The column-wise copy is not produced here. Requirements beyond mxfp8_gemm_ex: M and N multiples
+ * of the output tile (256 when ceil(M/256)*ceil(N/256) >= 128, else 128), K >= 256, c_bf16 16-byte
+ * aligned with ldc*2 a multiple of 16, cq_row and cs_row 16-byte aligned; anything else returns
+ * MXFP8_ERR_SHAPE / MXFP8_ERR_ALIGN.
+ */
+mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
+                                    const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
+                                    void *c_bf16, int64_t ldc, uint8_t *cq_row, uint8_t *cs_row,
+                                    mxfp8_scale_layout scale_layout, void *hip_stream);
+
+/*
  * Decode q [rows x cols], s [rows x cols/32] (dense, blocks along a row) to
  * dst[r, c] = E4M3(q[r, c]) * 2^(s[r, c/32] - 127) (Section 2), FP32 or BF16, leading dimension
  * ld_dst >= cols. The product is rounded once to the destination type (exact in FP32 unless it

@@ -54,6 +54,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_quantize_ex.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, vp, ci, vp]
     lib.mxfp8_gemm_ex.restype = ci
     lib.mxfp8_gemm_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, ci, vp]
+    lib.mxfp8_gemm_quantize_ex.restype = ci
+    lib.mxfp8_gemm_quantize_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp, ci, vp]
     lib.mxfp8_dequantize_ex.restype = ci
     lib.mxfp8_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
     lib.mxfp8_scale_bytes.restype = i64
@@ -165,6 +167,29 @@ def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, st
         raise MXFP8Error(rc, "mxfp8_gemm")
 
 
+def mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, cq_row, cs_row, scale_layout=SCALES_ROWMAJOR,
+                           stream=None) -> None:
+    """mxfp8_gemm_ex with bfloat16 c [M x N] plus the row-wise MXFP8 copy of c (cq_row [M x N], cs_row)."""
+    _need_cuda(a_q, a_s, b_q, b_s, c, cq_row, cs_row)
+    M, K = a_q.shape
+    N, Kb = b_q.shape
+    if K != Kb or c.dtype != torch.bfloat16 or tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
+        raise ValueError("c must be bfloat16 [M x N] with contiguous rows, operands must agree in K")
+    _check_scales(a_s, M, K, scale_layout, "a_s")
+    _check_scales(b_s, N, K, scale_layout, "b_s")
+    _check_scales(cs_row, M, N, scale_layout, "cs_row")
+    for t in (a_q, b_q, cq_row):
+        if not t.is_contiguous() or t.dtype != torch.uint8:
+            raise ValueError("element tensors must be dense uint8")
+    if tuple(cq_row.shape) != (M, N):
+        raise ValueError("cq_row must be [M x N]")
+    ldc = c.stride(0) if M > 1 else max(N, 1)
+    rc = load().mxfp8_gemm_quantize_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c), ldc,
+                                       _ptr(cq_row), _ptr(cs_row), scale_layout, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_gemm_quantize_ex")
+
+
 def mxfp8_dequantize(q, s, dst, stream=None) -> None:
     """dst [rows x cols] (float32/bfloat16) = E4M3(q) * 2^(s - 127), blocks along a row."""
     mxfp8_dequantize_ex(q, s, dst, SCALES_ROWMAJOR, stream)
@@ -216,6 +241,18 @@ def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES
     c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
     mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout)
     return c
+
+
+def gemm_quantize(pass_, a_q, a_s, b_q, b_s, scale_layout=SCALES_ROWMAJOR):
+    """Allocate and return (c bfloat16 [M x N], cq_row, cs_row) of mxfp8_gemm_quantize_ex."""
+    M, N = a_q.shape[0], b_q.shape[0]
+    u8 = dict(dtype=torch.uint8, device=a_q.device)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=a_q.device)
+    cq = torch.empty((M, N), **u8)
+    cs = torch.empty((mxfp8_scale_bytes(M, N, scale_layout),) if scale_layout != SCALES_ROWMAJOR
+                     else (M, N // K_BLOCK), **u8)
+    mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, cq, cs, scale_layout)
+    return c, cq, cs
 
 
 def dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):

@@ -13,6 +13,9 @@ hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, i
 hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
                        int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
                        hipStream_t stream);
+hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                             int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs,
+                             bool tiled_scales, hipStream_t stream);
 }  // namespace mxfp8
 
 namespace {
@@ -105,6 +108,33 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
     const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16,
                                             scale_layout == MXFP8_SCALES_TILED, ldc,
                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
+                                    const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c_bf16, int64_t ldc,
+                                    uint8_t *cq_row, uint8_t *cs_row, mxfp8_scale_layout scale_layout,
+                                    void *hip_stream)
+{
+    if (!valid_layout(scale_layout))
+        return MXFP8_ERR_MODE;
+    if (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD)
+        return MXFP8_ERR_MODE;
+    if (M < 0 || N < 0 || K < 0 || M > kMaxGemmMN || N > kMaxGemmMN || K > kMaxGemmK || K % 128 || K < 256 || ldc < N ||
+        M % 128 || N % 128 || ((M + 127) / 128) * ((N + 127) / 128) > kMaxDim)
+        return MXFP8_ERR_SHAPE;
+    if (M == 0 || N == 0)
+        return MXFP8_OK;
+    if (!c_bf16 || !cq_row || !cs_row || !a_q || !a_s || !b_q || !b_s)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(c_bf16) || (ldc * 2) % 16 || !aligned16(cq_row) || !aligned16(cs_row) || !aligned16(a_q) ||
+        !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_gemm_fused(a_q, a_s, b_q, b_s, M, N, K, c_bf16, ldc, cq_row, cs_row,
+                                                  scale_layout == MXFP8_SCALES_TILED,
+                                                  static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidConfiguration)  // the chosen tile does not divide M and N: nothing was launched
+        return MXFP8_ERR_SHAPE;
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

@@ -351,12 +351,18 @@ template <int ID> struct GemmTune {
 // Wait counts: the epilogue's stores also count in vmcnt. Loads complete in order among themselves,
 // so "at most n operations outstanding" still implies that all but the last n loads have landed,
 // whatever the stores do; the immediates of the K step stay valid (they can only wait longer).
-template <class Cfg, bool OUT_BF16, bool TILED, class Tune>
+// FUSE_Q (BF16 output only): the epilogue also emits the row-wise MXFP8 copy of the BF16-rounded output
+// tile (Section 2: the output is re-quantized when the next layer needs it in MX format; conversion of
+// Section 3.3 / Appendix A.1, A.2 applied to the BF16 values): cq [M x N] element bytes, cs the block
+// scales of C as an [M x N] operand, in the same scale layout as the inputs. A 32-column block lies in
+// two adjacent MFMA tiles of one row, 8 values in each of the 4 lanes that share the row.
+template <class Cfg, bool OUT_BF16, bool TILED, class Tune, bool FUSE_Q = false>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
-    int tiles_m, int tiles_n)
+    int tiles_m, int tiles_n, uint8_t *__restrict__ cq, uint8_t *__restrict__ cs)
 {
+    static_assert(!FUSE_Q || (OUT_BF16 && Cfg::TN % 2 == 0 && (Cfg::TN == 8 || Cfg::TN == 4)), "fused output quantization");
     static_assert(Cfg::SA_LOADS == 1 && Cfg::SB_LOADS == 1, "one scale request per wavefront and operand");
     MXFP8_DYNAMIC_LDS(lds);
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -595,6 +601,60 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 MXFP8_KEEP_IN_ACC(acc[i][j]);
+            if constexpr (FUSE_Q) {
+                const int64_t m = cur_tile.m0 + wm * Cfg::WM + i * 16 + r16;        // this lane's row of C
+                const int n_wave = cur_tile.n0 + wn * Cfg::WN;                       // first column of the wavefront
+                uint32_t scales = 0;                                                 // scale bytes of the row's blocks
+#pragma unroll
+                for (int blk = 0; blk < TN / 2; ++blk) {
+                    uint32_t h[4];  // BF16 pairs: columns 4g..4g+3 of tile 2*blk, then of tile 2*blk+1
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const v4f v = acc[i][2 * blk + t];
+                        v2bf p0 = {(__bf16)v[0], (__bf16)v[1]}, p1 = {(__bf16)v[2], (__bf16)v[3]};
+                        h[2 * t] = __builtin_bit_cast(uint32_t, p0);
+                        h[2 * t + 1] = __builtin_bit_cast(uint32_t, p1);
+                        *reinterpret_cast<uint2 *>(crow + lane_off + (2 * blk + t) * 16 * ESZ) = make_uint2(h[2 * t], h[2 * t + 1]);
+                    }
+                    // block amax on the magnitude bits: 8 values here, then the 3 other lanes of the row
+                    uint32_t am = pk_max_u16(pk_max_u16(h[0] & 0x7FFF7FFFu, h[1] & 0x7FFF7FFFu),
+                                             pk_max_u16(h[2] & 0x7FFF7FFFu, h[3] & 0x7FFF7FFFu));
+                    am = umax(am & 0xFFFFu, am >> 16);
+                    am = umax(am, (uint32_t)__shfl_xor((int)am, 16, 64));
+                    am = umax(am, (uint32_t)__shfl_xor((int)am, 32, 64));
+                    const uint32_t sb = scale_byte_from_bf16_bits(am);
+                    const float sc = scale_operand(sb);
+                    uint32_t q[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        q[t] = cvt2_bf16(cvt2_bf16(0, h[2 * t], sc, false), h[2 * t + 1], sc, true);
+                        if (sb >= 254) {  // NaN or Inf in the block: rare
+                            if (sb == 0xFF) {
+                                q[t] = 0x7F7F7F7Fu;
+                            } else {
+                                uint32_t f = 0;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const uint32_t bits = (e & 1) ? h[2 * t + e / 2] >> 16 : h[2 * t + e / 2] & 0xFFFFu;
+                                    f |= inf_byte_bf16(bits, (q[t] >> (8 * e)) & 0xFFu) << (8 * e);
+                                }
+                                q[t] = f;
+                            }
+                        }
+                        *reinterpret_cast<uint32_t *>(cq + m * N + n_wave + (2 * blk + t) * 16 + 4 * g) = q[t];
+                    }
+                    scales |= sb << (8 * blk);
+                }
+                if (g == 0) {  // the TN/2 scale bytes of this row and wavefront: one dword or halfword
+                    const int64_t nb = N / kBlock, b0 = n_wave / kBlock;
+                    uint8_t *sp = TILED ? cs + (((m >> 6) * ((nb + 3) / 4) + (b0 >> 2)) * 64 + (m & 63)) * 4 + (b0 & 3)
+                                        : cs + m * nb + b0;
+                    if constexpr (TN / 2 == 4)
+                        *reinterpret_cast<uint32_t *>(sp) = scales;
+                    else
+                        *reinterpret_cast<uint16_t *>(sp) = (uint16_t)scales;
+                }
+            } else {
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const v4f v = acc[i][j];
@@ -605,6 +665,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 } else {
                     *reinterpret_cast<float4 *>(crow + lane_off + j * 16 * ESZ) = make_float4(v[0], v[1], v[2], v[3]);
                 }
+            }
             }
             MXFP8_PIN();
         }
@@ -657,7 +718,7 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
             const int ntiles = tiles_m * tiles_n;
             hipLaunchKernelGGL(kern, dim3((unsigned)min(ntiles, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
                                stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m,
-                               tiles_n);
+                               tiles_n, static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr));
             return hipGetLastError();
         };
         if constexpr (Cfg::BM == 256 && TILED) {
@@ -706,6 +767,46 @@ hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_
     if (big)
         return launch_any<Big>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, stream);
     return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, stream);
+}
+
+// GEMM with BF16 output and the row-wise MXFP8 copy of that output from the same epilogue. Runs on the
+// persistent kernel, hence full tiles only: returns hipErrorInvalidConfiguration (nothing launched) when
+// M or N is not a multiple of the tile (256 when the problem has at least 128 such tiles, else 128) or K
+// has fewer than two steps.
+template <class Cfg, bool TILED>
+static hipError_t launch_fused_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                                   int M, int N, int K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs,
+                                   hipStream_t stream)
+{
+    const int64_t ldc_bytes = ldc * 2;
+    if (M % Cfg::BM || N % Cfg::BN || K < 2 * BK || ldc_bytes * Cfg::BM >= (int64_t(1) << 31))
+        return hipErrorInvalidConfiguration;
+    const int tiles_m = M / Cfg::BM, tiles_n = N / Cfg::BN;
+    const int requested = persistent_workgroups();
+    const int workgroups = requested > 0 ? requested : 256;  // one per compute unit of an MI355X
+    auto kern = gemm_persistent_kernel<Cfg, true, TILED, GemmTune<0>, true>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    if (e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)min(tiles_m * tiles_n, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
+                       stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, cq,
+                       cs);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                             int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs,
+                             bool tiled_scales, hipStream_t stream)
+{
+    using Big = GemmCfg<256, 256, 2, 2>;
+    using Small = GemmCfg<128, 128, 2, 2>;
+    const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
+    if (big)
+        return tiled_scales ? launch_fused_cfg<Big, true>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream)
+                            : launch_fused_cfg<Big, false>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream);
+    return tiled_scales ? launch_fused_cfg<Small, true>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream)
+                        : launch_fused_cfg<Small, false>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream);
 }
 
 }  // namespace mxfp8

@@ -215,3 +215,36 @@ def test_persistent_gemm_full_size_equals_ordinary_kernel():
             pers = mx.gemm(*args, scale_layout=lay)
         torch.cuda.synchronize()
         assert torch.equal(plain.view(torch.int16), pers.view(torch.int16))
+
+
+# ---- GEMM with the row-wise MXFP8 copy of its BF16 output from the same epilogue -------------------------
+@pytest.mark.parametrize("shape", [(256, 384, 384), (128, 128, 256), (2048, 4096, 512)])
+@pytest.mark.parametrize("tiled", [False, True])
+def test_fused_output_quantization_matches_gemm_then_quantize(shape, tiled):
+    """c must equal the plain BF16 product bit for bit, and (cq, cs) must be the oracle's row-wise
+    quantization of those BF16 values: NaN rows (a NaN scale), rows that overflow to Inf and ordinary rows."""
+    M, N, K = shape
+    a_q, a_s, b_q, b_s = _operands(M, N, K, seed=200 + M)
+    a_s = a_s.copy()
+    a_s[3, 1] = 0xFF                     # row 3 of C becomes NaN
+    a_s[5, :] = 250                      # row 5: many products overflow FP32, +-Inf in BF16
+    lay = TILED if tiled else mx.SCALES_ROWMAJOR
+    sc = (lambda s: _dev(sl.tile(s, filler=0xFF))) if tiled else _dev
+    args = ("fprop", _dev(a_q), sc(a_s), _dev(b_q), sc(b_s))
+    c, cq, cs = mx.gemm_quantize(*args, scale_layout=lay)
+    plain = mx.gemm(*args, torch.bfloat16, scale_layout=lay)
+    torch.cuda.synchronize()
+    assert torch.equal(c.view(torch.int16), plain.view(torch.int16))
+    bits = c.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert ((bits[3] & 0x7FFF) > 0x7F80).all() and ((bits[5] & 0x7FFF) == 0x7F80).any()   # NaN row, Inf entries
+    q, s = oracle.quantize_rowwise(np.ascontiguousarray(bits))
+    assert np.array_equal(cq.cpu().numpy(), q)
+    got_s = cs.cpu().numpy()
+    assert np.array_equal(sl.untile(got_s, M, N // 32) if tiled else got_s, s)
+
+
+def test_fused_output_quantization_rejects_partial_tiles():
+    a_q, a_s, b_q, b_s = _operands(200, 128, 256, seed=7)
+    with pytest.raises(mx.MXFP8Error) as e:
+        mx.gemm_quantize("fprop", _dev(a_q), _dev(a_s), _dev(b_q), _dev(b_s))
+    assert e.value.code == 2
