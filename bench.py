@@ -204,11 +204,13 @@ def main():
             finally:
                 os.environ.pop("MXFP8_GEMM_PERSISTENT", None)
                 os.environ.pop("MXFP8_GEMM_TUNE", None)
-        # forward product that also emits the row-wise MXFP8 copy of its BF16 output (next layer's operand)
-        Yq = torch.empty((T, O), **u8)
-        Ys = torch.empty(mx.mxfp8_scale_bytes(T, O, lay), **u8)
-        out["fprop_tflops_fused_output_quantize"] = tf(timed_ms(lambda: mx.mxfp8_gemm_quantize_ex(
-            mx.FPROP, Xt["q_row"], Xt["s_row"], Wt["q_row"], Wt["s_row"], Y, Yq, Ys, lay)))
+        # forward product that also emits the MXFP8 copies of its BF16 output (the next layer's operands)
+        Yt = tbufs(T, O)
+        for axis, key in ((mx.ROWWISE, "row"), (mx.BOTH, "both")):
+            out[f"fprop_tflops_fused_output_quantize_{key}"] = tf(timed_ms(lambda: mx.mxfp8_gemm_quantize_ex(
+                mx.FPROP, Xt["q_row"], Xt["s_row"], Wt["q_row"], Wt["s_row"], Y, axis, Yt["q_row"], Yt["s_row"],
+                Yt["q_colT"], Yt["s_colT"], lay)))
+        out["quantize_y_bf16_both_ms_tiled"] = timed_ms(lambda: mx.mxfp8_quantize_ex(Y, mx.BOTH, **Yt, scale_layout=lay))
         return out
 
     tiled = None

@@ -137,19 +137,22 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
                            void *hip_stream);
 
 /*
- * mxfp8_gemm_ex with BF16 output AND, from the same pass, the row-wise MXFP8 copy of that output, i.e. the
- * next layer's forward operand (Section 2: the FP32 result is re-quantized when it is needed in MX
- * format; Section 3.3, Appendix A.1/A.2 for the conversion). c_bf16 [M x N] is the accumulator rounded
- * to BF16 (RNE); cq_row [M x N], cs_row (scales of C as an [M x N] operand, `scale_layout`,
- * mxfp8_scale_bytes(M, N)) are exactly what mxfp8_quantize_ex(c_bf16, BF16, M, N, ldc, ROWWISE) would
- * give. The column-wise copy is not produced here. Requirements beyond mxfp8_gemm_ex: M and N multiples
- * of the output tile (256 when ceil(M/256)*ceil(N/256) >= 128, else 128), K >= 256, c_bf16 16-byte
- * aligned with ldc*2 a multiple of 16, cq_row and cs_row 16-byte aligned; anything else returns
- * MXFP8_ERR_SHAPE / MXFP8_ERR_ALIGN.
+ * mxfp8_gemm_ex with BF16 output AND, from the same pass, MXFP8 copies of that output, i.e. the next
+ * layer's operands (Section 2: the FP32 result is re-quantized when it is needed in MX format;
+ * Section 3.2 for the two axes; Section 3.3, Appendix A.1/A.2 for the conversion). c_bf16 [M x N] is the
+ * accumulator rounded to BF16 (RNE); the copies selected by `axis` are exactly what
+ * mxfp8_quantize_ex(c_bf16, BF16, M, N, ldc, axis, ...) would give:
+ *   cq_row  [M x N], cs_row  = scales of C   as an [M x N] operand (mxfp8_scale_bytes(M, N, layout))
+ *   cq_colT [N x M], cs_colT = scales of C^T as an [N x M] operand (mxfp8_scale_bytes(N, M, layout))
+ * Outputs not selected by `axis` are ignored and may be NULL. Requirements beyond mxfp8_gemm_ex: M and N
+ * multiples of the output tile (256 when ceil(M/256)*ceil(N/256) >= 128, else 128), K >= 256, c_bf16
+ * 16-byte aligned with ldc*2 a multiple of 16, every selected output 16-byte aligned; anything else
+ * returns MXFP8_ERR_SHAPE / MXFP8_ERR_ALIGN.
  */
 mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
                                     const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
-                                    void *c_bf16, int64_t ldc, uint8_t *cq_row, uint8_t *cs_row,
+                                    void *c_bf16, int64_t ldc, mxfp8_axis axis, uint8_t *cq_row,
+                                    uint8_t *cs_row, uint8_t *cq_colT, uint8_t *cs_colT,
                                     mxfp8_scale_layout scale_layout, void *hip_stream);
 
 /*

@@ -55,7 +55,7 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_gemm_ex.restype = ci
     lib.mxfp8_gemm_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, ci, vp]
     lib.mxfp8_gemm_quantize_ex.restype = ci
-    lib.mxfp8_gemm_quantize_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp, ci, vp]
+    lib.mxfp8_gemm_quantize_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, vp, vp, vp, vp, ci, vp]
     lib.mxfp8_dequantize_ex.restype = ci
     lib.mxfp8_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
     lib.mxfp8_scale_bytes.restype = i64
@@ -167,25 +167,30 @@ def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, st
         raise MXFP8Error(rc, "mxfp8_gemm")
 
 
-def mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, cq_row, cs_row, scale_layout=SCALES_ROWMAJOR,
-                           stream=None) -> None:
-    """mxfp8_gemm_ex with bfloat16 c [M x N] plus the row-wise MXFP8 copy of c (cq_row [M x N], cs_row)."""
-    _need_cuda(a_q, a_s, b_q, b_s, c, cq_row, cs_row)
+def mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, axis, cq_row=None, cs_row=None, cq_colT=None, cs_colT=None,
+                           scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """mxfp8_gemm_ex with bfloat16 c [M x N] plus the MXFP8 copies of c selected by `axis`:
+    cq_row [M x N] / cs_row and cq_colT [N x M] / cs_colT."""
+    _need_cuda(a_q, a_s, b_q, b_s, c, cq_row, cs_row, cq_colT, cs_colT)
     M, K = a_q.shape
     N, Kb = b_q.shape
     if K != Kb or c.dtype != torch.bfloat16 or tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
         raise ValueError("c must be bfloat16 [M x N] with contiguous rows, operands must agree in K")
     _check_scales(a_s, M, K, scale_layout, "a_s")
     _check_scales(b_s, N, K, scale_layout, "b_s")
-    _check_scales(cs_row, M, N, scale_layout, "cs_row")
-    for t in (a_q, b_q, cq_row):
+    ax = _AXIS[axis]
+    for want, q, s, rows, cols, what in ((ax & ROWWISE, cq_row, cs_row, M, N, "row"), (ax & COLWISE, cq_colT, cs_colT, N, M, "colT")):
+        if want and q is not None and s is not None:
+            if tuple(q.shape) != (rows, cols) or not q.is_contiguous() or q.dtype != torch.uint8:
+                raise ValueError(f"cq_{what} must be dense uint8 [{rows} x {cols}]")
+            _check_scales(s, rows, cols, scale_layout, f"cs_{what}")
+    for t in (a_q, b_q):
         if not t.is_contiguous() or t.dtype != torch.uint8:
             raise ValueError("element tensors must be dense uint8")
-    if tuple(cq_row.shape) != (M, N):
-        raise ValueError("cq_row must be [M x N]")
     ldc = c.stride(0) if M > 1 else max(N, 1)
     rc = load().mxfp8_gemm_quantize_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c), ldc,
-                                       _ptr(cq_row), _ptr(cs_row), scale_layout, _stream(stream))
+                                       ax, _ptr(cq_row), _ptr(cs_row), _ptr(cq_colT), _ptr(cs_colT), scale_layout,
+                                       _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_gemm_quantize_ex")
 
@@ -243,16 +248,23 @@ def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES
     return c
 
 
-def gemm_quantize(pass_, a_q, a_s, b_q, b_s, scale_layout=SCALES_ROWMAJOR):
-    """Allocate and return (c bfloat16 [M x N], cq_row, cs_row) of mxfp8_gemm_quantize_ex."""
+def gemm_quantize(pass_, a_q, a_s, b_q, b_s, axis="both", scale_layout=SCALES_ROWMAJOR):
+    """Allocate the outputs of mxfp8_gemm_quantize_ex and return them as a dict: 'c' (bfloat16 [M x N]) and,
+    as selected by `axis`, 'q_row', 's_row', 'q_colT', 's_colT' of c (same conventions as quantize)."""
     M, N = a_q.shape[0], b_q.shape[0]
+    ax = _AXIS[axis]
     u8 = dict(dtype=torch.uint8, device=a_q.device)
-    c = torch.empty((M, N), dtype=torch.bfloat16, device=a_q.device)
-    cq = torch.empty((M, N), **u8)
-    cs = torch.empty((mxfp8_scale_bytes(M, N, scale_layout),) if scale_layout != SCALES_ROWMAJOR
-                     else (M, N // K_BLOCK), **u8)
-    mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, cq, cs, scale_layout)
-    return c, cq, cs
+    tiled = scale_layout != SCALES_ROWMAJOR
+    out = {"c": torch.empty((M, N), dtype=torch.bfloat16, device=a_q.device)}
+    if ax & ROWWISE:
+        out["q_row"] = torch.empty((M, N), **u8)
+        out["s_row"] = torch.empty((mxfp8_scale_bytes(M, N, scale_layout),) if tiled else (M, N // K_BLOCK), **u8)
+    if ax & COLWISE:
+        out["q_colT"] = torch.empty((N, M), **u8)
+        out["s_colT"] = torch.empty((mxfp8_scale_bytes(N, M, scale_layout),) if tiled else (N, M // K_BLOCK), **u8)
+    mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, out["c"], ax, out.get("q_row"), out.get("s_row"),
+                           out.get("q_colT"), out.get("s_colT"), scale_layout)
+    return out
 
 
 def dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):

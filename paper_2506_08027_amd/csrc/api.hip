@@ -14,8 +14,8 @@ hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_
                        int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
                        hipStream_t stream);
 hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
-                             int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs,
-                             bool tiled_scales, hipStream_t stream);
+                             int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
+                             uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, hipStream_t stream);
 }  // namespace mxfp8
 
 namespace {
@@ -113,11 +113,14 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
 
 mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
                                     const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c_bf16, int64_t ldc,
-                                    uint8_t *cq_row, uint8_t *cs_row, mxfp8_scale_layout scale_layout,
-                                    void *hip_stream)
+                                    mxfp8_axis axis, uint8_t *cq_row, uint8_t *cs_row, uint8_t *cq_colT,
+                                    uint8_t *cs_colT, mxfp8_scale_layout scale_layout, void *hip_stream)
 {
     if (!valid_layout(scale_layout))
         return MXFP8_ERR_MODE;
+    if (axis != MXFP8_ROWWISE && axis != MXFP8_COLWISE && axis != MXFP8_BOTH)
+        return MXFP8_ERR_MODE;
+    const bool want_row = axis & MXFP8_ROWWISE, want_col = axis & MXFP8_COLWISE;
     if (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD)
         return MXFP8_ERR_MODE;
     if (M < 0 || N < 0 || K < 0 || M > kMaxGemmMN || N > kMaxGemmMN || K > kMaxGemmK || K % 128 || K < 256 || ldc < N ||
@@ -125,13 +128,15 @@ mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const u
         return MXFP8_ERR_SHAPE;
     if (M == 0 || N == 0)
         return MXFP8_OK;
-    if (!c_bf16 || !cq_row || !cs_row || !a_q || !a_s || !b_q || !b_s)
+    if (!c_bf16 || !a_q || !a_s || !b_q || !b_s || (want_row && (!cq_row || !cs_row)) ||
+        (want_col && (!cq_colT || !cs_colT)))
         return MXFP8_ERR_NULL;
-    if (!aligned16(c_bf16) || (ldc * 2) % 16 || !aligned16(cq_row) || !aligned16(cs_row) || !aligned16(a_q) ||
-        !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))
+    if (!aligned16(c_bf16) || (ldc * 2) % 16 || !aligned16(a_q) || !aligned16(a_s) || !aligned16(b_q) ||
+        !aligned16(b_s) || (want_row && (!aligned16(cq_row) || !aligned16(cs_row))) ||
+        (want_col && (!aligned16(cq_colT) || !aligned16(cs_colT))))
         return MXFP8_ERR_ALIGN;
-    const hipError_t e = mxfp8::launch_gemm_fused(a_q, a_s, b_q, b_s, M, N, K, c_bf16, ldc, cq_row, cs_row,
-                                                  scale_layout == MXFP8_SCALES_TILED,
+    const hipError_t e = mxfp8::launch_gemm_fused(a_q, a_s, b_q, b_s, M, N, K, c_bf16, ldc, (int)axis, cq_row, cs_row,
+                                                  cq_colT, cs_colT, scale_layout == MXFP8_SCALES_TILED,
                                                   static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidConfiguration)  // the chosen tile does not divide M and N: nothing was launched
         return MXFP8_ERR_SHAPE;

@@ -351,18 +351,27 @@ template <int ID> struct GemmTune {
 // Wait counts: the epilogue's stores also count in vmcnt. Loads complete in order among themselves,
 // so "at most n operations outstanding" still implies that all but the last n loads have landed,
 // whatever the stores do; the immediates of the K step stay valid (they can only wait longer).
-// FUSE_Q (BF16 output only): the epilogue also emits the row-wise MXFP8 copy of the BF16-rounded output
-// tile (Section 2: the output is re-quantized when the next layer needs it in MX format; conversion of
-// Section 3.3 / Appendix A.1, A.2 applied to the BF16 values): cq [M x N] element bytes, cs the block
-// scales of C as an [M x N] operand, in the same scale layout as the inputs. A 32-column block lies in
-// two adjacent MFMA tiles of one row, 8 values in each of the 4 lanes that share the row.
-template <class Cfg, bool OUT_BF16, bool TILED, class Tune, bool FUSE_Q = false>
+// FUSE_Q (BF16 output only; bit 0 = row-wise copy, bit 1 = column-wise copy): the epilogue also emits
+// MXFP8 copies of the BF16-rounded output tile (Section 2: the output is re-quantized when the next layer
+// needs it in MX format; Section 3.2: along rows and along columns; conversion of Section 3.3 /
+// Appendix A.1, A.2 applied to the BF16 values), scales in the same layout as the inputs.
+//   row-wise:    cq [M x N], cs = scales of C as an [M x N] operand. A 32-column block lies in two adjacent
+//                MFMA tiles of one row, 8 values in each of the 4 lanes that share the row.
+//   column-wise: cqT [N x M], csT = scales of C^T as an [N x M] operand. A 32-row block lies in two
+//                vertically adjacent MFMA tiles, 2 values in each of the 16 lanes of a DPP row. The bytes
+//                are transposed through the two LDS buffers that are idle between tiles (the B buffer the
+//                finished step read and the A buffer whose fragments already sit in registers) and leave
+//                as full lines of cqT.
+template <class Cfg, bool OUT_BF16, bool TILED, class Tune, int FUSE_Q = 0>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
-    int tiles_m, int tiles_n, uint8_t *__restrict__ cq, uint8_t *__restrict__ cs)
+    int tiles_m, int tiles_n, uint8_t *__restrict__ cq, uint8_t *__restrict__ cs, uint8_t *__restrict__ cqT,
+    uint8_t *__restrict__ csT)
 {
-    static_assert(!FUSE_Q || (OUT_BF16 && Cfg::TN % 2 == 0 && (Cfg::TN == 8 || Cfg::TN == 4)), "fused output quantization");
+    static_assert(!FUSE_Q || (OUT_BF16 && (Cfg::TN == 8 || Cfg::TN == 4) && Cfg::TM == Cfg::TN), "fused output quantization");
+    constexpr bool Q_ROW = (FUSE_Q & 1) != 0, Q_COL = (FUSE_Q & 2) != 0;
+    static_assert(!Q_COL || Cfg::BM * Cfg::BN <= 2 * Cfg::B_BYTES, "transposed tile fits the two idle buffers");
     static_assert(Cfg::SA_LOADS == 1 && Cfg::SB_LOADS == 1, "one scale request per wavefront and operand");
     MXFP8_DYNAMIC_LDS(lds);
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -591,6 +600,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         // the A fragments of the next tile. Rows are finished one after the other (pinned) so that the
         // converted values of only one row group are live at a time.
         constexpr int ESZ = OUT_BF16 ? 2 : 4;
+        if constexpr (Q_COL)
+            __syncthreads();  // every wavefront's fragment refills have left the A buffer that is reused below
         uint8_t *ctile = c + (int64_t)cur_tile.m0 * ldc_bytes + (int64_t)cur_tile.n0 * ESZ;
         const uint32_t lane_off = (uint32_t)(wm * Cfg::WM + r16) * (uint32_t)ldc_bytes + (uint32_t)(wn * Cfg::WN + 4 * g) * ESZ;
 #pragma unroll
@@ -601,7 +612,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 MXFP8_KEEP_IN_ACC(acc[i][j]);
-            if constexpr (FUSE_Q) {
+            if constexpr (Q_ROW) {
                 const int64_t m = cur_tile.m0 + wm * Cfg::WM + i * 16 + r16;        // this lane's row of C
                 const int n_wave = cur_tile.n0 + wn * Cfg::WN;                       // first column of the wavefront
                 uint32_t scales = 0;                                                 // scale bytes of the row's blocks
@@ -669,6 +680,88 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             }
             MXFP8_PIN();
         }
+        if constexpr (Q_COL) {
+            // Idle LDS between tiles: B buffer par^1 (read by the step that just ended) and A buffer par (its
+            // fragments are in registers). Transposed tile [column][BM row bytes]; the first half of the
+            // columns in the B buffer, the second half in the A buffer when one buffer is too small. The
+            // 16-byte chunk of a column line is XORed with (column / 4) so that the four lanes of a row,
+            // whose columns are 4 apart, write different banks.
+            constexpr bool SPLIT = Cfg::BM * Cfg::BN > Cfg::B_BYTES;
+            constexpr int COLS_PER_REGION = SPLIT ? Cfg::BN / 2 : Cfg::BN;
+            constexpr int CHUNKS = Cfg::BM / 16;  // 16-byte chunks per column line
+            uint8_t *region0 = lds + Cfg::B_OFF + (par ^ 1) * Cfg::B_BYTES;
+            uint8_t *region1 = lds + Cfg::A_OFF + par * Cfg::A_BYTES;
+            auto line_of = [&](int n_tile) __attribute__((always_inline)) {
+                return (SPLIT && n_tile >= COLS_PER_REGION ? region1 : region0) + (n_tile % COLS_PER_REGION) * Cfg::BM;
+            };
+            const int64_t nbT = M / kBlock;                                   // scale blocks per row of C^T
+            const int64_t bT0 = (cur_tile.m0 + wm * Cfg::WM) / kBlock;        // first row block of this wavefront
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    MXFP8_KEEP_IN_ACC(acc[i][j]);  // (see the row loop above)
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int n_tile = wn * Cfg::WN + j * 16 + 4 * g + 2 * half;  // columns n_tile and n_tile + 1
+                    uint8_t *line0 = line_of(n_tile), *line1 = line_of(n_tile + 1);
+                    const int sw0 = (n_tile >> 2) & (CHUNKS - 1);                 // same for n_tile + 1
+                    uint32_t scales0 = 0, scales1 = 0;
+#pragma unroll
+                    for (int rb = 0; rb < TM / 2; ++rb) {
+                        // rows r16 and 16 + r16 of the 32-row block, as BF16 pairs (column n_tile low, n_tile + 1 high)
+                        const v4f va = acc[2 * rb][j], vb = acc[2 * rb + 1][j];
+                        v2bf pa = {(__bf16)va[2 * half], (__bf16)va[2 * half + 1]}, pb = {(__bf16)vb[2 * half], (__bf16)vb[2 * half + 1]};
+                        const uint32_t xa = __builtin_bit_cast(uint32_t, pa), xb = __builtin_bit_cast(uint32_t, pb);
+                        uint32_t am = pk_max_u16(xa & 0x7FFF7FFFu, xb & 0x7FFF7FFFu);
+                        am = pk_max_u16(am, dpp_xor1(am));
+                        am = pk_max_u16(am, dpp_xor2(am));
+                        am = pk_max_u16(am, dpp_half_mirror(am));
+                        am = pk_max_u16(am, dpp_mirror(am));
+                        const uint32_t sb0 = scale_byte_from_bf16_bits(am & 0xFFFFu), sb1 = scale_byte_from_bf16_bits(am >> 16);
+                        // (row r16, row 16 + r16) of one column as a BF16 pair
+                        const uint32_t c0 = __builtin_amdgcn_perm(xb, xa, 0x05040100u), c1 = __builtin_amdgcn_perm(xb, xa, 0x07060302u);
+                        uint32_t q0 = cvt2_bf16(0, c0, scale_operand(sb0), false) & 0xFFFFu;
+                        uint32_t q1 = cvt2_bf16(0, c1, scale_operand(sb1), false) & 0xFFFFu;
+                        if (sb0 >= 254)
+                            q0 = sb0 == 0xFF ? 0x7F7Fu
+                                             : inf_byte_bf16(c0 & 0xFFFFu, q0 & 0xFFu) | (inf_byte_bf16(c0 >> 16, q0 >> 8) << 8);
+                        if (sb1 >= 254)
+                            q1 = sb1 == 0xFF ? 0x7F7Fu
+                                             : inf_byte_bf16(c1 & 0xFFFFu, q1 & 0xFFu) | (inf_byte_bf16(c1 >> 16, q1 >> 8) << 8);
+                        const int m_lo = wm * Cfg::WM + rb * 32 + r16, m_hi = m_lo + 16;  // rows inside the tile
+                        line0[(((m_lo >> 4) ^ sw0) << 4) + (m_lo & 15)] = (uint8_t)q0;
+                        line0[(((m_hi >> 4) ^ sw0) << 4) + (m_hi & 15)] = (uint8_t)(q0 >> 8);
+                        line1[(((m_lo >> 4) ^ sw0) << 4) + (m_lo & 15)] = (uint8_t)q1;
+                        line1[(((m_hi >> 4) ^ sw0) << 4) + (m_hi & 15)] = (uint8_t)(q1 >> 8);
+                        scales0 |= sb0 << (8 * rb);
+                        scales1 |= sb1 << (8 * rb);
+                    }
+                    if (r16 == 0) {  // the TM/2 scale bytes of two columns of C^T: a dword or halfword each
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const int64_t n = cur_tile.n0 + n_tile + t;
+                            uint8_t *sp = TILED ? csT + (((n >> 6) * ((nbT + 3) / 4) + (bT0 >> 2)) * 64 + (n & 63)) * 4 + (bT0 & 3)
+                                                : csT + n * nbT + bT0;
+                            if constexpr (TM / 2 == 4)
+                                *reinterpret_cast<uint32_t *>(sp) = t ? scales1 : scales0;
+                            else
+                                *reinterpret_cast<uint16_t *>(sp) = (uint16_t)(t ? scales1 : scales0);
+                        }
+                    }
+                }
+                MXFP8_PIN();
+            }
+            __syncthreads();  // the transposed tile is complete
+#pragma unroll
+            for (int pass = 0; pass < Cfg::BN * CHUNKS / Cfg::THREADS; ++pass) {
+                const int chunk = pass * Cfg::THREADS + tid;
+                const int n_tile = chunk / CHUNKS, part = chunk % CHUNKS;
+                const uint4 v = *reinterpret_cast<const uint4 *>(line_of(n_tile) + ((part ^ ((n_tile >> 2) & (CHUNKS - 1))) << 4));
+                *reinterpret_cast<uint4 *>(cqT + (int64_t)(cur_tile.n0 + n_tile) * M + cur_tile.m0 + part * 16) = v;
+            }
+            __syncthreads();  // nobody requests the next tiles into these buffers while they are still read
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -718,7 +811,8 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
             const int ntiles = tiles_m * tiles_n;
             hipLaunchKernelGGL(kern, dim3((unsigned)min(ntiles, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
                                stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m,
-                               tiles_n, static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr));
+                               tiles_n, static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr),
+                               static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr));
             return hipGetLastError();
         };
         if constexpr (Cfg::BM == 256 && TILED) {
@@ -769,14 +863,14 @@ hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_
     return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, stream);
 }
 
-// GEMM with BF16 output and the row-wise MXFP8 copy of that output from the same epilogue. Runs on the
-// persistent kernel, hence full tiles only: returns hipErrorInvalidConfiguration (nothing launched) when
-// M or N is not a multiple of the tile (256 when the problem has at least 128 such tiles, else 128) or K
-// has fewer than two steps.
-template <class Cfg, bool TILED>
+// GEMM with BF16 output and MXFP8 copies of that output (axis bit 0: row-wise, bit 1: column-wise) from
+// the same epilogue. Runs on the persistent kernel, hence full tiles only: returns
+// hipErrorInvalidConfiguration (nothing launched) when M or N is not a multiple of the tile (256 when the
+// problem has at least 128 such tiles, else 128) or K has fewer than two steps.
+template <class Cfg, bool TILED, int AXIS>
 static hipError_t launch_fused_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
-                                   int M, int N, int K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs,
-                                   hipStream_t stream)
+                                   int M, int N, int K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs, uint8_t *cqT,
+                                   uint8_t *csT, hipStream_t stream)
 {
     const int64_t ldc_bytes = ldc * 2;
     if (M % Cfg::BM || N % Cfg::BN || K < 2 * BK || ldc_bytes * Cfg::BM >= (int64_t(1) << 31))
@@ -784,29 +878,39 @@ static hipError_t launch_fused_cfg(const uint8_t *a_q, const uint8_t *a_s, const
     const int tiles_m = M / Cfg::BM, tiles_n = N / Cfg::BN;
     const int requested = persistent_workgroups();
     const int workgroups = requested > 0 ? requested : 256;  // one per compute unit of an MI355X
-    auto kern = gemm_persistent_kernel<Cfg, true, TILED, GemmTune<0>, true>;
+    auto kern = gemm_persistent_kernel<Cfg, true, TILED, GemmTune<0>, AXIS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
     if (e != hipSuccess)
         return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)min(tiles_m * tiles_n, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
                        stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, cq,
-                       cs);
+                       cs, cqT, csT);
     return hipGetLastError();
 }
 
+template <class Cfg, bool TILED, class... Args> static hipError_t launch_fused_axis(int axis, Args... args)
+{
+    switch (axis) {
+    case 1: return launch_fused_cfg<Cfg, TILED, 1>(args...);
+    case 2: return launch_fused_cfg<Cfg, TILED, 2>(args...);
+    default: return launch_fused_cfg<Cfg, TILED, 3>(args...);
+    }
+}
+
 hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
-                             int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs,
-                             bool tiled_scales, hipStream_t stream)
+                             int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
+                             uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, hipStream_t stream)
 {
     using Big = GemmCfg<256, 256, 2, 2>;
     using Small = GemmCfg<128, 128, 2, 2>;
     const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
+    const int m = (int)M, n = (int)N, k = (int)K;
     if (big)
-        return tiled_scales ? launch_fused_cfg<Big, true>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream)
-                            : launch_fused_cfg<Big, false>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream);
-    return tiled_scales ? launch_fused_cfg<Small, true>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream)
-                        : launch_fused_cfg<Small, false>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, ldc, cq, cs, stream);
+        return tiled_scales ? launch_fused_axis<Big, true>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream)
+                            : launch_fused_axis<Big, false>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream);
+    return tiled_scales ? launch_fused_axis<Small, true>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream)
+                        : launch_fused_axis<Small, false>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream);
 }
 
 }  // namespace mxfp8

@@ -35,6 +35,13 @@ __device__ __forceinline__ uint32_t dpp_half_mirror(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);
 }
 
+// row_mirror: lane i <-> 15-i inside a row of 16 lanes (after a reduction over each group of 8 this
+// delivers the other group)
+__device__ __forceinline__ uint32_t dpp_mirror(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true);
+}
+
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 
 // max of the two 16-bit halves, both halves at once (v_pk_max_u16)

@@ -72,14 +72,17 @@ def test_ex_entry_points_validate_the_layout(lib):
     assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, 9, None) == 5
     assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 96, FAKE, 0, 64, 1, None) == 2
     f = lib.mxfp8_gemm_quantize_ex
-    f.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, I64, P, P, ctypes.c_int, P]
+    f.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, I64, ctypes.c_int, P, P, P, P, ctypes.c_int, P]
     ok = (FAKE, FAKE, FAKE, FAKE)
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, FAKE, FAKE, 3, None) == 5
-    assert f(0, *ok, 200, 256, 256, FAKE, 256, FAKE, FAKE, 0, None) == 2          # M not a multiple of the tile
-    assert f(0, *ok, 256, 256, 128, FAKE, 256, FAKE, FAKE, 0, None) == 2          # fewer than two K steps
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, None, FAKE, 0, None) == 1
-    assert f(0, *ok, 256, 256, 256, FAKE, 260, FAKE, FAKE, 0, None) == 3          # ldc * 2 not a multiple of 16
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, FAKE, P(0x1004), 1, None) == 3
+    outs = (FAKE, FAKE, FAKE, FAKE)
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 3, *outs, 3, None) == 5           # layout
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 0, *outs, 0, None) == 5           # axis
+    assert f(0, *ok, 200, 256, 256, FAKE, 256, 3, *outs, 0, None) == 2           # M not a multiple of the tile
+    assert f(0, *ok, 256, 256, 128, FAKE, 256, 3, *outs, 0, None) == 2           # fewer than two K steps
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 1, None, FAKE, None, None, 0, None) == 1
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 2, None, None, FAKE, None, 0, None) == 1
+    assert f(0, *ok, 256, 256, 256, FAKE, 260, 3, *outs, 0, None) == 3           # ldc * 2 not a multiple of 16
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 1, FAKE, P(0x1004), None, None, 1, None) == 3
     d = lib.mxfp8_dequantize_ex
     d.argtypes = [P, P, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, P]
     assert d(FAKE, FAKE, 4, 64, FAKE, 0, 64, -1, None) == 5

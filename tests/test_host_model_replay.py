@@ -51,4 +51,4 @@ def test_opt_in_gpu_tests_pass_on_the_host_model(hostmodel_lib):
                "(quantize_tiled_matches_oracle and (shape1 or shape2)) or single_axis or dequantize_tiled or "
                "error_codes or (gemm_tiled_matches and (shape0 or shape2)) or (persistent_gemm_matches and shape0) or "
                "(fused and not shape2)")
-    assert n >= 17
+    assert n >= 25

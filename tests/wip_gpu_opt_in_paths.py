@@ -217,12 +217,13 @@ def test_persistent_gemm_full_size_equals_ordinary_kernel():
         assert torch.equal(plain.view(torch.int16), pers.view(torch.int16))
 
 
-# ---- GEMM with the row-wise MXFP8 copy of its BF16 output from the same epilogue -------------------------
+# ---- GEMM with the MXFP8 copies of its BF16 output from the same epilogue -------------------------------
 @pytest.mark.parametrize("shape", [(256, 384, 384), (128, 128, 256), (2048, 4096, 512)])
 @pytest.mark.parametrize("tiled", [False, True])
-def test_fused_output_quantization_matches_gemm_then_quantize(shape, tiled):
-    """c must equal the plain BF16 product bit for bit, and (cq, cs) must be the oracle's row-wise
-    quantization of those BF16 values: NaN rows (a NaN scale), rows that overflow to Inf and ordinary rows."""
+@pytest.mark.parametrize("axis", ["rowwise", "colwise", "both"])
+def test_fused_output_quantization_matches_gemm_then_quantize(shape, tiled, axis):
+    """c must equal the plain BF16 product bit for bit, and the copies must be the oracle's quantization of
+    those BF16 values: NaN rows (a NaN scale), rows with entries that overflow to Inf and ordinary rows."""
     M, N, K = shape
     a_q, a_s, b_q, b_s = _operands(M, N, K, seed=200 + M)
     a_s = a_s.copy()
@@ -231,16 +232,21 @@ def test_fused_output_quantization_matches_gemm_then_quantize(shape, tiled):
     lay = TILED if tiled else mx.SCALES_ROWMAJOR
     sc = (lambda s: _dev(sl.tile(s, filler=0xFF))) if tiled else _dev
     args = ("fprop", _dev(a_q), sc(a_s), _dev(b_q), sc(b_s))
-    c, cq, cs = mx.gemm_quantize(*args, scale_layout=lay)
+    out = mx.gemm_quantize(*args, axis=axis, scale_layout=lay)
     plain = mx.gemm(*args, torch.bfloat16, scale_layout=lay)
     torch.cuda.synchronize()
-    assert torch.equal(c.view(torch.int16), plain.view(torch.int16))
-    bits = c.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert torch.equal(out["c"].view(torch.int16), plain.view(torch.int16))
+    bits = np.ascontiguousarray(out["c"].view(torch.int16).cpu().numpy().view(np.uint16))
     assert ((bits[3] & 0x7FFF) > 0x7F80).all() and ((bits[5] & 0x7FFF) == 0x7F80).any()   # NaN row, Inf entries
-    q, s = oracle.quantize_rowwise(np.ascontiguousarray(bits))
-    assert np.array_equal(cq.cpu().numpy(), q)
-    got_s = cs.cpu().numpy()
-    assert np.array_equal(sl.untile(got_s, M, N // 32) if tiled else got_s, s)
+    for ax, fn, qk, sk, shp in (("rowwise", oracle.quantize_rowwise, "q_row", "s_row", (M, N // 32)),
+                                ("colwise", oracle.quantize_colwise, "q_colT", "s_colT", (N, M // 32))):
+        if axis in (ax, "both"):
+            q, s = fn(bits)
+            assert np.array_equal(out[qk].cpu().numpy(), q), ax
+            got = out[sk].cpu().numpy()
+            assert np.array_equal(sl.untile(got, *shp) if tiled else got, s), ax
+        else:
+            assert qk not in out
 
 
 def test_fused_output_quantization_rejects_partial_tiles():
