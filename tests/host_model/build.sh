@@ -16,6 +16,6 @@ if [ "$1" = "--shared" ]; then
 else
     out="${1:-$here/_build/hostmodel}"
     mkdir -p "$(dirname "$out")"
-    "$CXX" "${common[@]}" -O1 -g -fsanitize=address,alignment -fno-sanitize-recover=all -fno-omit-frame-pointer \
+    "$CXX" "${common[@]}" -O0 -gline-tables-only -fsanitize=address,alignment -fno-sanitize-recover=all -fno-omit-frame-pointer \
         -o "$out" "$here/driver.cpp" "${kernels[@]}"
 fi

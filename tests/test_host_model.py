@@ -318,7 +318,7 @@ def test_gemm_persistent_small_tiles(hostmodel, tmp_path, mode, tiled):
         _check_gemm(out, M, N, N, ops, bf16)
 
 
-@pytest.mark.parametrize("tune", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tune", [0, 1, 3, 4, 6])    # 2 (like 3) and 5 (like 6) differ only in a constant
 def test_gemm_persistent_large_tiles_sampled_workgroups(hostmodel, tmp_path, tune):
     """256x256 configuration: 128 tiles on 64 workgroups (2 tiles each); first and last workgroup for the
     default schedule, the last one for each schedule variant (MXFP8_GEMM_TUNE)."""
