@@ -1,7 +1,7 @@
 """Mutation check of the oracle's pins (test infrastructure, run by hand: `python oracle/mutation_check.py`,
 a few minutes). Plants one plausible mistake at a time -- a wrong bias, tie rule, clamp, sign, index,
 transposed operand, dropped term -- into a scratch copy of oracle/mxfp8_oracle.c and runs
-tests/test_oracle_pins.py against it. Every mutant must be caught; a survivor means a pin is missing.
+tests/test_oracle_pins.py and tests/test_oracle_modes.py against it. Every mutant must be caught; a survivor means a pin is missing.
 Arguments, if any, select the mutants whose description contains one of them."""
 import os
 import shutil
@@ -54,6 +54,17 @@ M=[
  ("gemm: row selection ignored", "mxo_dequantize_f64(a_q + row_idx[idx] * K, a_s + row_idx[idx] * nb, 1, K, a + idx * K);", "mxo_dequantize_f64(a_q + idx * K, a_s + idx * nb, 1, K, a + idx * K);"),
  ("gemm: A scales of the wrong row", "mxo_dequantize_f64(a_q + row_idx[idx] * K, a_s + row_idx[idx] * nb, 1, K, a + idx * K);", "mxo_dequantize_f64(a_q + row_idx[idx] * K, a_s + idx * nb, 1, K, a + idx * K);"),
  ("gemm: product sign", "acc += p;", "acc -= p;"),
+ # ablation arms (pinned by tests/test_oracle_modes.py)
+ ("e5m2 decode: exponent bias 16", "ldexp(1.0 + (double)m / 4.0, e - 15)", "ldexp(1.0 + (double)m / 4.0, e - 16)"),
+ ("e5m2 decode: subnormal unit 2^-17", "v = ldexp((double)m, -16);", "v = ldexp((double)m, -17);"),
+ ("e5m2 decode: no infinities", "return m ? NAN : (sign ? -INFINITY : INFINITY);", "return NAN;"),
+ ("e5m2 encode: overflow gives Inf instead of saturating", "return (uint8_t)(sign | 0x7B);", "return (uint8_t)(sign | 0x7C);"),
+ ("e5m2 encode: ties to odd", "if (d < best_d || (d == best_d && (c & 1) == 0)) {\n            best_d = d;\n            best = c;\n        }\n    }\n    return (uint8_t)(sign | best);\n}\n\nstatic double fmt_max",
+  "if (d < best_d || (d == best_d && (c & 1) == 1)) {\n            best_d = d;\n            best = c;\n        }\n    }\n    return (uint8_t)(sign | best);\n}\n\nstatic double fmt_max"),
+ ("ocp rule: strict inequality (powers of two round down a binade)", "if (ldexp(1.0, n + fmt_emax(fmt)) <= amax)", "if (ldexp(1.0, n + fmt_emax(fmt)) < amax)"),
+ ("ocp rule: E4M3 emax 7", "return fmt ? 15 : 8;", "return fmt ? 15 : 7;"),
+ ("mode quantize: scale bias off by one", "ldexp((double)v[i], -(sb - 127))", "ldexp((double)v[i], -(sb - 128))"),
+ ("mode quantize: E5M2 destination maximum 448", "return fmt ? 57344.0 : 448.0;", "return fmt ? 448.0 : 448.0;"),
 ]
 src=open(os.path.join(ROOT,'oracle','mxfp8_oracle.c')).read()
 results=[]
@@ -68,12 +79,12 @@ for name,old,new in M:
         shutil.copy(os.path.join(ROOT,'oracle','__init__.py'), os.path.join(tmp,'oracle'))
         open(os.path.join(tmp,'oracle','mxfp8_oracle.c'),'w').write(mutated)
         shutil.copytree(os.path.join(ROOT,'tests','golden'), os.path.join(tmp,'tests','golden'))
-        for f in ('conftest.py','test_oracle_pins.py'):
+        for f in ('conftest.py','test_oracle_pins.py','test_oracle_modes.py'):
             shutil.copy(os.path.join(ROOT,'tests',f), os.path.join(tmp,'tests'))
         os.makedirs(os.path.join(tmp,'paper_2506_08027_amd'))
         shutil.copy(os.path.join(ROOT,'paper_2506_08027_amd','synth_inputs.py'), os.path.join(tmp,'paper_2506_08027_amd'))
         open(os.path.join(tmp,'paper_2506_08027_amd','__init__.py'),'w').write('')
-        r=subprocess.run([sys.executable,'-m','pytest','-q','-x','-p','no:cacheprovider','tests/test_oracle_pins.py'],cwd=tmp,capture_output=True,text=True,timeout=900)
+        r=subprocess.run([sys.executable,'-m','pytest','-q','-x','-p','no:cacheprovider','tests/test_oracle_pins.py','tests/test_oracle_modes.py'],cwd=tmp,capture_output=True,text=True,timeout=900)
         killed = r.returncode!=0
         first=[l for l in r.stdout.splitlines() if l.startswith('FAILED') or 'Error' in l][:1]
         results.append((name,killed,first[0][:110] if first else ''))
