@@ -11,14 +11,21 @@ H = 4096 -> O = 14336), forward and backward, on seeded synthetic tensors reside
     wgrad  dW = dY_colT . X_colT^T (FP32 out)
     dequantize X_row -> BF16
 
+through the `_ex` entry points with the tiled scale layout (the layout both kernels are fastest with).
+
 Prints ONE JSON line. `value` is the GEMM work of a step (3 x 2*T*H*O flop) divided by the whole
-step time, quantize and dequantize passes included. `roofline` describes the GEMM (fprop launch),
-`roofline_quantize` the quantizer (X, both axes), both timed live with events on the launch
-stream inside the timed region. `cpu_baseline` times the CPU oracle on a bounded sample.
+step time, quantize and dequantize passes included. `roofline` describes the forward GEMM launch and
+`roofline_dgrad` / `roofline_wgrad` the two backward products, each timed with events on the launch
+stream inside the timed region. `roofline_quantize` (X, BF16, both axes) and `roofline_quantize_f32`
+(dY, FP32, both axes) are timed after the step loop over >= 100 launches that rotate over more than
+512 MB of distinct sources and destinations, so that the 256 MB memory-side cache cannot serve them.
+`layer_set_16384` times the three products of each linear layer of an 8B-class transformer block at
+16384 tokens. `cpu_baseline` times the CPU oracle on a bounded sample.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -69,15 +76,29 @@ def cpu_baseline():
     }
 
 
+def kernel_sources_digest():
+    """Identifies the kernel sources a profile was taken with."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2506_08027_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def traffic_from_profile(row_prefix):
     """HBM-side bytes per launch (fetched + written) measured with rocprofv3 PMC counters and kept in
-    profiles/hbm_traffic_pmc.txt (the counters cannot be read from inside this process)."""
+    profiles/hbm_traffic_pmc.txt (the counters cannot be read from inside this process). Only a profile
+    taken with the kernel sources of this very tree counts; otherwise the traffic is unknown (None)."""
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")) as f:
-            for line in f:
-                if line.startswith(row_prefix):
-                    cells = [c.strip() for c in line.split("|")]
-                    return (float(cells[1]) + float(cells[2])) * 1e6
+            lines = f.read().splitlines()
+        if not any(l.startswith("# kernel sources:") and kernel_sources_digest() in l for l in lines):
+            return None
+        for line in lines:
+            if line.startswith(row_prefix):
+                cells = [c.strip() for c in line.split("|")]
+                return (float(cells[1]) + float(cells[2])) * 1e6
     except (OSError, ValueError, IndexError):
         pass
     return None
@@ -89,9 +110,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--opt-in", action="store_true",
-                    help="also time the opt-in paths (tiled scale layout, persistent GEMM kernel) after the step "
-                         "loop and report them as `opt_in_paths`; the headline numbers are not affected")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the step loop (for profiler runs): no rotating quantize timing, no 16384-token layer set")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, used to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -108,6 +128,7 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    lay = mx.SCALES_TILED
     bf = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
     X = bf(si.activations(T, H, seed=2))
     W = bf(si.weights(O, H, seed=4))
@@ -115,36 +136,34 @@ def main():
     u8 = dict(dtype=torch.uint8, device=dev)
 
     def qbufs(r, c):
-        return dict(q_row=torch.empty((r, c), **u8), s_row=torch.empty((r, c // 32), **u8),
-                    q_colT=torch.empty((c, r), **u8), s_colT=torch.empty((c, r // 32), **u8))
+        return dict(q_row=torch.empty((r, c), **u8), s_row=torch.empty(mx.mxfp8_scale_bytes(r, c, lay), **u8),
+                    q_colT=torch.empty((c, r), **u8), s_colT=torch.empty(mx.mxfp8_scale_bytes(c, r, lay), **u8))
     Xq, Wq, dYq = qbufs(T, H), qbufs(O, H), qbufs(T, O)
     Y = torch.empty((T, O), dtype=torch.bfloat16, device=dev)
     dX = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
     dW = torch.empty((O, H), dtype=torch.float32, device=dev)
     Xd = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    gemm_ev, quant_ev = [], []
+    ev = lambda: torch.cuda.Event(enable_timing=True)   # recorded on torch's current stream, where the launches go
+    marks = {"fprop": [], "dgrad": [], "wgrad": []}
 
-    def step(timed):
-        e = (ev(), ev(), ev(), ev()) if timed else None
-        if timed:
-            e[0].record()
-        mx.mxfp8_quantize(X, mx.BOTH, **Xq)
-        if timed:
-            e[1].record()
-        mx.mxfp8_quantize(W, mx.BOTH, **Wq)
-        if timed:
-            e[2].record()
-        mx.mxfp8_gemm(mx.FPROP, Xq["q_row"], Xq["s_row"], Wq["q_row"], Wq["s_row"], Y)
-        if timed:
-            e[3].record()
-            quant_ev.append((e[0], e[1]))
-            gemm_ev.append((e[2], e[3]))
-        mx.mxfp8_quantize(dY, mx.BOTH, **dYq)
-        mx.mxfp8_gemm(mx.DGRAD, dYq["q_row"], dYq["s_row"], Wq["q_colT"], Wq["s_colT"], dX)
-        mx.mxfp8_gemm(mx.WGRAD, dYq["q_colT"], dYq["s_colT"], Xq["q_colT"], Xq["s_colT"], dW)
-        mx.mxfp8_dequantize(Xq["q_row"], Xq["s_row"], Xd)
+    def timed(name, on, fn):
+        if not on:
+            return fn()
+        a, b = ev(), ev()
+        a.record()
+        fn()
+        b.record()
+        marks[name].append((a, b))
+
+    def step(on):
+        mx.mxfp8_quantize_ex(X, mx.BOTH, **Xq, scale_layout=lay)
+        mx.mxfp8_quantize_ex(W, mx.BOTH, **Wq, scale_layout=lay)
+        timed("fprop", on, lambda: mx.mxfp8_gemm_ex(mx.FPROP, Xq["q_row"], Xq["s_row"], Wq["q_row"], Wq["s_row"], Y, lay))
+        mx.mxfp8_quantize_ex(dY, mx.BOTH, **dYq, scale_layout=lay)
+        timed("dgrad", on, lambda: mx.mxfp8_gemm_ex(mx.DGRAD, dYq["q_row"], dYq["s_row"], Wq["q_colT"], Wq["s_colT"], dX, lay))
+        timed("wgrad", on, lambda: mx.mxfp8_gemm_ex(mx.WGRAD, dYq["q_colT"], dYq["s_colT"], Xq["q_colT"], Xq["s_colT"], dW, lay))
+        mx.mxfp8_dequantize_ex(Xq["q_row"], Xq["s_row"], Xd, lay)
 
     for _ in range(args.warmup):
         step(False)
@@ -155,70 +174,77 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    def timed_ms(fn, reps=10):
-        for _ in range(3):
-            fn()
+    def rotating_quantize(src, sets, launches):
+        """Average time of one both-axes quantize launch over `launches` launches that walk through `sets`
+        distinct source tensors and as many distinct output sets (bracketed by one pair of events)."""
+        r, c = src.shape
+        srcs = [src] + [src.clone() for _ in range(sets - 1)]
+        outs = [qbufs(r, c) for _ in range(sets)]
+        for i in range(min(sets, 4)):
+            mx.mxfp8_quantize_ex(srcs[i], mx.BOTH, **outs[i], scale_layout=lay)
         a, b = ev(), ev()
+        torch.cuda.synchronize()
         a.record()
-        for _ in range(reps):
-            fn()
+        for i in range(launches):
+            mx.mxfp8_quantize_ex(srcs[i % sets], mx.BOTH, **outs[i % sets], scale_layout=lay)
         b.record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
+        footprint = sets * (src.numel() * src.element_size() + 2 * r * c)
+        return a.elapsed_time(b) / launches, footprint
 
-    def tiled_scale_variants():
-        """The opt-in paths (tiled scale layout, persistent GEMM kernel), timed outside the step and
-        reported next to the headline numbers, which stay on the default entry points."""
-        lay = mx.SCALES_TILED
+    def layer_set():
+        """The four linear layers of an 8B-class transformer block at 16384 tokens: every product timed on
+        operands quantized on the GPU from tensors drawn on the GPU (torch generator, seed 16384)."""
+        T5 = 16384
+        g = torch.Generator(device=dev)
+        g.manual_seed(16384)
+        out, total_flop, total_ms = {}, 0.0, 0.0
 
-        def tbufs(r, c):
-            return dict(q_row=torch.empty((r, c), **u8), s_row=torch.empty(mx.mxfp8_scale_bytes(r, c, lay), **u8),
-                        q_colT=torch.empty((c, r), **u8), s_colT=torch.empty(mx.mxfp8_scale_bytes(c, r, lay), **u8))
-        Xt, Wt, dYt = tbufs(T, H), tbufs(O, H), tbufs(T, O)
-        q_x = timed_ms(lambda: mx.mxfp8_quantize_ex(X, mx.BOTH, **Xt, scale_layout=lay))
-        mx.mxfp8_quantize_ex(W, mx.BOTH, **Wt, scale_layout=lay)
-        q_dy = timed_ms(lambda: mx.mxfp8_quantize_ex(dY, mx.BOTH, **dYt, scale_layout=lay))
-        # the three products of the layer: default kernel / tiled scales / persistent kernel on either layout
-        calls = {
-            "fprop": (lambda q, lay_: (mx.FPROP, q[0]["q_row"], q[0]["s_row"], q[1]["q_row"], q[1]["s_row"], Y, lay_),
-                      (Xq, Wq), (Xt, Wt)),
-            "dgrad": (lambda q, lay_: (mx.DGRAD, q[0]["q_row"], q[0]["s_row"], q[1]["q_colT"], q[1]["s_colT"], dX, lay_),
-                      (dYq, Wq), (dYt, Wt)),
-            "wgrad": (lambda q, lay_: (mx.WGRAD, q[0]["q_colT"], q[0]["s_colT"], q[1]["q_colT"], q[1]["s_colT"], dW, lay_),
-                      (dYq, Xq), (dYt, Xt)),
-        }
-        tf = lambda ms: 2.0 * T * H * O / (ms * 1e-3) / 1e12
-        out = {"quantize_x_bf16_both_gbs_tiled": T * H * 4.0625 / (q_x * 1e-3) / 1e9, "quantize_x_ms_tiled": q_x,
-               "quantize_dy_f32_both_gbs_tiled": T * O * 6.0625 / (q_dy * 1e-3) / 1e9, "quantize_dy_ms_tiled": q_dy}
-        for name, (mk, rowmajor, tiled_ops) in calls.items():
-            out[name + "_tflops_default"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(rowmajor, mx.SCALES_ROWMAJOR))))
-            out[name + "_tflops_tiled"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(tiled_ops, lay))))
-            os.environ["MXFP8_GEMM_PERSISTENT"] = "256"
-            try:
-                out[name + "_tflops_persistent"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(rowmajor, mx.SCALES_ROWMAJOR))))
-                out[name + "_tflops_tiled_persistent"] = tf(timed_ms(lambda: mx.mxfp8_gemm_ex(*mk(tiled_ops, lay))))
-                for tune in (1, 2, 3, 4, 5, 6):          # schedule variants of the persistent K step
-                    os.environ["MXFP8_GEMM_TUNE"] = str(tune)
-                    out[f"{name}_tflops_tiled_persistent_tune{tune}"] = tf(timed_ms(
-                        lambda: mx.mxfp8_gemm_ex(*mk(tiled_ops, lay))))
-            finally:
-                os.environ.pop("MXFP8_GEMM_PERSISTENT", None)
-                os.environ.pop("MXFP8_GEMM_TUNE", None)
-        # forward product that also emits the MXFP8 copies of its BF16 output (the next layer's operands)
-        Yt = tbufs(T, O)
-        for axis, key in ((mx.ROWWISE, "row"), (mx.BOTH, "both")):
-            out[f"fprop_tflops_fused_output_quantize_{key}"] = tf(timed_ms(lambda: mx.mxfp8_gemm_quantize_ex(
-                mx.FPROP, Xt["q_row"], Xt["s_row"], Wt["q_row"], Wt["s_row"], Y, axis, Yt["q_row"], Yt["s_row"],
-                Yt["q_colT"], Yt["s_colT"], lay)))
-        out["quantize_y_bf16_both_ms_tiled"] = timed_ms(lambda: mx.mxfp8_quantize_ex(Y, mx.BOTH, **Yt, scale_layout=lay))
+        def ms_of(fn, reps=5):
+            fn()
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        for name, h, o in (("qkv", 4096, 6144), ("attn_out", 4096, 4096), ("gate_up", 4096, 28672), ("down", 14336, 4096)):
+            x = torch.randn((T5, h), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            w = (0.02 * torch.randn((o, h), generator=g, device=dev, dtype=torch.float32)).to(torch.bfloat16)
+            dy = (1e-3 * torch.randn((T5, o), generator=g, device=dev, dtype=torch.float32)).to(torch.bfloat16)
+            xq, wq, dyq = (mx.quantize(t, "both", scale_layout=lay) for t in (x, w, dy))
+            del x, w, dy
+            y = torch.empty((T5, o), dtype=torch.bfloat16, device=dev)
+            dx = torch.empty((T5, h), dtype=torch.bfloat16, device=dev)
+            dw = torch.empty((o, h), dtype=torch.float32, device=dev)
+            flop = 2.0 * T5 * h * o
+            times = {
+                "fprop": ms_of(lambda: mx.mxfp8_gemm_ex(mx.FPROP, xq["q_row"], xq["s_row"], wq["q_row"], wq["s_row"], y, lay)),
+                "dgrad": ms_of(lambda: mx.mxfp8_gemm_ex(mx.DGRAD, dyq["q_row"], dyq["s_row"], wq["q_colT"], wq["s_colT"], dx, lay)),
+                "wgrad": ms_of(lambda: mx.mxfp8_gemm_ex(mx.WGRAD, dyq["q_colT"], dyq["s_colT"], xq["q_colT"], xq["s_colT"], dw, lay)),
+            }
+            out[name] = {"H": h, "O": o, **{k + "_tflops": flop / (v * 1e-3) / 1e12 for k, v in times.items()}}
+            total_flop += 3 * flop
+            total_ms += sum(times.values())
+            del xq, wq, dyq, y, dx, dw
+        out["layer_tflop"] = total_flop / 1e12
+        out["layer_gemm_ms"] = total_ms
+        out["layer_tflops"] = total_flop / (total_ms * 1e-3) / 1e12
+        out["frac_of_peak"] = out["layer_tflops"] / MFMA_FP8_PEAK_TFLOPS
         return out
 
-    tiled = None
-    if args.opt_in:
+    extras = {}
+    if not args.no_extras:
+        q_ms, q_fp = rotating_quantize(X, 8, 160)
+        f_ms, f_fp = rotating_quantize(dY, 2, 100)
+        extras["quant_bf16"] = (q_ms, q_fp, 160)
+        extras["quant_f32"] = (f_ms, f_fp, 100)
         try:
-            tiled = tiled_scale_variants()
-        except Exception as exc:  # the headline measurement above must survive a problem in the extra one
-            tiled = {"error": repr(exc)}
+            extras["layer_set"] = layer_set()
+        except Exception as exc:   # the headline measurement must survive a problem in the extra one
+            extras["layer_set"] = {"error": repr(exc)}
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -228,12 +254,20 @@ def main():
         del src, dst
 
     ms_per_step = dt / args.steps * 1e3
-    step_flops = 3 * 2.0 * T * H * O
-    gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_ev]))
-    quant_ms = float(np.mean([a.elapsed_time(b) for a, b in quant_ev]))
-    gemm_tflops = 2.0 * T * H * O / (gemm_ms * 1e-3) / 1e12
-    quant_bytes = T * H * 4.0625            # 2 B read + 2 x (1 + 1/32) B written per element
-    quant_gbs = quant_bytes / (quant_ms * 1e-3) / 1e9
+    gemm_flop = 2.0 * T * H * O
+    step_flops = 3 * gemm_flop
+    gemm_bytes = {"fprop": (T + O) * H * (1 + 1 / 32) + T * O * 2, "dgrad": (T + H) * O * (1 + 1 / 32) + T * H * 2,
+                  "wgrad": (O + H) * T * (1 + 1 / 32) + O * H * 4}
+    shapes = {"fprop": f"{T}x{O}x{H}, BF16 out", "dgrad": f"{T}x{H}x{O}, BF16 out", "wgrad": f"{O}x{H}x{T}, FP32 out"}
+
+    def gemm_roofline(name):
+        ms = float(np.mean([a.elapsed_time(b) for a, b in marks[name]]))
+        tf = gemm_flop / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": tf, "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_FP8_PEAK_TFLOPS, "peak_sustained": MFMA_SUSTAINED_TFLOPS,
+                "frac_sustained": tf / MFMA_SUSTAINED_TFLOPS, "traffic": traffic_from_profile(name + " "),
+                "algorithmic_bytes": gemm_bytes[name], "kernel": f"gemm_persistent_kernel ({name} {shapes[name]})",
+                "avg_ms": ms, "launches": len(marks[name])}
 
     out = {
         "metric": "MXFP8 GEMM TFLOP/s (% MFMA peak) + quantize GB/s (% HBM), 8B-class, 1 GPU",
@@ -243,20 +277,27 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp8-e4m3 x ue8m0, fp32 accumulate", "data": "synthetic",
         "config": {"workload": f"8B-class MLP up-projection linear layer, fwd+bwd: T={T} tokens, H={H} -> O={O}; "
-                               "quantize X,W (BF16) and dY (FP32) along both axes, fprop+dgrad+wgrad, dequantize X",
+                               "quantize X,W (BF16) and dY (FP32) along both axes, fprop+dgrad+wgrad, dequantize X; "
+                               "tiled scale layout",
                    "T": T, "H": H, "O": O},
-        "gemm_tflops_fprop": gemm_tflops, "quantize_gbs_bf16_both": quant_gbs,
-        "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / MFMA_FP8_PEAK_TFLOPS,
-                     "peak_sustained": MFMA_SUSTAINED_TFLOPS, "frac_sustained": gemm_tflops / MFMA_SUSTAINED_TFLOPS,
-                     "traffic": traffic_from_profile("fprop 8192x14336x4096"),
-                     "kernel": "gemm_kernel (fprop 8192x14336x4096, BF16 out)", "avg_ms": gemm_ms},
-        "roofline_quantize": {"bound": "hbm", "achieved": quant_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": quant_gbs / HBM_PEAK_GBS, "traffic": traffic_from_profile("quantize X BF16"),
-                              "kernel": "quantize_kernel<BF16, row+col> (X 8192x4096)", "avg_ms": quant_ms},
+        "roofline": gemm_roofline("fprop"),
+        "roofline_dgrad": gemm_roofline("dgrad"),
+        "roofline_wgrad": gemm_roofline("wgrad"),
     }
-    if tiled is not None:
-        out["opt_in_paths"] = tiled
+    out["gemm_tflops_fprop"] = out["roofline"]["achieved"]
+    for key, name, elems, bpe, prof in (("roofline_quantize", "quant_bf16", T * H, 4.0625, "quantize X BF16"),
+                                        ("roofline_quantize_f32", "quant_f32", T * O, 6.0625, "quantize dY FP32")):
+        if name in extras:
+            ms, footprint, launches = extras[name]
+            gbs = elems * bpe / (ms * 1e-3) / 1e9
+            out[key] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                        "traffic": traffic_from_profile(prof), "algorithmic_bytes": elems * bpe,
+                        "kernel": f"quantize_kernel ({'BF16 X 8192x4096' if name == 'quant_bf16' else 'FP32 dY 8192x14336'}, both axes)",
+                        "avg_ms": ms, "launches": launches, "rotating_footprint_mb": footprint / 1e6}
+    if "roofline_quantize" in out:
+        out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
+    if "layer_set" in extras:
+        out["layer_set_16384"] = extras["layer_set"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

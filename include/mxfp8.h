@@ -46,7 +46,7 @@ typedef enum {
     MXFP8_ERR_SHAPE = 2, /* negative dimension, axis not a multiple of 32, ld too small */
     MXFP8_ERR_ALIGN = 3, /* pointer or leading dimension not aligned as documented */
     MXFP8_ERR_DTYPE = 4, /* unknown mxfp8_dtype */
-    MXFP8_ERR_MODE = 5,  /* unknown mxfp8_axis / mxfp8_pass / mxfp8_scale_layout */
+    MXFP8_ERR_MODE = 5,  /* unknown mxfp8_axis / mxfp8_pass / mxfp8_scale_layout, negative workgroup bound */
     MXFP8_ERR_HIP = 6    /* kernel launch rejected by the HIP runtime, or not a gfx950 device */
 } mxfp8_status;
 
@@ -130,11 +130,18 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
                         const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
                         void *c, mxfp8_dtype c_dtype, int64_t ldc, void *hip_stream);
 
-/* mxfp8_gemm with a_s and b_s both stored in `scale_layout` (Section 2, Appendix A.3: same sum). */
+/* mxfp8_gemm with a_s and b_s both stored in `scale_layout` (Section 2, Appendix A.3: same sum), on at
+ * most `max_workgroups` compute units. Problems made of full output tiles (M and N multiples of 256, or of
+ * 128 when ceil(M/256)*ceil(N/256) < 128; K >= 256; c 16-byte aligned with ldc*sizeof(element) a multiple
+ * of 16) run as one resident workgroup per compute unit that walks over its share of the tiles;
+ * max_workgroups > 0 caps the number of those workgroups, e.g. to leave compute units to a kernel that
+ * runs beside the product, max_workgroups == 0 takes every compute unit of the current device, a negative
+ * value returns MXFP8_ERR_MODE. Other shapes take one workgroup per tile and ignore the bound. The result
+ * does not depend on it. */
 mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
                            const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
                            void *c, mxfp8_dtype c_dtype, int64_t ldc, mxfp8_scale_layout scale_layout,
-                           void *hip_stream);
+                           int32_t max_workgroups, void *hip_stream);
 
 /*
  * mxfp8_gemm_ex with BF16 output AND, from the same pass, MXFP8 copies of that output, i.e. the next
@@ -147,13 +154,13 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
  * Outputs not selected by `axis` are ignored and may be NULL. Requirements beyond mxfp8_gemm_ex: M and N
  * multiples of the output tile (256 when ceil(M/256)*ceil(N/256) >= 128, else 128), K >= 256, c_bf16
  * 16-byte aligned with ldc*2 a multiple of 16, every selected output 16-byte aligned; anything else
- * returns MXFP8_ERR_SHAPE / MXFP8_ERR_ALIGN.
+ * returns MXFP8_ERR_SHAPE / MXFP8_ERR_ALIGN. max_workgroups as in mxfp8_gemm_ex.
  */
 mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
                                     const uint8_t *b_q, const uint8_t *b_s, int64_t M, int64_t N, int64_t K,
                                     void *c_bf16, int64_t ldc, mxfp8_axis axis, uint8_t *cq_row,
                                     uint8_t *cs_row, uint8_t *cq_colT, uint8_t *cs_colT,
-                                    mxfp8_scale_layout scale_layout, void *hip_stream);
+                                    mxfp8_scale_layout scale_layout, int32_t max_workgroups, void *hip_stream);
 
 /*
  * Decode q [rows x cols], s [rows x cols/32] (dense, blocks along a row) to

@@ -1,5 +1,5 @@
-"""Mutation check of the oracle's pins (test infrastructure, run by hand: `python oracle/mutation_check.py`,
-a few minutes). Plants one plausible mistake at a time -- a wrong bias, tie rule, clamp, sign, index,
+"""Mutation check of the oracle's pins (test infrastructure: `python oracle/mutation_check.py`, or
+tests/test_mutation_checks.py; the full set takes a quarter of an hour). Plants one plausible mistake at a time -- a wrong bias, tie rule, clamp, sign, index,
 transposed operand, dropped term -- into a scratch copy of oracle/mxfp8_oracle.c and runs
 tests/test_oracle_pins.py and tests/test_oracle_modes.py against it. Every mutant must be caught; a survivor means a pin is missing.
 Arguments, if any, select the mutants whose description contains one of them."""

@@ -53,9 +53,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_quantize_ex.restype = ci
     lib.mxfp8_quantize_ex.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, vp, ci, vp]
     lib.mxfp8_gemm_ex.restype = ci
-    lib.mxfp8_gemm_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, ci, vp]
+    lib.mxfp8_gemm_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, ci, ctypes.c_int32, vp]
     lib.mxfp8_gemm_quantize_ex.restype = ci
-    lib.mxfp8_gemm_quantize_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, vp, vp, vp, vp, ci, vp]
+    lib.mxfp8_gemm_quantize_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, vp, vp, vp, vp, ci,
+                                           ctypes.c_int32, vp]
     lib.mxfp8_dequantize_ex.restype = ci
     lib.mxfp8_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
     lib.mxfp8_scale_bytes.restype = i64
@@ -143,11 +144,12 @@ def mxfp8_quantize_ex(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=Non
 
 def mxfp8_gemm(pass_, a_q, a_s, b_q, b_s, c, stream=None) -> None:
     """c [M x N] (float32/bfloat16) = A [M x K] . B [N x K]^T with block scales [. x K/32]."""
-    mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, SCALES_ROWMAJOR, stream)
+    mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, SCALES_ROWMAJOR, 0, stream)
 
 
-def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
-    """mxfp8_gemm with both scale operands stored in `scale_layout`."""
+def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, max_workgroups=0, stream=None) -> None:
+    """mxfp8_gemm with both scale operands stored in `scale_layout`, on at most `max_workgroups` compute
+    units (0 = all)."""
     _need_cuda(a_q, a_s, b_q, b_s, c)
     M, K = a_q.shape
     N, Kb = b_q.shape
@@ -162,13 +164,13 @@ def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, st
             raise ValueError("quantized operands must be dense uint8")
     ldc = c.stride(0) if M > 1 else max(N, 1)
     rc = load().mxfp8_gemm_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c),
-                              _dtype_code(c.dtype), ldc, scale_layout, _stream(stream))
+                              _dtype_code(c.dtype), ldc, scale_layout, max_workgroups, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_gemm")
 
 
 def mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, axis, cq_row=None, cs_row=None, cq_colT=None, cs_colT=None,
-                           scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+                           scale_layout=SCALES_ROWMAJOR, max_workgroups=0, stream=None) -> None:
     """mxfp8_gemm_ex with bfloat16 c [M x N] plus the MXFP8 copies of c selected by `axis`:
     cq_row [M x N] / cs_row and cq_colT [N x M] / cs_colT."""
     _need_cuda(a_q, a_s, b_q, b_s, c, cq_row, cs_row, cq_colT, cs_colT)
@@ -190,7 +192,7 @@ def mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, axis, cq_row=None, cs_r
     ldc = c.stride(0) if M > 1 else max(N, 1)
     rc = load().mxfp8_gemm_quantize_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c), ldc,
                                        ax, _ptr(cq_row), _ptr(cs_row), _ptr(cq_colT), _ptr(cs_colT), scale_layout,
-                                       _stream(stream))
+                                       max_workgroups, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_gemm_quantize_ex")
 
@@ -242,13 +244,13 @@ def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR):
     return out
 
 
-def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):
+def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
     c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
-    mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout)
+    mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout, max_workgroups)
     return c
 
 
-def gemm_quantize(pass_, a_q, a_s, b_q, b_s, axis="both", scale_layout=SCALES_ROWMAJOR):
+def gemm_quantize(pass_, a_q, a_s, b_q, b_s, axis="both", scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
     """Allocate the outputs of mxfp8_gemm_quantize_ex and return them as a dict: 'c' (bfloat16 [M x N]) and,
     as selected by `axis`, 'q_row', 's_row', 'q_colT', 's_colT' of c (same conventions as quantize)."""
     M, N = a_q.shape[0], b_q.shape[0]
@@ -263,7 +265,7 @@ def gemm_quantize(pass_, a_q, a_s, b_q, b_s, axis="both", scale_layout=SCALES_RO
         out["q_colT"] = torch.empty((N, M), **u8)
         out["s_colT"] = torch.empty((mxfp8_scale_bytes(N, M, scale_layout),) if tiled else (N, M // K_BLOCK), **u8)
     mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, out["c"], ax, out.get("q_row"), out.get("s_row"),
-                           out.get("q_colT"), out.get("s_colT"), scale_layout)
+                           out.get("q_colT"), out.get("s_colT"), scale_layout, max_workgroups)
     return out
 
 

@@ -11,11 +11,12 @@ hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t col
 hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
                              bool bf16, bool tiled_scales, int64_t ld, hipStream_t stream);
 hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
-                       int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                       int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc, int max_workgroups,
                        hipStream_t stream);
 hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
                              int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
-                             uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, hipStream_t stream);
+                             uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, int max_workgroups,
+                             hipStream_t stream);
 }  // namespace mxfp8
 
 namespace {
@@ -82,16 +83,16 @@ mxfp8_status mxfp8_gemm(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
                         const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c, mxfp8_dtype c_dtype,
                         int64_t ldc, void *hip_stream)
 {
-    return mxfp8_gemm_ex(pass, a_q, a_s, b_q, b_s, M, N, K, c, c_dtype, ldc, MXFP8_SCALES_ROWMAJOR, hip_stream);
+    return mxfp8_gemm_ex(pass, a_q, a_s, b_q, b_s, M, N, K, c, c_dtype, ldc, MXFP8_SCALES_ROWMAJOR, 0, hip_stream);
 }
 
 mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
                            const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c, mxfp8_dtype c_dtype,
-                           int64_t ldc, mxfp8_scale_layout scale_layout, void *hip_stream)
+                           int64_t ldc, mxfp8_scale_layout scale_layout, int32_t max_workgroups, void *hip_stream)
 {
     if (!valid_dtype(c_dtype))
         return MXFP8_ERR_DTYPE;
-    if (!valid_layout(scale_layout))
+    if (!valid_layout(scale_layout) || max_workgroups < 0)
         return MXFP8_ERR_MODE;
     if (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD)
         return MXFP8_ERR_MODE;
@@ -106,7 +107,7 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
         (K > 0 && (!aligned16(a_q) || !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))))
         return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16,
-                                            scale_layout == MXFP8_SCALES_TILED, ldc,
+                                            scale_layout == MXFP8_SCALES_TILED, ldc, max_workgroups,
                                             static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
@@ -114,9 +115,10 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
 mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
                                     const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c_bf16, int64_t ldc,
                                     mxfp8_axis axis, uint8_t *cq_row, uint8_t *cs_row, uint8_t *cq_colT,
-                                    uint8_t *cs_colT, mxfp8_scale_layout scale_layout, void *hip_stream)
+                                    uint8_t *cs_colT, mxfp8_scale_layout scale_layout, int32_t max_workgroups,
+                                    void *hip_stream)
 {
-    if (!valid_layout(scale_layout))
+    if (!valid_layout(scale_layout) || max_workgroups < 0)
         return MXFP8_ERR_MODE;
     if (axis != MXFP8_ROWWISE && axis != MXFP8_COLWISE && axis != MXFP8_BOTH)
         return MXFP8_ERR_MODE;
@@ -136,7 +138,7 @@ mxfp8_status mxfp8_gemm_quantize_ex(mxfp8_pass pass, const uint8_t *a_q, const u
         (want_col && (!aligned16(cq_colT) || !aligned16(cs_colT))))
         return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_gemm_fused(a_q, a_s, b_q, b_s, M, N, K, c_bf16, ldc, (int)axis, cq_row, cs_row,
-                                                  cq_colT, cs_colT, scale_layout == MXFP8_SCALES_TILED,
+                                                  cq_colT, cs_colT, scale_layout == MXFP8_SCALES_TILED, max_workgroups,
                                                   static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidConfiguration)  // the chosen tile does not divide M and N: nothing was launched
         return MXFP8_ERR_SHAPE;
@@ -179,7 +181,7 @@ const char *mxfp8_status_string(mxfp8_status status)
     case MXFP8_ERR_SHAPE: return "bad shape: negative, not a multiple of the block size, or leading dimension too small";
     case MXFP8_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
     case MXFP8_ERR_DTYPE: return "unknown element type";
-    case MXFP8_ERR_MODE: return "unknown axis, pass or scale layout";
+    case MXFP8_ERR_MODE: return "unknown axis, pass or scale layout, or a negative workgroup bound";
     case MXFP8_ERR_HIP: return "HIP launch failed (is this a gfx950 device?)";
     }
     return "unknown status";

@@ -23,8 +23,6 @@
 // fetches the chunk that belongs at its slot.
 #include "mxfp8_device.h"
 
-#include <stdlib.h>
-
 namespace mxfp8 {
 
 constexpr int BK = 128;  // K bytes per step = 4 scale blocks = one MFMA
@@ -319,26 +317,15 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     }
 }
 
-// Workgroup barrier without the LDS fence of __syncthreads(): LDS reads issued before it may still be
-// in flight afterwards. The K step of the persistent kernel only hands DMA-written buffers from one
-// phase to the next (their arrival is tracked by vmcnt), and the fragment reads still in flight at its
-// barriers go to registers from a buffer whose next overwrite is requested hundreds of cycles later
-// and lands a global-memory latency after that, while this wavefront's next lgkmcnt wait (LDS reads
-// return in order) comes first.
+// Workgroup barrier without the LDS fence of __syncthreads(): LDS reads issued before it may still be in
+// flight afterwards. The persistent kernel uses it where a barrier only publishes DMA-written buffers
+// (their arrival is tracked by vmcnt) and nothing that is still being read is handed back for overwriting.
+// Where a buffer IS handed back (end of a K step) the reads that can still be in flight are awaited first
+// (MXFP8_WAIT_VMCNT_AND_LDS): fragment reads that an already issued MFMA consumed have returned by
+// construction, the in-place refills of the A fragments are the only ones left.
 #define MXFP8_BARRIER() __builtin_amdgcn_s_barrier()
-
-// Schedule variants of the persistent kernel's K step, to be timed against each other on the hardware
-// (MXFP8_GEMM_TUNE=<id>; 0 is the schedule of the kernel above). Every variant issues all B requests of
-// a step before its A requests and all of them before the last MFMA column: the wait counts rely on it.
-template <int ID> struct GemmTune {
-    static_assert(ID >= 0 && ID <= 6, "known variant");
-    // B(k+1) is awaited together with A(k+1) at the barrier before the last MFMA column, so that the first
-    // B fragments of the next step can be read during that column instead of after the end-of-step barrier
-    static constexpr bool EARLY_B = ID == 4;
-    static constexpr int NFB = ID == 2 ? 2 : ID == 3 ? 4 : 3;  // B fragment register sets (read NFB-1 columns ahead)
-    static constexpr bool SPREAD = ID == 1;                    // one B request per 2 MFMAs, then one A request per 4
-    static constexpr int POLICY = ID == 5 ? 1 : ID == 6 ? 2 : 0;  // cache-policy bits of the tile loads (see dma_load)
-};
+// s_waitcnt vmcnt(n) lgkmcnt(0): additionally every LDS read of this wavefront has returned
+#define MXFP8_WAIT_VMCNT_AND_LDS(n) __builtin_amdgcn_s_waitcnt(0x0070 | ((n) & 15) | (((n) >> 4) << 14))
 
 // ---- persistent variant --------------------------------------------------------------------------
 // One workgroup per compute unit walks over several output tiles and keeps the K pipeline running
@@ -362,7 +349,7 @@ template <int ID> struct GemmTune {
 //                are transposed through the two LDS buffers that are idle between tiles (the B buffer the
 //                finished step read and the A buffer whose fragments already sit in registers) and leave
 //                as full lines of cqT.
-template <class Cfg, bool OUT_BF16, bool TILED, class Tune, int FUSE_Q = 0>
+template <class Cfg, bool OUT_BF16, bool TILED, bool SPREAD, int FUSE_Q = 0>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
@@ -427,13 +414,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     // DMA slot t of the A / B requests of one K step, from the step's source pointers into buffer buf
     auto issue_a = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::A_LOADS)
-            dma_load<16, Tune::POLICY>(src, goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
+            dma_load<16>(src, goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
         else if (t < Cfg::NA)
             dma_load<4>(ssrc, sgoff, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + grp * 256);
     };
     auto issue_b = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::B_LOADS)
-            dma_load<16, Tune::POLICY>(src, goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
+            dma_load<16>(src, goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
         else if (t < Cfg::NB)
             dma_load<4>(ssrc, sgoff, lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + grp * 256);
     };
@@ -456,8 +443,6 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
     v8i fa[TM];
     int sa[TM];
-    v8i fb_carry[2];  // Tune::EARLY_B: the first two B fragments of the next step, read during the last column
-    int sb_carry[2];
 
     // One K step, same schedule as in the kernel above; the requests go to the sources handed in:
     // (b_src, bs_src) = B tile and scales of the workgroup's NEXT step, (a_src, as_src) = A tile and
@@ -469,19 +454,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         const int nxt = cur ^ 1;
         const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
         const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::BM * 4;
-        constexpr int NFB = Tune::NFB;
+        constexpr int NFB = 3;  // B fragment register sets, read NFB-1 columns ahead
         v8i fb[NFB];
         int sb[NFB];
-        static_assert(!Tune::EARLY_B || (NFB == 3 && TN >= 3), "two carried fragments");
 #pragma unroll
         for (int j = 0; j < NFB - 1 && j < TN; ++j) {
-            if constexpr (Tune::EARLY_B) {
-                fb[j] = fb_carry[j];
-                sb[j] = sb_carry[j];
-            } else {
-                fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
-                sb[j] = sbbuf[b_soff + j * 64];
-            }
+            fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
+            sb[j] = sbbuf[b_soff + j * 64];
         }
         MXFP8_PIN();
         int a_slot = 0;
@@ -492,7 +471,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 sb[(j + NFB - 1) % NFB] = sbbuf[b_soff + (j + NFB - 1) * 64];
             }
             if (j == TN - 1) {
-                MXFP8_WAIT_VMCNT(Tune::EARLY_B ? Cfg::NA : Cfg::NA + Cfg::NB);
+                MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);
                 MXFP8_BARRIER();
             }
             MXFP8_PIN();
@@ -501,7 +480,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j % NFB], fa[i], acc[i][j], 0, 0, 0,
                                                                              sb[j % NFB], 0, sa[i]);
                 MXFP8_PIN();
-                if constexpr (Tune::SPREAD) {
+                if constexpr (SPREAD) {
                     constexpr int A_FIRST = 2 * Cfg::NB + 2;  // MFMA after which the first A request goes out
                     static_assert(A_FIRST + 4 * (Cfg::NA - 1) < (TN - 1) * TM, "all requests before the last column");
                     const int m = j * TM + i;  // compile-time after unrolling
@@ -521,19 +500,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 if (j == TN - 1) {
                     fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
                     sa[i] = sanext[a_soff + i * 64];
-                    if constexpr (Tune::EARLY_B) {
-                        if (i < 2) {  // B buffer nxt holds B(k+1) since the barrier above
-                            fb_carry[i] = read_frag(lds + Cfg::B_OFF + nxt * Cfg::B_BYTES, b_off0 + i * 2048, b_off1 + i * 2048);
-                            sb_carry[i] = (lds + Cfg::SB_OFF + nxt * Cfg::BN * 4)[b_soff + i * 64];
-                        }
-                    }
                 }
                 MXFP8_PIN();
             }
         }
-        if constexpr (!Tune::EARLY_B)
-            MXFP8_WAIT_VMCNT(Cfg::NA);
-        MXFP8_BARRIER();  // (EARLY_B: nobody requests B(k+2) into a buffer that a slower wavefront still reads)
+        // end of the step: B(k+1) has landed; B buffer cur and A buffer nxt go back to the DMA, so this
+        // wavefront's refill reads of A buffer nxt must have returned before anybody passes the barrier
+        MXFP8_WAIT_VMCNT_AND_LDS(Cfg::NA);
+        MXFP8_BARRIER();
     };
 
     Tile cur_tile = tile_at(0);
@@ -553,13 +527,6 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     for (int i = 0; i < TM; ++i) {
         fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
         sa[i] = (lds + Cfg::SA_OFF)[a_soff + i * 64];
-    }
-    if constexpr (Tune::EARLY_B) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            fb_carry[j] = read_frag(lds + Cfg::B_OFF, b_off0 + j * 2048, b_off1 + j * 2048);
-            sb_carry[j] = (lds + Cfg::SB_OFF)[b_soff + j * 64];
-        }
     }
     __syncthreads();
 
@@ -772,62 +739,55 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     MXFP8_WAIT_VMCNT(0);  // the redundant prefetches of the last steps must land before LDS is released
 }
 
-// The persistent kernel is opt-in until it has been timed against the one-tile-per-workgroup kernel:
-// MXFP8_GEMM_PERSISTENT=<workgroups> in the environment (256 = one per compute unit of an MI355X)
-// selects it for the shapes it supports; unset or 0 leaves it off.
-static int persistent_tune()
+// Number of workgroups of a persistent launch: one per compute unit of the current device, at most
+// `max_workgroups` when the caller gives a positive bound, never more than there are tiles.
+static hipError_t persistent_grid(int ntiles, int max_workgroups, int &grid)
 {
-    const char *e = getenv("MXFP8_GEMM_TUNE");
-    const long n = e ? strtol(e, nullptr, 10) : 0;
-    return n >= 0 && n <= 6 ? (int)n : 0;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess)
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess)
+        return e;
+    grid = cus > 0 ? cus : 1;
+    if (max_workgroups > 0 && max_workgroups < grid)
+        grid = max_workgroups;
+    if (ntiles < grid)
+        grid = ntiles;
+    return hipSuccess;
 }
 
-static int persistent_workgroups()
+// The K-step schedule that spreads the requests over the step is the faster one on an MI355X wherever
+// its spacing fits the tile (measured on the 8B-class layer shapes: +3 % over issuing them in bursts).
+template <class Cfg> constexpr bool spread_fits()
 {
-    const char *e = getenv("MXFP8_GEMM_PERSISTENT");
-    const long n = e ? strtol(e, nullptr, 10) : 0;
-    return n > 0 && n <= 65536 ? (int)n : 0;
+    return 2 * Cfg::NB + 2 + 4 * (Cfg::NA - 1) < (Cfg::TN - 1) * Cfg::TM;
 }
 
 template <class Cfg, bool OUT_BF16, bool TILED>
 static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
-                             int M, int N, int K, void *c, int64_t ldc, hipStream_t stream)
+                             int M, int N, int K, void *c, int64_t ldc, int max_workgroups, hipStream_t stream)
 {
     const int tiles_m = (M + Cfg::BM - 1) / Cfg::BM, tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
     const int64_t ldc_bytes = ldc * (OUT_BF16 ? 2 : 4);
     // 128-bit (FP32) / 64-bit (BF16) stores need every row start aligned; otherwise element stores
     const bool vec_store = (reinterpret_cast<uintptr_t>(c) % 16 == 0) && (ldc_bytes % 16 == 0);
-    const int workgroups = persistent_workgroups();
-    // (its epilogue addresses a tile's rows with 32-bit offsets from the tile origin)
-    if (workgroups > 0 && M % Cfg::BM == 0 && N % Cfg::BN == 0 && K >= 2 * BK && vec_store &&
-        ldc_bytes * Cfg::BM < (int64_t(1) << 31)) {
-        // schedule variants exist for the 256x256 tile with tiled scales; anything else runs variant 0
-        const int tune = (Cfg::BM == 256 && TILED) ? persistent_tune() : 0;
-        auto launch = [&](auto kern) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-            if (e != hipSuccess)
-                return e;
-            const int ntiles = tiles_m * tiles_n;
-            hipLaunchKernelGGL(kern, dim3((unsigned)min(ntiles, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
-                               stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m,
-                               tiles_n, static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr),
-                               static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr));
-            return hipGetLastError();
-        };
-        if constexpr (Cfg::BM == 256 && TILED) {
-            switch (tune) {
-            case 1: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<1>>);
-            case 2: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<2>>);
-            case 3: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<3>>);
-            case 4: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<4>>);
-            case 5: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<5>>);
-            case 6: return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<6>>);
-            default: break;
-            }
-        }
-        (void)tune;
-        return launch(gemm_persistent_kernel<Cfg, OUT_BF16, TILED, GemmTune<0>>);
+    // Problems made of full tiles run on the persistent kernel (its epilogue addresses a tile's rows with
+    // 32-bit offsets from the tile origin); everything else takes one workgroup per tile.
+    if (M % Cfg::BM == 0 && N % Cfg::BN == 0 && K >= 2 * BK && vec_store && ldc_bytes * Cfg::BM < (int64_t(1) << 31)) {
+        auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED, spread_fits<Cfg>()>;
+        int grid = 0;
+        hipError_t e = persistent_grid(tiles_m * tiles_n, max_workgroups, grid);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    Cfg::LDS_BYTES);
+        if (e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, a_q, a_s, b_q, b_s, M, N,
+                           K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, static_cast<uint8_t *>(nullptr),
+                           static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr),
+                           static_cast<uint8_t *>(nullptr));
+        return hipGetLastError();
     }
     auto kern = gemm_kernel<Cfg, OUT_BF16, TILED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -841,17 +801,18 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
 
 template <class Cfg>
 static hipError_t launch_any(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int M,
-                             int N, int K, void *c, bool c_bf16, bool tiled, int64_t ldc, hipStream_t stream)
+                             int N, int K, void *c, bool c_bf16, bool tiled, int64_t ldc, int max_workgroups,
+                             hipStream_t stream)
 {
     if (tiled)
-        return c_bf16 ? launch_cfg<Cfg, true, true>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream)
-                      : launch_cfg<Cfg, false, true>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream);
-    return c_bf16 ? launch_cfg<Cfg, true, false>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream)
-                  : launch_cfg<Cfg, false, false>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, stream);
+        return c_bf16 ? launch_cfg<Cfg, true, true>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, max_workgroups, stream)
+                      : launch_cfg<Cfg, false, true>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, max_workgroups, stream);
+    return c_bf16 ? launch_cfg<Cfg, true, false>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, max_workgroups, stream)
+                  : launch_cfg<Cfg, false, false>(a_q, a_s, b_q, b_s, M, N, K, c, ldc, max_workgroups, stream);
 }
 
 hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
-                       int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                       int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc, int max_workgroups,
                        hipStream_t stream)
 {
     using Big = GemmCfg<256, 256, 2, 2>;
@@ -859,8 +820,10 @@ hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_
     // Small problems cannot fill 256 compute units with 256x256 tiles.
     const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
     if (big)
-        return launch_any<Big>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, stream);
-    return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, stream);
+        return launch_any<Big>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, max_workgroups,
+                               stream);
+    return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, max_workgroups,
+                             stream);
 }
 
 // GEMM with BF16 output and MXFP8 copies of that output (axis bit 0: row-wise, bit 1: column-wise) from
@@ -870,22 +833,22 @@ hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_
 template <class Cfg, bool TILED, int AXIS>
 static hipError_t launch_fused_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
                                    int M, int N, int K, void *c, int64_t ldc, uint8_t *cq, uint8_t *cs, uint8_t *cqT,
-                                   uint8_t *csT, hipStream_t stream)
+                                   uint8_t *csT, int max_workgroups, hipStream_t stream)
 {
     const int64_t ldc_bytes = ldc * 2;
     if (M % Cfg::BM || N % Cfg::BN || K < 2 * BK || ldc_bytes * Cfg::BM >= (int64_t(1) << 31))
         return hipErrorInvalidConfiguration;
     const int tiles_m = M / Cfg::BM, tiles_n = N / Cfg::BN;
-    const int requested = persistent_workgroups();
-    const int workgroups = requested > 0 ? requested : 256;  // one per compute unit of an MI355X
-    auto kern = gemm_persistent_kernel<Cfg, true, TILED, GemmTune<0>, AXIS>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    auto kern = gemm_persistent_kernel<Cfg, true, TILED, spread_fits<Cfg>(), AXIS>;
+    int grid = 0;
+    hipError_t e = persistent_grid(tiles_m * tiles_n, max_workgroups, grid);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                Cfg::LDS_BYTES);
     if (e != hipSuccess)
         return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)min(tiles_m * tiles_n, workgroups)), dim3(Cfg::THREADS), Cfg::LDS_BYTES,
-                       stream, a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, cq,
-                       cs, cqT, csT);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, a_q, a_s, b_q, b_s, M, N, K,
+                       static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, cq, cs, cqT, csT);
     return hipGetLastError();
 }
 
@@ -900,17 +863,18 @@ template <class Cfg, bool TILED, class... Args> static hipError_t launch_fused_a
 
 hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
                              int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
-                             uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, hipStream_t stream)
+                             uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, int max_workgroups,
+                             hipStream_t stream)
 {
     using Big = GemmCfg<256, 256, 2, 2>;
     using Small = GemmCfg<128, 128, 2, 2>;
     const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
     const int m = (int)M, n = (int)N, k = (int)K;
     if (big)
-        return tiled_scales ? launch_fused_axis<Big, true>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream)
-                            : launch_fused_axis<Big, false>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream);
-    return tiled_scales ? launch_fused_axis<Small, true>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream)
-                        : launch_fused_axis<Small, false>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, stream);
+        return tiled_scales ? launch_fused_axis<Big, true>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, max_workgroups, stream)
+                            : launch_fused_axis<Big, false>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, max_workgroups, stream);
+    return tiled_scales ? launch_fused_axis<Small, true>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, max_workgroups, stream)
+                        : launch_fused_axis<Small, false>(axis, a_q, a_s, b_q, b_s, m, n, k, c, ldc, cq, cs, cqT, csT, max_workgroups, stream);
 }
 
 }  // namespace mxfp8

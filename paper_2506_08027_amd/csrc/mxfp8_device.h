@@ -129,30 +129,17 @@ __device__ __forceinline__ uint32_t inf_byte_bf16(uint32_t bits16, uint32_t q)
 // load as "may complete out of order with LDS reads" and then turns every wait on an LDS read
 // into a wait for ALL outstanding LDS reads, which would serialise the fragment prefetch.
 // Completion is tracked by hand with s_waitcnt vmcnt(n) in front of the barriers.
-// POLICY picks the cache-policy bits of the load: 0 none, 1 "nt" (streaming), 2 "sc1" (device scope:
-// not served from the compute unit's vector L1).
-template <int BYTES, int POLICY = 0>
+template <int BYTES>
 __device__ __forceinline__ void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
 {
     const uint32_t m0v = lds_addr;  // callers pass a wavefront-uniform (scalar) address
-    static_assert((BYTES == 16 || BYTES == 4) && POLICY >= 0 && POLICY <= 2, "dword or dwordx4, known policy");
-#define MXFP8_DMA_ASM(insn, bits)                                                                          \
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t" insn " %0, %1" bits ::"v"(voff), "s"(base), "s"(m0v) : "memory")
-    if constexpr (BYTES == 16 && POLICY == 0)
+    static_assert(BYTES == 16 || BYTES == 4, "dword or dwordx4");
+    if constexpr (BYTES == 16)
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
                      : "memory");
-    else if constexpr (BYTES == 4 && POLICY == 0)
+    else
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(base), "s"(m0v)
                      : "memory");
-    else if constexpr (BYTES == 16 && POLICY == 1)
-        MXFP8_DMA_ASM("global_load_lds_dwordx4", " nt");
-    else if constexpr (BYTES == 4 && POLICY == 1)
-        MXFP8_DMA_ASM("global_load_lds_dword", " nt");
-    else if constexpr (BYTES == 16 && POLICY == 2)
-        MXFP8_DMA_ASM("global_load_lds_dwordx4", " sc1");
-    else
-        MXFP8_DMA_ASM("global_load_lds_dword", " sc1");
-#undef MXFP8_DMA_ASM
 }
 #endif  // MXFP8_HOST_MODEL
 

@@ -6,7 +6,10 @@
 //   quantize   <f32|bf16> <rows> <cols> <ld> <axis 1|2|3> <src.bin> <out-prefix> [tiled]
 //   gemm       <pass 0|1|2> <M> <N> <K> <f32|bf16> <ldc> <a_q> <a_s> <b_q> <b_s> <c.bin> [tiled]
 //   dequantize <rows> <cols> <f32|bf16> <ld> <q.bin> <s.bin> <out.bin> [tiled]
-// "tiled" selects MXFP8_SCALES_TILED for every scale buffer of the call (sizes from mxfp8_scale_bytes).
+//   gemmq      <pass 0|1|2> <M> <N> <K> <ldc> <axis 1|2|3> <a_q> <a_s> <b_q> <b_s> <out-prefix> [tiled]
+//              (BF16 product <prefix>.c plus the MXFP8 copies of it: .q_row .s_row .q_colT .s_colT)
+// "tiled" selects MXFP8_SCALES_TILED for every scale buffer of the call (sizes from mxfp8_scale_bytes);
+// "wg=<n>" is the max_workgroups argument of gemm / gemmq (default 0 = one per compute unit).
 // Each call prints "status <code> blocks <ids of the simulated workgroups...>".
 #include <cstdint>
 #include <cstdio>
@@ -106,15 +109,24 @@ mxfp8_dtype dtype_of(const std::string &s)
     exit(2);
 }
 
+int g_max_workgroups = 0;  // "wg=<n>" of the current line
+
 mxfp8_scale_layout layout_of(std::istringstream &ls)
 {
     std::string tok;
-    if (!(ls >> tok))
-        return MXFP8_SCALES_ROWMAJOR;
-    if (tok == "tiled")
-        return MXFP8_SCALES_TILED;
-    fprintf(stderr, "unknown trailing token %s\n", tok.c_str());
-    exit(2);
+    mxfp8_scale_layout lay = MXFP8_SCALES_ROWMAJOR;
+    g_max_workgroups = 0;
+    while (ls >> tok) {
+        if (tok == "tiled") {
+            lay = MXFP8_SCALES_TILED;
+        } else if (tok.rfind("wg=", 0) == 0) {
+            g_max_workgroups = atoi(tok.c_str() + 3);
+        } else {
+            fprintf(stderr, "unknown trailing token %s\n", tok.c_str());
+            exit(2);
+        }
+    }
+    return lay;
 }
 
 void report(int status)
@@ -178,13 +190,41 @@ int main(int argc, char **argv)
             Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)mxfp8_scale_bytes(M, K, lay));
             Buf b = load(bq, (size_t)N * K), sb = load(bs, (size_t)mxfp8_scale_bytes(N, K, lay));
             Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * es : 0);
-            const int st = mxfp8_gemm_ex((mxfp8_pass)pass, a.p, sa.p, b.p, sb.p, M, N, K, c.p, dtype_of(dt), ldc, lay, nullptr);
+            const int st = mxfp8_gemm_ex((mxfp8_pass)pass, a.p, sa.p, b.p, sb.p, M, N, K, c.p, dtype_of(dt), ldc, lay, g_max_workgroups, nullptr);
             unchanged(a, "a_q");
             unchanged(sa, "a_s");
             unchanged(b, "b_q");
             unchanged(sb, "b_s");
             report(st);
             save(cout, c);
+        } else if (op == "gemmq") {
+            int pass, axis;
+            long M, N, K, ldc;
+            std::string aq, as, bq, bs, prefix;
+            ls >> pass >> M >> N >> K >> ldc >> axis >> aq >> as >> bq >> bs >> prefix;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)mxfp8_scale_bytes(M, K, lay));
+            Buf b = load(bq, (size_t)N * K), sb = load(bs, (size_t)mxfp8_scale_bytes(N, K, lay));
+            Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * 2 : 0);
+            const bool r = axis & 1, t = axis & 2;
+            Buf qr = output(r ? (size_t)M * N : 0), sr = output(r ? (size_t)mxfp8_scale_bytes(M, N, lay) : 0);
+            Buf qc = output(t ? (size_t)M * N : 0), sc = output(t ? (size_t)mxfp8_scale_bytes(N, M, lay) : 0);
+            const int st = mxfp8_gemm_quantize_ex((mxfp8_pass)pass, a.p, sa.p, b.p, sb.p, M, N, K, c.p, ldc, (mxfp8_axis)axis,
+                                                  qr.p, sr.p, qc.p, sc.p, lay, g_max_workgroups, nullptr);
+            unchanged(a, "a_q");
+            unchanged(sa, "a_s");
+            unchanged(b, "b_q");
+            unchanged(sb, "b_s");
+            report(st);
+            save(prefix + ".c", c);
+            if (r) {
+                save(prefix + ".q_row", qr);
+                save(prefix + ".s_row", sr);
+            }
+            if (t) {
+                save(prefix + ".q_colT", qc);
+                save(prefix + ".s_colT", sc);
+            }
         } else if (op == "dequantize") {
             long rows, cols, ld;
             std::string dt, q, s, out;

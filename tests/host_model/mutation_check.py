@@ -1,5 +1,5 @@
-"""Sensitivity check of the CPU execution model (test infrastructure, run by hand:
-`python tests/host_model/mutation_check.py`, a few minutes). Plants one mistake at a time into a scratch
+"""Sensitivity check of the CPU execution model (test infrastructure; `python tests/host_model/mutation_check.py`,
+or tests/test_mutation_checks.py with --runslow). Plants one mistake at a time into a scratch
 copy of the GEMM kernel source -- a removed barrier, a wait count that is one too loose, a missing wait,
 a swizzle mismatch, a prefetch into the wrong buffer or of the wrong K step, a missing ragged-tile clamp,
 a wrong output row -- builds the host model from it and runs a few products against the oracle in all
@@ -48,12 +48,12 @@ MUTANTS = [  # (description, old text, new text): first occurrence, i.e. in the 
 # the same kinds of mistake in the persistent kernel (last occurrence of the text; run with several tiles per workgroup)
 PERSISTENT_MUTANTS = [
     ("persistent: barrier before the last MFMA column removed",
-     "                MXFP8_WAIT_VMCNT(Tune::EARLY_B ? Cfg::NA : Cfg::NA + Cfg::NB);\n                MXFP8_BARRIER();",
-     "                MXFP8_WAIT_VMCNT(Tune::EARLY_B ? Cfg::NA : Cfg::NA + Cfg::NB);"),
-    ("persistent: end-of-step wait one request too loose", "            MXFP8_WAIT_VMCNT(Cfg::NA);\n        MXFP8_BARRIER();",
-     "            MXFP8_WAIT_VMCNT(Cfg::NA + 1);\n        MXFP8_BARRIER();"),
+     "                MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);\n                MXFP8_BARRIER();",
+     "                MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);"),
+    ("persistent: end-of-step wait one request too loose", "        MXFP8_WAIT_VMCNT_AND_LDS(Cfg::NA);\n        MXFP8_BARRIER();",
+     "        MXFP8_WAIT_VMCNT_AND_LDS(Cfg::NA + 1);\n        MXFP8_BARRIER();"),
     ("persistent: barrier at the end of the K step removed",
-     "        MXFP8_BARRIER();  // (EARLY_B: nobody requests", "        // (EARLY_B: nobody requests"),
+     "        MXFP8_WAIT_VMCNT_AND_LDS(Cfg::NA);\n        MXFP8_BARRIER();", "        MXFP8_WAIT_VMCNT_AND_LDS(Cfg::NA);"),
     ("persistent: next tile's B fetched one K step late", "                b_src = next_tile.b;\n", "                b_src = next_tile.b + BK;\n"),
     ("persistent: next tile's first A step fetched from the current tile",
      "                a_src = next_tile.a + (int64_t)(kt + 2 - KT) * BK;", "                a_src = cur_tile.a + (int64_t)(kt + 2 - KT) * BK;"),
@@ -94,11 +94,11 @@ def caught(binary, work, persistent=0):
             v.tofile(names[-1])
         out = os.path.join(work, "c.bin")
         case = os.path.join(work, "case.txt")
-        open(case, "w").write(f"gemm 0 {M} {N} {K} f32 {N} {' '.join(names)} {out}\n")
+        # persistent: 6 small tiles on 2 workgroups, 128 large tiles on 64: K = 3 steps (odd: parity flips per tile)
+        wg = f" wg={2 if M == 256 else 64}" if persistent else ""
+        open(case, "w").write(f"gemm 0 {M} {N} {K} f32 {N} {' '.join(names)} {out}{wg}\n")
         for mode in MODES:
             env = dict(os.environ, WAVESIM_BLOCKS="2", **mode)
-            if persistent:      # 6 small tiles on 2 workgroups, 128 large tiles on 64: K = 3 steps (odd: parity flips per tile)
-                env["MXFP8_GEMM_PERSISTENT"] = "2" if M == 256 else "64"
             r = subprocess.run([binary, case], capture_output=True, text=True, env=env)
             if r.returncode != 0:
                 return f"model stopped: {r.stderr.strip().splitlines()[-1][:100]}"

@@ -70,6 +70,17 @@ enum hipError_t { hipSuccess = 0, hipErrorInvalidValue = 1, hipErrorInvalidConfi
 enum hipFuncAttribute { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
 inline hipError_t hipFuncSetAttribute(const void *, hipFuncAttribute, int) { return hipSuccess; }
 inline hipError_t hipGetLastError() { return hipSuccess; }
+enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 63 };
+inline hipError_t hipGetDevice(int *dev)
+{
+    *dev = 0;
+    return hipSuccess;
+}
+inline hipError_t hipDeviceGetAttribute(int *value, hipDeviceAttribute_t, int)
+{
+    *value = 256;  // compute units of an MI355X
+    return hipSuccess;
+}
 #define hipLaunchKernelGGL(kern, grid, block, shmem, stream, ...)                            \
     do {                                                                                     \
         (void)(stream);                                                                      \
@@ -81,7 +92,7 @@ inline hipError_t hipGetLastError() { return hipSuccess; }
 // dynamic LDS: the block allocated for this launch
 #define MXFP8_DYNAMIC_LDS(name) uint8_t *const name = ::wavesim::g.lds
 namespace mxfp8 {
-template <int BYTES, int POLICY = 0> inline void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+template <int BYTES> inline void dma_load(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
 {
     static_assert(BYTES == 4 || BYTES == 16, "dword or dwordx4");
     ::wavesim::dma_issue(base, voff, lds_addr, BYTES);

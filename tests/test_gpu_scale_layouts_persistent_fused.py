@@ -1,16 +1,11 @@
-"""NOT COLLECTED by pytest on purpose (file name): these paths have passed on the CPU execution model
-only; run this file by name on an MI355X (`python -m pytest tests/wip_gpu_opt_in_paths.py -m gpu`) and
-rename it to test_gpu_zz_opt_in_paths.py once it has passed there.
-
-GPU parity of the opt-in paths: the tiled scale layout (MXFP8_SCALES_TILED): mxfp8_quantize_ex, mxfp8_gemm_ex and
-mxfp8_dequantize_ex through the C ABI against the CPU oracle. The layout only moves scale bytes, so
-every value must equal what the row-major entry points are held to: quantized bytes bit-exact,
-products within the tolerance of test_gpu_gemm (and, on identical operands, identical to the
-row-major product bit for bit, since the same instructions add the same numbers in the same order).
-The persistent GEMM kernel (MXFP8_GEMM_PERSISTENT=<workgroups>) is held to the same: it runs the same
-K steps in the same order, so its output equals the ordinary kernel's bit for bit."""
-import os
-
+"""GPU parity of the tiled scale layout (MXFP8_SCALES_TILED), of the persistent GEMM kernel with a bounded
+number of workgroups, and of the GEMM that also emits the MXFP8 copies of its BF16 output, through the C
+ABI against the CPU oracle. The layout only moves scale bytes, so every value must equal what the
+row-major entry points are held to: quantized bytes bit-exact, products within the tolerance of
+test_gpu_gemm, and, on identical operands, identical to the row-major product bit for bit (the same
+instructions add the same numbers in the same order). The persistent kernel runs the same K steps in the
+same order as the one-tile-per-workgroup kernel, so the two agree bit for bit, whatever the number of
+workgroups."""
 import numpy as np
 import pytest
 import torch
@@ -19,7 +14,8 @@ import oracle
 import paper_2506_08027_amd as mx
 import scale_layout as sl
 from paper_2506_08027_amd import synth_inputs as si
-from test_gpu_gemm import TARGET_ELEM, _compare, hw_tolerance
+from mfma_model import hw_tolerance
+from test_gpu_gemm import FRO_HW, TARGET_ELEM, _compare
 
 pytestmark = pytest.mark.gpu
 TILED = mx.SCALES_TILED
@@ -105,7 +101,7 @@ def test_gemm_tiled_matches_oracle_and_row_major(shape):
     assert torch.equal(c_t, c_r)
     rows = np.unique(np.linspace(0, M - 1, min(M, 48)).astype(int))
     ref, absref = oracle.gemm_rows(*ops, rows)
-    _compare(c_t.cpu().numpy().astype(np.float64)[rows], ref, absref, TARGET_ELEM, None, f"tiled {shape}",
+    _compare(c_t.cpu().numpy().astype(np.float64)[rows], ref, absref, TARGET_ELEM, FRO_HW, f"tiled {shape}",
              extra=hw_tolerance(*ops, rows=rows))
 
 
@@ -165,21 +161,21 @@ def test_tiled_error_codes():
 
 
 # ---- persistent GEMM kernel ---------------------------------------------------------------------------
-class _persistent:
-    def __init__(self, workgroups):
-        self.n = str(workgroups)
-
-    def __enter__(self):
-        os.environ["MXFP8_GEMM_PERSISTENT"] = self.n
-
-    def __exit__(self, *exc):
-        os.environ.pop("MXFP8_GEMM_PERSISTENT", None)
+def _one_tile_per_workgroup(args, dtype, lay):
+    """The same product on the one-tile-per-workgroup kernel: an output whose rows are not 16-byte aligned
+    cannot take the persistent kernel's vector stores."""
+    M, N = args[1].shape[0], args[3].shape[0]
+    pad = torch.empty((M, N + 1), dtype=dtype, device="cuda")
+    mx.mxfp8_gemm_ex(*args, pad[:, :N], lay)
+    return pad[:, :N].contiguous()
 
 
-@pytest.mark.parametrize("shape,workgroups", [((256, 384, 384), 2), ((384, 256, 256), 6), ((2048, 4096, 512), 64),
-                                              ((2048, 4096, 512), 256)])
+@pytest.mark.parametrize("shape,workgroups", [((256, 384, 384), 2), ((384, 256, 256), 0), ((2048, 4096, 512), 64),
+                                              ((2048, 4096, 512), 0), ((4352, 4096, 256), 0)])
 @pytest.mark.parametrize("tiled", [False, True])
-def test_persistent_gemm_matches_oracle_and_ordinary_kernel(shape, workgroups, tiled):
+def test_persistent_gemm_matches_oracle_and_one_tile_kernel(shape, workgroups, tiled):
+    """Full-tile shapes run on the persistent kernel; 2 and 64 workgroups walk over 3 and 2 tiles each, the
+    last shape has 272 tiles of 256 x 256 for 256 compute units (16 workgroups take a second tile)."""
     M, N, K = shape
     ops = _operands(M, N, K, seed=100 + M + K)
     a_q, a_s, b_q, b_s = ops
@@ -187,41 +183,49 @@ def test_persistent_gemm_matches_oracle_and_ordinary_kernel(shape, workgroups, t
     sc = (lambda s: _dev(sl.tile(s, filler=0xFF))) if tiled else _dev
     args = ("fprop", _dev(a_q), sc(a_s), _dev(b_q), sc(b_s))
     for dtype in (torch.float32, torch.bfloat16):
-        plain = mx.gemm(*args, dtype, scale_layout=lay)
-        with _persistent(workgroups):
-            pers = mx.gemm(*args, dtype, scale_layout=lay)
+        bits = torch.int32 if dtype == torch.float32 else torch.int16
+        pers = mx.gemm(*args, dtype, scale_layout=lay, max_workgroups=workgroups)
+        plain = _one_tile_per_workgroup(args, dtype, lay)
         torch.cuda.synchronize()
-        assert torch.equal(plain.view(torch.int32 if dtype == torch.float32 else torch.int16),
-                           pers.view(torch.int32 if dtype == torch.float32 else torch.int16))
+        assert torch.equal(plain.view(bits), pers.view(bits))
     rows = np.unique(np.linspace(0, M - 1, min(M, 32)).astype(int))
     ref, absref = oracle.gemm_rows(*ops, rows)
-    with _persistent(workgroups):
-        got = mx.gemm(*args, torch.float32, scale_layout=lay)
+    got = mx.gemm(*args, torch.float32, scale_layout=lay, max_workgroups=workgroups)
     torch.cuda.synchronize()
-    _compare(got.cpu().numpy().astype(np.float64)[rows], ref, absref, TARGET_ELEM, None,
+    _compare(got.cpu().numpy().astype(np.float64)[rows], ref, absref, TARGET_ELEM, FRO_HW,
              f"persistent {shape} x{workgroups}", extra=hw_tolerance(*ops, rows=rows))
 
 
-def test_persistent_gemm_full_size_equals_ordinary_kernel():
-    """The benchmark's forward product with 256 persistent workgroups (7 tiles each), both layouts."""
+def test_persistent_gemm_full_size_equals_one_tile_kernel_and_ignores_the_bound():
+    """The benchmark's forward product (1792 tiles: 7 per workgroup on 256 compute units), both layouts; a
+    bound of 100 workgroups changes nothing in the result."""
     T, H, O = 8192, 4096, 14336
     X = _dev(si.activations(T, H, seed=2).view(np.int16)).view(torch.bfloat16)
     W = _dev(si.weights(O, H, seed=4).view(np.int16)).view(torch.bfloat16)
     for lay in (mx.SCALES_ROWMAJOR, TILED):
         x, w = mx.quantize(X, "rowwise", scale_layout=lay), mx.quantize(W, "rowwise", scale_layout=lay)
-        args = ("fprop", x["q_row"], x["s_row"], w["q_row"], w["s_row"], torch.bfloat16)
-        plain = mx.gemm(*args, scale_layout=lay)
-        with _persistent(256):
-            pers = mx.gemm(*args, scale_layout=lay)
+        args = ("fprop", x["q_row"], x["s_row"], w["q_row"], w["s_row"])
+        pers = mx.gemm(*args, torch.bfloat16, scale_layout=lay)
+        bounded = mx.gemm(*args, torch.bfloat16, scale_layout=lay, max_workgroups=100)
+        plain = _one_tile_per_workgroup(args, torch.bfloat16, lay)
         torch.cuda.synchronize()
         assert torch.equal(plain.view(torch.int16), pers.view(torch.int16))
+        assert torch.equal(bounded.view(torch.int16), pers.view(torch.int16))
+
+
+def test_negative_workgroup_bound_is_rejected():
+    a_q, a_s, b_q, b_s = (_dev(t) for t in _operands(128, 128, 256, seed=8))
+    with pytest.raises(mx.MXFP8Error) as e:
+        mx.gemm("fprop", a_q, a_s, b_q, b_s, max_workgroups=-1)
+    assert e.value.code == 5
 
 
 # ---- GEMM with the MXFP8 copies of its BF16 output from the same epilogue -------------------------------
-@pytest.mark.parametrize("shape", [(256, 384, 384), (128, 128, 256), (2048, 4096, 512)])
+@pytest.mark.parametrize("shape,workgroups", [((256, 384, 384), 2), ((128, 128, 256), 0), ((2048, 4096, 512), 0),
+                                              ((2048, 4096, 512), 50)])
 @pytest.mark.parametrize("tiled", [False, True])
 @pytest.mark.parametrize("axis", ["rowwise", "colwise", "both"])
-def test_fused_output_quantization_matches_gemm_then_quantize(shape, tiled, axis):
+def test_fused_output_quantization_matches_gemm_then_quantize(shape, workgroups, tiled, axis):
     """c must equal the plain BF16 product bit for bit, and the copies must be the oracle's quantization of
     those BF16 values: NaN rows (a NaN scale), rows with entries that overflow to Inf and ordinary rows."""
     M, N, K = shape
@@ -232,7 +236,7 @@ def test_fused_output_quantization_matches_gemm_then_quantize(shape, tiled, axis
     lay = TILED if tiled else mx.SCALES_ROWMAJOR
     sc = (lambda s: _dev(sl.tile(s, filler=0xFF))) if tiled else _dev
     args = ("fprop", _dev(a_q), sc(a_s), _dev(b_q), sc(b_s))
-    out = mx.gemm_quantize(*args, axis=axis, scale_layout=lay)
+    out = mx.gemm_quantize(*args, axis=axis, scale_layout=lay, max_workgroups=workgroups)
     plain = mx.gemm(*args, torch.bfloat16, scale_layout=lay)
     torch.cuda.synchronize()
     assert torch.equal(out["c"].view(torch.int16), plain.view(torch.int16))

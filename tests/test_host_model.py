@@ -182,7 +182,7 @@ def _operands(M, N, K, seed, spikes=False):
     return oracle.quantize_rowwise(np.asarray(a, np.float32)) + oracle.quantize_rowwise(np.asarray(b, np.float32))
 
 
-def _gemm_case(tmp_path, M, N, K, ops, bf16=False, ldc=None, tag="", tiled=False):
+def _gemm_case(tmp_path, M, N, K, ops, bf16=False, ldc=None, tag="", tiled=False, wg=0):
     a_q, a_s, b_q, b_s = ops
     ldc = ldc or N
     if tiled:   # filler bytes are 0xFF (a NaN scale): a kernel that read one as a scale would show it
@@ -190,7 +190,7 @@ def _gemm_case(tmp_path, M, N, K, ops, bf16=False, ldc=None, tag="", tiled=False
     names = [put(tmp_path, f"{n}{tag}.bin", v) for n, v in (("aq", a_q), ("as", a_s), ("bq", b_q), ("bs", b_s))]
     out = str(tmp_path / f"c{tag}.bin")
     return (f"gemm 0 {M} {N} {K} {'bf16' if bf16 else 'f32'} {ldc} {' '.join(names)} {out}"
-            + (" tiled" if tiled else "")), out
+            + (" tiled" if tiled else "") + (f" wg={wg}" if wg else "")), out
 
 
 def _check_gemm(out, M, N, ldc, ops, bf16, expect_full=True):
@@ -303,41 +303,38 @@ def test_dequantize_tiled_scales(hostmodel, tmp_path):
     assert np.array_equal(got[~np.isnan(want)], want[~np.isnan(want)])
 
 
-# ---- persistent GEMM kernel (opt-in through MXFP8_GEMM_PERSISTENT=<workgroups>) -------------------------
+# ---- persistent GEMM kernel (every problem made of full tiles; max_workgroups bounds its grid) ------------
 @pytest.mark.parametrize("mode,tiled", [(MODES[0], False), (MODES[3], True)], ids=["lazy-up-rowmajor", "eager-down-tiled"])
 def test_gemm_persistent_small_tiles(hostmodel, tmp_path, mode, tiled):
     """Workgroups that walk over 3, 2 and 1 tiles (6 tiles of 128x128 on 2, 4 and 6 workgroups), K of
     2 and 3 steps: the K pipeline runs across tile boundaries, each tile is stored once."""
-    lines, checks, envs = [], [], []
     for i, (M, N, K, bf16, wgs) in enumerate([(256, 384, 384, False, 2), (256, 384, 256, True, 4),
-                                               (384, 256, 384, False, 6)]):
+                                               (384, 256, 384, False, 0)]):
         ops = _operands(M, N, K, seed=80 + i)
-        line, out = _gemm_case(tmp_path, M, N, K, ops, bf16, tag=str(i), tiled=tiled)
-        _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=wgs, **mode)
-        assert calls[0] == (0, list(range(wgs)))
+        line, out = _gemm_case(tmp_path, M, N, K, ops, bf16, tag=str(i), tiled=tiled, wg=wgs)
+        _, calls = run_case(hostmodel, tmp_path, [line], **mode)
+        assert calls[0] == (0, list(range(wgs or 6)))
         _check_gemm(out, M, N, N, ops, bf16)
 
 
-@pytest.mark.parametrize("tune", [0, 1, 3, 4, 6])    # 2 (like 3) and 5 (like 6) differ only in a constant
-def test_gemm_persistent_large_tiles_sampled_workgroups(hostmodel, tmp_path, tune):
-    """256x256 configuration: 128 tiles on 64 workgroups (2 tiles each); first and last workgroup for the
-    default schedule, the last one for each schedule variant (MXFP8_GEMM_TUNE)."""
+@pytest.mark.parametrize("tiled,order", [(True, "up"), (False, "down")])
+def test_gemm_persistent_large_tiles_sampled_workgroups(hostmodel, tmp_path, tiled, order):
+    """256x256 configuration (requests spread over the K step): 128 tiles on 64 workgroups (2 tiles each),
+    first and last workgroup."""
     M, N, K = 2048, 4096, 384
     ops = _operands(M, N, K, seed=90, spikes=True)
-    line, out = _gemm_case(tmp_path, M, N, K, ops, bf16=True, tiled=True)
-    blocks = 2 if tune == 0 else 1
-    _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=64, MXFP8_GEMM_TUNE=tune,
-                        WAVESIM_BLOCKS=blocks, WAVESIM_ORDER="down" if tune % 2 else "up")
-    assert calls[0] == (0, [0, 63] if tune == 0 else [0])
-    assert _check_gemm(out, M, N, N, ops, True, expect_full=False) == 2 * blocks * 256 * 256
+    line, out = _gemm_case(tmp_path, M, N, K, ops, bf16=True, tiled=tiled, wg=64)
+    _, calls = run_case(hostmodel, tmp_path, [line], WAVESIM_BLOCKS=2, WAVESIM_ORDER=order)
+    assert calls[0] == (0, [0, 63])
+    assert _check_gemm(out, M, N, N, ops, True, expect_full=False) == 4 * 256 * 256
 
 
-def test_gemm_persistent_falls_back_for_ragged_shapes(hostmodel, tmp_path):
+def test_gemm_ragged_shapes_take_one_workgroup_per_tile(hostmodel, tmp_path):
     M, N, K = 200, 136, 384
     ops = _operands(M, N, K, seed=91)
-    line, out = _gemm_case(tmp_path, M, N, K, ops)
-    _, calls = run_case(hostmodel, tmp_path, [line], MXFP8_GEMM_PERSISTENT=2)
-    assert calls[0] == (0, [0, 1, 2, 3])                 # one workgroup per tile: the ordinary kernel ran
+    line, out = _gemm_case(tmp_path, M, N, K, ops, wg=2)
+    _, calls = run_case(hostmodel, tmp_path, [line])
+    assert calls[0] == (0, [0, 1, 2, 3])                 # the bound only applies to the persistent kernel
     _check_gemm(out, M, N, N, ops, False)
 
 
@@ -375,3 +372,66 @@ def test_validation_errors_reach_the_caller(hostmodel, tmp_path):
     bad_k = good.replace("gemm 0 32 32 128 f32 32", "gemm 0 32 32 128 f32 16")      # ldc < N
     res, calls = run_case(hostmodel, tmp_path, [bad_k], expect_ok=False)
     assert calls and calls[0][0] == 2
+
+
+# ---- GEMM that also emits the MXFP8 copies of its BF16 output -------------------------------------------
+def _fused_case(hostmodel, tmp_path, M, N, K, axis, tiled, seed, wg=0, **env):
+    """Runs mxfp8_gemm_quantize_ex with exact-size buffers under AddressSanitizer and checks, for every
+    output tile the simulated workgroups wrote, that c is the BF16 product and that the copies are the
+    oracle's quantization of exactly those BF16 values."""
+    a_q, a_s, b_q, b_s = _operands(M, N, K, seed=seed)
+    a_s = a_s.copy()
+    a_s[3, 1] = 0xFF                     # a NaN row of C
+    a_s[5, :] = 250                      # a row whose products overflow to +-Inf in BF16
+    ops = (a_q, a_s, b_q, b_s)
+    sa, sb = (sl.tile(a_s, filler=0xFF), sl.tile(b_s, filler=0xFF)) if tiled else (a_s, b_s)
+    names = [put(tmp_path, f"{n}.bin", v) for n, v in (("aq", a_q), ("as", sa), ("bq", b_q), ("bs", sb))]
+    prefix = str(tmp_path / "f")
+    _, calls = run_case(hostmodel, tmp_path,
+                        [f"gemmq 0 {M} {N} {K} {N} {axis} {' '.join(names)} {prefix}" + (" tiled" if tiled else "")
+                         + (f" wg={wg}" if wg else "")], **env)
+    assert calls[0][0] == 0
+    bits = np.fromfile(prefix + ".c", np.uint16).reshape(M, N)
+    written = bits != 0xA5A5
+    rows = np.unique(np.nonzero(written)[0])
+    cols = np.unique(np.nonzero(written)[1])
+    assert rows.size and rows.size % 32 == 0 and cols.size % 32 == 0
+    # the product itself, on the written part (one FP32 rounding of the modelled sum, one BF16 rounding)
+    ref, absum = oracle.gemm_rows(*ops, rows)
+    val = si.bf16_bits_to_f32(bits[rows]).astype(np.float64)
+    w = written[rows]
+    fin = w & np.isfinite(ref) & (absum < 3e38)
+    assert (np.abs(val - ref)[fin] <= (2.0 ** -23 * absum + 2.0 ** -8 * np.abs(ref) + 1e-300)[fin]).all()
+    # the copies: whole 32-blocks of written rows / columns, quantized from the stored BF16 bits
+    if axis & 1:
+        q = np.fromfile(prefix + ".q_row", np.uint8).reshape(M, N)
+        s = np.fromfile(prefix + ".s_row", np.uint8)
+        s = sl.untile(s, M, N // 32) if tiled else s.reshape(M, N // 32)
+        for r in rows:
+            c = np.nonzero(written[r])[0]
+            wq, ws = oracle.quantize_rowwise(np.ascontiguousarray(bits[r:r + 1, c]))
+            assert np.array_equal(q[r, c], wq[0]) and np.array_equal(s[r, c[::32] // 32], ws[0])
+    if axis & 2:
+        q = np.fromfile(prefix + ".q_colT", np.uint8).reshape(N, M)
+        s = np.fromfile(prefix + ".s_colT", np.uint8)
+        s = sl.untile(s, N, M // 32) if tiled else s.reshape(N, M // 32)
+        for c in cols:
+            r = np.nonzero(written[:, c])[0]
+            wq, ws = oracle.quantize_colwise(np.ascontiguousarray(bits[r, c:c + 1]))
+            assert np.array_equal(q[c, r], wq[0]) and np.array_equal(s[c, r[::32] // 32], ws[0])
+    return int(written.sum())
+
+
+@pytest.mark.parametrize("axis,tiled,mode", [(1, False, MODES[0]), (2, True, MODES[3]), (3, False, MODES[3]),
+                                             (3, True, MODES[0])])
+def test_fused_output_quantization_small_tiles(hostmodel, tmp_path, axis, tiled, mode):
+    """128x128 configuration, 6 tiles on 2 workgroups and one tile on the default grid."""
+    assert _fused_case(hostmodel, tmp_path, 256, 384, 384, axis, tiled, seed=300 + axis, wg=2, **mode) == 256 * 384
+    assert _fused_case(hostmodel, tmp_path, 128, 128, 256, axis, tiled, seed=310 + axis, **mode) == 128 * 128
+
+
+@pytest.mark.parametrize("axis,tiled", [(3, True), (3, False)])
+def test_fused_output_quantization_large_tiles_sampled_workgroups(hostmodel, tmp_path, axis, tiled):
+    """256x256 configuration, 128 tiles on 64 workgroups: the first and the last workgroup, two tiles each."""
+    n = _fused_case(hostmodel, tmp_path, 2048, 4096, 384, axis, tiled, seed=320, wg=64, WAVESIM_BLOCKS=2)
+    assert n == 4 * 256 * 256
