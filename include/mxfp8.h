@@ -178,6 +178,16 @@ mxfp8_status mxfp8_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t row
                                  void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst,
                                  mxfp8_scale_layout scale_layout, void *hip_stream);
 
+/*
+ * Measurement aid for benchmarks (no operation of the paper): `workgroups` workgroups of 4 wavefronts each
+ * issue iterations * 64 independent scaled FP8 matrix instructions (16x16x128, 65536 flop each) on register
+ * operands, without memory traffic, and then store one float per work-item to sink[workgroups * 256]
+ * (device memory, 4-byte aligned, contents meaningless). Timing the call gives the matrix rate this GPU
+ * sustains at whatever clock its power management settles on: workgroups * 4 * iterations * 64 * 65536 flop.
+ * workgroups in [0, 2^20], iterations in [0, 2^24], else MXFP8_ERR_SHAPE; workgroups == 0 does nothing.
+ */
+mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float *sink, void *hip_stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp8_status_string(mxfp8_status status);
 

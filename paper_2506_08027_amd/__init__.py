@@ -5,4 +5,4 @@ The work is done by hand-written HIP kernels behind a C ABI (``include/mxfp8.h``
 """
 from .binding import (BF16, BOTH, COLWISE, DGRAD, F32, FPROP, ROWWISE, SCALES_ROWMAJOR, SCALES_TILED,  # noqa: F401
                       WGRAD, MXFP8Error, dequantize, gemm, gemm_quantize, load, mxfp8_dequantize, mxfp8_dequantize_ex, mxfp8_gemm,
-                      mxfp8_gemm_ex, mxfp8_gemm_quantize_ex, mxfp8_quantize, mxfp8_quantize_ex, mxfp8_scale_bytes, quantize, status_string)
+                      mxfp8_gemm_ex, mxfp8_gemm_quantize_ex, mxfp8_mfma_rate_probe, mxfp8_quantize, mxfp8_quantize_ex, mxfp8_scale_bytes, quantize, status_string)

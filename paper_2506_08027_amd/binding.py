@@ -61,6 +61,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
     lib.mxfp8_scale_bytes.restype = i64
     lib.mxfp8_scale_bytes.argtypes = [i64, i64, ci]
+    lib.mxfp8_mfma_rate_probe.restype = ci
+    lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_status_string.restype = ctypes.c_char_p
     lib.mxfp8_status_string.argtypes = [ci]
     _lib = lib
@@ -218,6 +220,17 @@ def mxfp8_dequantize_ex(q, s, dst, scale_layout=SCALES_ROWMAJOR, stream=None) ->
                                     scale_layout, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_dequantize")
+
+
+def mxfp8_mfma_rate_probe(workgroups: int, iterations: int, sink, stream=None) -> float:
+    """Enqueue the register-only matrix-instruction loop; returns the flop it performs (time it yourself)."""
+    _need_cuda(sink)
+    if sink.dtype != torch.float32 or sink.numel() < workgroups * 256 or not sink.is_contiguous():
+        raise ValueError("sink must be a dense float32 tensor of workgroups * 256 elements")
+    rc = load().mxfp8_mfma_rate_probe(workgroups, iterations, _ptr(sink), _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_mfma_rate_probe")
+    return workgroups * 4.0 * iterations * 64 * 65536
 
 
 # ---- conveniences that only allocate the outputs ----------------------------------------------

@@ -17,6 +17,7 @@ hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8
                              int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
                              uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, int max_workgroups,
                              hipStream_t stream);
+hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream);
 }  // namespace mxfp8
 
 namespace {
@@ -170,6 +171,20 @@ mxfp8_status mxfp8_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t row
     const hipError_t e = mxfp8::launch_dequantize(q, s, rows, cols, dst, dst_dtype == MXFP8_BF16,
                                                   scale_layout == MXFP8_SCALES_TILED, ld_dst,
                                                   static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float *sink, void *hip_stream)
+{
+    if (workgroups < 0 || iterations < 0 || workgroups > (1 << 20) || iterations > (1 << 24))
+        return MXFP8_ERR_SHAPE;
+    if (workgroups == 0)
+        return MXFP8_OK;
+    if (!sink)
+        return MXFP8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(sink) % 4)
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_mfma_rate(workgroups, iterations, sink, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

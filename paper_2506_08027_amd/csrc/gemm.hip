@@ -775,16 +775,17 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
     // Problems made of full tiles run on the persistent kernel (its epilogue addresses a tile's rows with
     // 32-bit offsets from the tile origin); everything else takes one workgroup per tile.
     if (M % Cfg::BM == 0 && N % Cfg::BN == 0 && K >= 2 * BK && vec_store && ldc_bytes * Cfg::BM < (int64_t(1) << 31)) {
-        auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED, spread_fits<Cfg>()>;
         int grid = 0;
         hipError_t e = persistent_grid(tiles_m * tiles_n, max_workgroups, grid);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    Cfg::LDS_BYTES);
         if (e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, a_q, a_s, b_q, b_s, M, N,
-                           K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, static_cast<uint8_t *>(nullptr),
+        auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED, spread_fits<Cfg>()>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                Cfg::LDS_BYTES);
+        if (e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, a_q, a_s, b_q, b_s, M, N, K,
+                           static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, static_cast<uint8_t *>(nullptr),
                            static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr),
                            static_cast<uint8_t *>(nullptr));
         return hipGetLastError();
