@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     for (int i = 0; i < ROWS; ++i) {
         x[i] = make_uint4(0, 0, 0, 0);
         if (active)
-            x[i] = *reinterpret_cast<const uint4 *>(src + (row0 + i) * ld_bytes + col0 * ESIZE);
+            x[i] = stream_load(reinterpret_cast<const uint4 *>(src + (row0 + i) * ld_bytes + col0 * ESIZE));
     }
 
     if constexpr (ROW) {
@@ -180,9 +180,9 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
             if (active) {
                 uint8_t *qp = q_row + (row0 + i) * cols + col0;
                 if constexpr (BF16)
-                    *reinterpret_cast<uint2 *>(qp) = make_uint2(q0, q1);
+                    stream_store(reinterpret_cast<uint2 *>(qp), make_uint2(q0, q1));
                 else
-                    *reinterpret_cast<uint32_t *>(qp) = q0;
+                    stream_store(reinterpret_cast<uint32_t *>(qp), q0);
             }
             if ((cc % LANES_PER_BLOCK) == 0)
                 lds_rs[(lrow0 + i) * 4 + cc / LANES_PER_BLOCK] = (uint8_t)sb;
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
             if (c < cols && r < rows) {
                 const int slot16 = part ^ ((col / VEC) & 7);
                 const uint4 v = *reinterpret_cast<const uint4 *>(lds_q + col * kTile + slot16 * 16);
-                *reinterpret_cast<uint4 *>(q_colT + c * rows + r) = v;
+                stream_store(reinterpret_cast<uint4 *>(q_colT + c * rows + r), v);
             }
         }
         if (tid >= kTile) {  // the upper half of the workgroup, so that it overlaps the row scales

@@ -77,7 +77,7 @@ def build(work, gemm_text):
     binary = os.path.join(work, "hostmodel")
     cmd = ["/opt/rocm/llvm/bin/clang++", "-std=c++17", "-x", "c++", "-I", os.path.join(HERE, "shim"), "-O2",
            "-Wno-unknown-pragmas", "-Wno-psabi", "-o", binary, os.path.join(work, "driver.cpp")]
-    cmd += [os.path.join(csrc, f) for f in ("api.hip", "quantize.hip", "dequantize.hip", "gemm.hip")]
+    cmd += [os.path.join(csrc, f) for f in ("api.hip", "quantize.hip", "dequantize.hip", "gemm.hip", "diagnostics.hip")]
     subprocess.run(cmd, check=True, capture_output=True)
     return binary
 
