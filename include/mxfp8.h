@@ -46,7 +46,7 @@ typedef enum {
     MXFP8_ERR_SHAPE = 2, /* negative dimension, axis not a multiple of 32, ld too small */
     MXFP8_ERR_ALIGN = 3, /* pointer or leading dimension not aligned as documented */
     MXFP8_ERR_DTYPE = 4, /* unknown mxfp8_dtype */
-    MXFP8_ERR_MODE = 5,  /* unknown mxfp8_axis / mxfp8_pass / mxfp8_scale_layout, negative workgroup bound */
+    MXFP8_ERR_MODE = 5,  /* unknown axis / pass / scale layout / element / scale rule, negative workgroup bound */
     MXFP8_ERR_HIP = 6    /* kernel launch rejected by the HIP runtime, or not a gfx950 device */
 } mxfp8_status;
 
@@ -67,6 +67,20 @@ typedef enum { MXFP8_FPROP = 0, MXFP8_DGRAD = 1, MXFP8_WGRAD = 2 } mxfp8_pass;
  *                          blocks >= nb are unspecified filler. Must be 16-byte aligned.
  */
 typedef enum { MXFP8_SCALES_ROWMAJOR = 0, MXFP8_SCALES_TILED = 1 } mxfp8_scale_layout;
+
+/*
+ * The two choices of the conversion that the paper studies as ablations. The recipe, and every entry point
+ * without these arguments, is MXFP8_E4M3 with MXFP8_SCALE_ROUND_UP.
+ *   mxfp8_element     MXFP8_E4M3: 1-4-3, bias 7, max 448 (Table 1). MXFP8_E5M2: 1-5-2, bias 15, max 57344,
+ *                     IEEE-style Inf/NaN codes (Table 1; Section 3.2.2 compares the two per tensor role).
+ *   mxfp8_scale_rule  MXFP8_SCALE_ROUND_UP: X = amax / max rounded UP to a power of two (Algorithm 1,
+ *                     Appendix A.1): no element of a finite block exceeds the FP8 maximum.
+ *                     MXFP8_SCALE_OCP_V1: X = 2^(floor(log2(amax)) - emax), i.e. rounded DOWN (the OCP v1.0
+ *                     suggestion that Section 3.3 replaces): elements of a block whose amax has a
+ *                     significand above 1.75 exceed the maximum and saturate to +-max.
+ */
+typedef enum { MXFP8_E4M3 = 0, MXFP8_E5M2 = 1 } mxfp8_element;
+typedef enum { MXFP8_SCALE_ROUND_UP = 0, MXFP8_SCALE_OCP_V1 = 1 } mxfp8_scale_rule;
 
 /* Size in bytes of the scale buffer of a [rows x cols] operand in `layout` (host arithmetic only);
  * -1 for negative sizes, sizes beyond 2^31 - 1, cols not a multiple of 32 or an unknown layout. */
@@ -103,6 +117,16 @@ mxfp8_status mxfp8_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t r
                                int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
                                uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout,
                                void *hip_stream);
+
+/* mxfp8_quantize_ex with the element format and the scale rule chosen by the caller (Table 1; Section 3.2.2;
+ * Section 3.3 with Figure 4's comparison arm). Same layouts, requirements and special-value rules; values that
+ * round beyond the largest finite code saturate to it with the sign of the input (Appendix A.2), infinities
+ * included; a block with a NaN gets scale 0xFF and all elements 0x7F in either format. Unknown element or
+ * rule: MXFP8_ERR_MODE. */
+mxfp8_status mxfp8_quantize_mode_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                                    int64_t ld_src, mxfp8_axis axis, mxfp8_element element, mxfp8_scale_rule rule,
+                                    uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                                    mxfp8_scale_layout scale_layout, void *hip_stream);
 
 /*
  * C [M x N] = A [M x K] * B [N x K]^T with per-block scales (Section 2, Appendix A.3):
@@ -177,6 +201,12 @@ mxfp8_status mxfp8_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, 
 mxfp8_status mxfp8_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
                                  void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst,
                                  mxfp8_scale_layout scale_layout, void *hip_stream);
+
+/* mxfp8_dequantize_ex for element bytes in `element` format (Section 2 decode; Table 1): E5M2 codes 0x7C / 0xFC
+ * decode to +-Inf, 0x7D..0x7F / 0xFD..0xFF to NaN. */
+mxfp8_status mxfp8_dequantize_mode_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
+                                      mxfp8_element element, void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst,
+                                      mxfp8_scale_layout scale_layout, void *hip_stream);
 
 /*
  * Measurement aid for benchmarks (no operation of the paper): `workgroups` workgroups of 4 wavefronts each

@@ -20,6 +20,8 @@ F32, BF16 = 0, 1
 ROWWISE, COLWISE, BOTH = 1, 2, 3
 FPROP, DGRAD, WGRAD = 0, 1, 2
 SCALES_ROWMAJOR, SCALES_TILED = 0, 1
+E4M3, E5M2 = 0, 1
+SCALE_ROUND_UP, SCALE_OCP_V1 = 0, 1
 K_BLOCK = 32
 
 _AXIS = {"rowwise": ROWWISE, "colwise": COLWISE, "both": BOTH, ROWWISE: ROWWISE, COLWISE: COLWISE, BOTH: BOTH}
@@ -61,6 +63,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
     lib.mxfp8_scale_bytes.restype = i64
     lib.mxfp8_scale_bytes.argtypes = [i64, i64, ci]
+    lib.mxfp8_quantize_mode_ex.restype = ci
+    lib.mxfp8_quantize_mode_ex.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, ci, vp]
+    lib.mxfp8_dequantize_mode_ex.restype = ci
+    lib.mxfp8_dequantize_mode_ex.argtypes = [vp, vp, i64, i64, ci, vp, ci, i64, ci, vp]
     lib.mxfp8_mfma_rate_probe.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_status_string.restype = ctypes.c_char_p
@@ -127,6 +133,13 @@ def mxfp8_quantize_ex(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=Non
                       scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
     """mxfp8_quantize with the scale bytes stored in `scale_layout` (tiled buffers: flat uint8 of
     mxfp8_scale_bytes(rows, cols) / mxfp8_scale_bytes(cols, rows) bytes)."""
+    mxfp8_quantize_mode_ex(src, axis, E4M3, SCALE_ROUND_UP, q_row, s_row, q_colT, s_colT, scale_layout, stream)
+
+
+def mxfp8_quantize_mode_ex(src, axis, element=E4M3, rule=SCALE_ROUND_UP, q_row=None, s_row=None, q_colT=None,
+                           s_colT=None, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """mxfp8_quantize_ex with the element format (E4M3 / E5M2) and the scale rule (SCALE_ROUND_UP /
+    SCALE_OCP_V1) of the paper's ablations."""
     _need_cuda(src, q_row, s_row, q_colT, s_colT)
     if src.dim() != 2 or (src.numel() and src.stride(1) != 1):
         raise ValueError("src must be 2-D with contiguous rows")
@@ -137,9 +150,9 @@ def mxfp8_quantize_ex(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=Non
             _check_scales(s_row, rows, cols, scale_layout, "s_row")
         if s_colT is not None and _AXIS[axis] & COLWISE:
             _check_scales(s_colT, cols, rows, scale_layout, "s_colT")
-    rc = load().mxfp8_quantize_ex(_ptr(src), _dtype_code(src.dtype), rows, cols, ld, _AXIS[axis],
-                                  _ptr(q_row), _ptr(s_row), _ptr(q_colT), _ptr(s_colT), scale_layout,
-                                  _stream(stream))
+    rc = load().mxfp8_quantize_mode_ex(_ptr(src), _dtype_code(src.dtype), rows, cols, ld, _AXIS[axis], element, rule,
+                                       _ptr(q_row), _ptr(s_row), _ptr(q_colT), _ptr(s_colT), scale_layout,
+                                       _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_quantize")
 
@@ -204,8 +217,8 @@ def mxfp8_dequantize(q, s, dst, stream=None) -> None:
     mxfp8_dequantize_ex(q, s, dst, SCALES_ROWMAJOR, stream)
 
 
-def mxfp8_dequantize_ex(q, s, dst, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
-    """mxfp8_dequantize with s stored in `scale_layout`."""
+def mxfp8_dequantize_ex(q, s, dst, scale_layout=SCALES_ROWMAJOR, stream=None, element=E4M3) -> None:
+    """mxfp8_dequantize with s stored in `scale_layout` and the element bytes in `element` format."""
     _need_cuda(q, s, dst)
     rows, cols = q.shape
     if tuple(dst.shape) != (rows, cols):
@@ -216,8 +229,8 @@ def mxfp8_dequantize_ex(q, s, dst, scale_layout=SCALES_ROWMAJOR, stream=None) ->
     if dst.numel() and dst.stride(1) != 1:
         raise ValueError("dst rows must be contiguous")
     ld = dst.stride(0) if rows > 1 else max(cols, 1)
-    rc = load().mxfp8_dequantize_ex(_ptr(q), _ptr(s), rows, cols, _ptr(dst), _dtype_code(dst.dtype), ld,
-                                    scale_layout, _stream(stream))
+    rc = load().mxfp8_dequantize_mode_ex(_ptr(q), _ptr(s), rows, cols, element, _ptr(dst), _dtype_code(dst.dtype), ld,
+                                         scale_layout, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_dequantize")
 
@@ -233,9 +246,14 @@ def mxfp8_mfma_rate_probe(workgroups: int, iterations: int, sink, stream=None) -
     return workgroups * 4.0 * iterations * 64 * 65536
 
 
+def mxfp8_dequantize_mode_ex(q, s, element, dst, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """mxfp8_dequantize_ex for element bytes in `element` format (E4M3 / E5M2)."""
+    mxfp8_dequantize_ex(q, s, dst, scale_layout, stream, element)
+
+
 # ---- conveniences that only allocate the outputs ----------------------------------------------
 
-def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR):
+def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR, element=E4M3, rule=SCALE_ROUND_UP):
     """Allocate outputs and call mxfp8_quantize_ex. Returns a dict with the selected copies:
     'q_row' [R x C], 's_row' [R x C/32], 'q_colT' [C x R], 's_colT' [C x R/32] (uint8); with
     tiled scales 's_row' and 's_colT' are flat buffers of mxfp8_scale_bytes bytes."""
@@ -252,8 +270,8 @@ def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR):
         out["q_colT"] = torch.empty((cols, rows), **u8)
         out["s_colT"] = torch.empty((mxfp8_scale_bytes(cols, rows, scale_layout),) if tiled
                                     else (cols, rows // K_BLOCK), **u8)
-    mxfp8_quantize_ex(src, ax, out.get("q_row"), out.get("s_row"), out.get("q_colT"), out.get("s_colT"),
-                      scale_layout)
+    mxfp8_quantize_mode_ex(src, ax, element, rule, out.get("q_row"), out.get("s_row"), out.get("q_colT"),
+                           out.get("s_colT"), scale_layout)
     return out
 
 
@@ -282,7 +300,7 @@ def gemm_quantize(pass_, a_q, a_s, b_q, b_s, axis="both", scale_layout=SCALES_RO
     return out
 
 
-def dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):
+def dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, element=E4M3):
     dst = torch.empty(tuple(q.shape), dtype=out_dtype, device=q.device)
-    mxfp8_dequantize_ex(q, s, dst, scale_layout)
+    mxfp8_dequantize_ex(q, s, dst, scale_layout, element=element)
     return dst

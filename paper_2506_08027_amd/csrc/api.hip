@@ -7,9 +7,9 @@
 namespace mxfp8 {
 hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
                            uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales,
-                           hipStream_t stream);
+                           int mode, hipStream_t stream);
 hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
-                             bool bf16, bool tiled_scales, int64_t ld, hipStream_t stream);
+                             bool bf16, bool tiled_scales, bool e5m2, int64_t ld, hipStream_t stream);
 hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
                        int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc, int max_workgroups,
                        hipStream_t stream);
@@ -55,9 +55,19 @@ mxfp8_status mxfp8_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t r
                                uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout,
                                void *hip_stream)
 {
+    return mxfp8_quantize_mode_ex(src, src_dtype, rows, cols, ld_src, axis, MXFP8_E4M3, MXFP8_SCALE_ROUND_UP, q_row, s_row,
+                                  q_colT, s_colT, scale_layout, hip_stream);
+}
+
+mxfp8_status mxfp8_quantize_mode_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                                    int64_t ld_src, mxfp8_axis axis, mxfp8_element element, mxfp8_scale_rule rule,
+                                    uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                                    mxfp8_scale_layout scale_layout, void *hip_stream)
+{
     if (!valid_dtype(src_dtype))
         return MXFP8_ERR_DTYPE;
-    if (!valid_layout(scale_layout))
+    if (!valid_layout(scale_layout) || (element != MXFP8_E4M3 && element != MXFP8_E5M2) ||
+        (rule != MXFP8_SCALE_ROUND_UP && rule != MXFP8_SCALE_OCP_V1))
         return MXFP8_ERR_MODE;
     if (axis != MXFP8_ROWWISE && axis != MXFP8_COLWISE && axis != MXFP8_BOTH)
         return MXFP8_ERR_MODE;
@@ -76,6 +86,7 @@ mxfp8_status mxfp8_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t r
         return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_quantize(src, src_dtype == MXFP8_BF16, rows, cols, ld_src, (int)axis,
                                                 q_row, s_row, q_colT, s_colT, tiled,
+                                                (element == MXFP8_E5M2 ? 1 : 0) | (rule == MXFP8_SCALE_OCP_V1 ? 2 : 0),
                                                 static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
@@ -156,9 +167,16 @@ mxfp8_status mxfp8_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t row
                                  mxfp8_dtype dst_dtype, int64_t ld_dst, mxfp8_scale_layout scale_layout,
                                  void *hip_stream)
 {
+    return mxfp8_dequantize_mode_ex(q, s, rows, cols, MXFP8_E4M3, dst, dst_dtype, ld_dst, scale_layout, hip_stream);
+}
+
+mxfp8_status mxfp8_dequantize_mode_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
+                                      mxfp8_element element, void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst,
+                                      mxfp8_scale_layout scale_layout, void *hip_stream)
+{
     if (!valid_dtype(dst_dtype))
         return MXFP8_ERR_DTYPE;
-    if (!valid_layout(scale_layout))
+    if (!valid_layout(scale_layout) || (element != MXFP8_E4M3 && element != MXFP8_E5M2))
         return MXFP8_ERR_MODE;
     if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || cols % 32 || ld_dst < cols)
         return MXFP8_ERR_SHAPE;
@@ -169,7 +187,7 @@ mxfp8_status mxfp8_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t row
     if (!aligned16(q) || !aligned16(dst) || (ld_dst * esize(dst_dtype)) % 16)
         return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_dequantize(q, s, rows, cols, dst, dst_dtype == MXFP8_BF16,
-                                                  scale_layout == MXFP8_SCALES_TILED, ld_dst,
+                                                  scale_layout == MXFP8_SCALES_TILED, element == MXFP8_E5M2, ld_dst,
                                                   static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
@@ -196,7 +214,7 @@ const char *mxfp8_status_string(mxfp8_status status)
     case MXFP8_ERR_SHAPE: return "bad shape: negative, not a multiple of the block size, or leading dimension too small";
     case MXFP8_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
     case MXFP8_ERR_DTYPE: return "unknown element type";
-    case MXFP8_ERR_MODE: return "unknown axis, pass or scale layout, or a negative workgroup bound";
+    case MXFP8_ERR_MODE: return "unknown axis, pass, scale layout, element format or scale rule, or a negative workgroup bound";
     case MXFP8_ERR_HIP: return "HIP launch failed (is this a gfx950 device?)";
     }
     return "unknown status";

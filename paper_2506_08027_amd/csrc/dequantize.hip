@@ -10,10 +10,10 @@ namespace mxfp8 {
 
 typedef float v2f __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ void decode4(uint32_t q, int e, float out[4])
+template <bool E5M2> __device__ __forceinline__ void decode4(uint32_t q, int e, float out[4])
 {
-    const v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)q, false);
-    const v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)q, true);
+    const v2f lo = E5M2 ? __builtin_amdgcn_cvt_pk_f32_bf8((int)q, false) : __builtin_amdgcn_cvt_pk_f32_fp8((int)q, false);
+    const v2f hi = E5M2 ? __builtin_amdgcn_cvt_pk_f32_bf8((int)q, true) : __builtin_amdgcn_cvt_pk_f32_fp8((int)q, true);
     out[0] = ldexpf(lo[0], e);
     out[1] = ldexpf(lo[1], e);
     out[2] = ldexpf(hi[0], e);
@@ -26,7 +26,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
-template <bool BF16, bool TILED>
+template <bool BF16, bool TILED, bool E5M2>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restrict__ q,
                                                          const uint8_t *__restrict__ s, int64_t rows,
                                                          int64_t cols, uint8_t *__restrict__ dst,
@@ -52,8 +52,8 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restri
         if constexpr (BF16) {
             const uint2 qq = *reinterpret_cast<const uint2 *>(q + r * cols + c);
             float v[8];
-            decode4(qq.x, e, v);
-            decode4(qq.y, e, v + 4);
+            decode4<E5M2>(qq.x, e, v);
+            decode4<E5M2>(qq.y, e, v + 4);
             if (sb == 0xFF)
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restri
         } else {
             const uint32_t qq = *reinterpret_cast<const uint32_t *>(q + r * cols + c);
             float v[4];
-            decode4(qq, e, v);
+            decode4<E5M2>(qq, e, v);
             if (sb == 0xFF)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restri
     }
 }
 
-template <bool TILED>
+template <bool TILED, bool E5M2>
 static hipError_t launch_dequantize_t(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
                                       bool bf16, int64_t ld, hipStream_t stream)
 {
@@ -83,19 +83,22 @@ static hipError_t launch_dequantize_t(const uint8_t *q, const uint8_t *s, int64_
     if (blocks > 256 * 64)
         blocks = 256 * 64;  // grid-stride beyond 64 workgroups per compute unit
     if (bf16)
-        hipLaunchKernelGGL((dequantize_kernel<true, TILED>), dim3((unsigned)blocks), dim3(256), 0, stream, q, s, rows,
-                           cols, static_cast<uint8_t *>(dst), ld * 2);
+        hipLaunchKernelGGL((dequantize_kernel<true, TILED, E5M2>), dim3((unsigned)blocks), dim3(256), 0, stream, q, s,
+                           rows, cols, static_cast<uint8_t *>(dst), ld * 2);
     else
-        hipLaunchKernelGGL((dequantize_kernel<false, TILED>), dim3((unsigned)blocks), dim3(256), 0, stream, q, s, rows,
-                           cols, static_cast<uint8_t *>(dst), ld * 4);
+        hipLaunchKernelGGL((dequantize_kernel<false, TILED, E5M2>), dim3((unsigned)blocks), dim3(256), 0, stream, q, s,
+                           rows, cols, static_cast<uint8_t *>(dst), ld * 4);
     return hipGetLastError();
 }
 
 hipError_t launch_dequantize(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
-                             bool bf16, bool tiled_scales, int64_t ld, hipStream_t stream)
+                             bool bf16, bool tiled_scales, bool e5m2, int64_t ld, hipStream_t stream)
 {
-    return tiled_scales ? launch_dequantize_t<true>(q, s, rows, cols, dst, bf16, ld, stream)
-                        : launch_dequantize_t<false>(q, s, rows, cols, dst, bf16, ld, stream);
+    if (e5m2)
+        return tiled_scales ? launch_dequantize_t<true, true>(q, s, rows, cols, dst, bf16, ld, stream)
+                            : launch_dequantize_t<false, true>(q, s, rows, cols, dst, bf16, ld, stream);
+    return tiled_scales ? launch_dequantize_t<true, false>(q, s, rows, cols, dst, bf16, ld, stream)
+                        : launch_dequantize_t<false, false>(q, s, rows, cols, dst, bf16, ld, stream);
 }
 
 }  // namespace mxfp8

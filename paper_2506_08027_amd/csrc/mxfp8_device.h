@@ -75,6 +75,32 @@ __device__ __forceinline__ uint32_t scale_byte_from_bf16_bits(uint32_t abs_bits1
     return (uint32_t)s;
 }
 
+// ---- ablation arms (Table 1: E5M2 elements; Section 3.3: the OCP v1 scale rule the recipe replaces) ----
+// MODE bit 0: elements are E5M2 (1-5-2, bias 15, max 57344 = 1.75 * 2^15, code 0x7B) instead of E4M3;
+// MODE bit 1: the scale exponent is floor(log2(amax)) - emax (amax / max rounded DOWN to a power of two)
+//             instead of Algorithm 1's round-up, so that block maxima above 1.75 * 2^e saturate.
+// MODE 0 is the recipe and takes the functions above.
+constexpr int kModeE5M2 = 1, kModeOcpRule = 2;
+template <int MODE> constexpr uint32_t max_code() { return (MODE & kModeE5M2) ? 0x7Bu : 0x7Eu; }
+template <int MODE> constexpr int emax() { return (MODE & kModeE5M2) ? 15 : 8; }
+template <int MODE> __device__ __forceinline__ uint32_t scale_byte_mode_f32_bits(uint32_t abs_bits)
+{
+    // round-up rule: the mantissa carry of Algorithm 1's bit form; OCP rule: the exponent field itself
+    int s = (int)(((MODE & kModeOcpRule) ? abs_bits : abs_bits + 0x1FFFFFu) >> 23) - emax<MODE>();
+    s = s < 0 ? 0 : s;
+    if (abs_bits >= 0x7F800000u)
+        s = abs_bits > 0x7F800000u ? 0xFF : 254;
+    return (uint32_t)s;
+}
+template <int MODE> __device__ __forceinline__ uint32_t scale_byte_mode_bf16_bits(uint32_t abs_bits16)
+{
+    int s = (int)(((MODE & kModeOcpRule) ? abs_bits16 : abs_bits16 + 0x1Fu) >> 7) - emax<MODE>();
+    s = s < 0 ? 0 : s;
+    if (abs_bits16 >= 0x7F80u)
+        s = abs_bits16 > 0x7F80u ? 0xFF : 254;
+    return (uint32_t)s;
+}
+
 // The conversion instructions divide by 2^(exponent field of the scale operand - 127) and read an
 // exponent field of 0 as 2^-127, so the scale byte shifted into the exponent field is the operand.
 __device__ __forceinline__ float scale_operand(uint32_t scale_byte)
@@ -101,6 +127,32 @@ __device__ __forceinline__ uint32_t cvt2_bf16(uint32_t old, uint32_t pair, float
     v2s r = hi ? __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(o, p, scale, true)
                : __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(o, p, scale, false);
     return __builtin_bit_cast(uint32_t, r);
+}
+
+// E5M2 forms of the two conversions (v_cvt_scalef32_pk_bf8_{f32,bf16}): same operands, same rounding.
+__device__ __forceinline__ uint32_t cvt2_e5m2_f32(uint32_t old, float a, float b, float scale, bool hi)
+{
+    v2s o = __builtin_bit_cast(v2s, old);
+    v2s r = hi ? __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(o, a, b, scale, true)
+               : __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(o, a, b, scale, false);
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ uint32_t cvt2_e5m2_bf16(uint32_t old, uint32_t pair, float scale, bool hi)
+{
+    v2s o = __builtin_bit_cast(v2s, old);
+    v2bf p = __builtin_bit_cast(v2bf, pair);
+    v2s r = hi ? __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(o, p, scale, true)
+               : __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(o, p, scale, false);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// Saturation for the ablation arms (Appendix A.2: what exceeds the FP8 maximum after rounding is clamped to
+// it): the converters answer with a code above the largest finite one (NaN, or Inf for E5M2) whenever the
+// scaled value rounds beyond the maximum; such a byte, and the byte of an infinite input, becomes
+// sign | largest finite code, the sign taken from the input. Only for blocks without NaN.
+template <int MODE> __device__ __forceinline__ uint32_t saturate_byte(uint32_t q, bool negative, bool input_inf)
+{
+    return ((q & 0x7Fu) > max_code<MODE>() || input_inf) ? (negative ? 0x80u : 0u) | max_code<MODE>() : q;
 }
 
 // Saturating rule for infinities: the element byte becomes sign | 0x7E (+-448).

@@ -53,12 +53,27 @@ template <bool BF16> __device__ __forceinline__ uint32_t lane_amax(const uint4 &
     }
 }
 
-template <bool BF16> __device__ __forceinline__ uint32_t scale_byte(uint32_t abs_bits)
+template <bool BF16, int MODE> __device__ __forceinline__ uint32_t scale_byte(uint32_t abs_bits)
 {
-    if constexpr (BF16)
-        return scale_byte_from_bf16_bits(abs_bits);
+    if constexpr (MODE == 0)
+        return BF16 ? scale_byte_from_bf16_bits(abs_bits) : scale_byte_from_f32_bits(abs_bits);
     else
-        return scale_byte_from_f32_bits(abs_bits);
+        return BF16 ? scale_byte_mode_bf16_bits<MODE>(abs_bits) : scale_byte_mode_f32_bits<MODE>(abs_bits);
+}
+// the pair conversions in the element format of MODE
+template <int MODE> __device__ __forceinline__ uint32_t cvt_pair_bf16(uint32_t old, uint32_t pair, float sc, bool hi)
+{
+    if constexpr (MODE & kModeE5M2)
+        return cvt2_e5m2_bf16(old, pair, sc, hi);
+    else
+        return cvt2_bf16(old, pair, sc, hi);
+}
+template <int MODE> __device__ __forceinline__ uint32_t cvt_pair_f32(uint32_t old, float a, float b, float sc, bool hi)
+{
+    if constexpr (MODE & kModeE5M2)
+        return cvt2_e5m2_f32(old, a, b, sc, hi);
+    else
+        return cvt2_f32(old, a, b, sc, hi);
 }
 
 __device__ __forceinline__ uint32_t word_at(const uint4 &x, int j)
@@ -75,32 +90,37 @@ template <bool BF16> __device__ __forceinline__ uint32_t elem_at(const uint4 &x,
         return word_at(x, j);
     }
 }
-template <bool BF16> __device__ __forceinline__ uint32_t inf_byte(uint32_t bits, uint32_t q)
+// What becomes of element byte q whose input has the raw bits `bits`, in a block that holds no NaN: the
+// recipe (MODE 0) only has infinities to clamp; the ablation arms clamp whatever rounds beyond the maximum.
+template <bool BF16, int MODE> __device__ __forceinline__ uint32_t inf_byte(uint32_t bits, uint32_t q)
 {
-    if constexpr (BF16)
-        return inf_byte_bf16(bits, q);
-    else
-        return inf_byte_f32(bits, q);
+    if constexpr (MODE == 0) {
+        return BF16 ? inf_byte_bf16(bits, q) : inf_byte_f32(bits, q);
+    } else {
+        const bool negative = BF16 ? (bits & 0x8000u) != 0 : (bits & 0x80000000u) != 0;
+        const bool inf = BF16 ? (bits & 0x7FFFu) == 0x7F80u : (bits & 0x7FFFFFFFu) == 0x7F800000u;
+        return saturate_byte<MODE>(q, negative, inf);
+    }
 }
 
 // Four element bytes of column j taken from rows r0..r0+3 of the lane's registers.
-template <bool BF16, int NROWS>
+template <bool BF16, int MODE, int NROWS>
 __device__ __forceinline__ uint32_t convert_down4(const uint4 (&x)[NROWS], int r0, int j, float sc)
 {
     uint32_t q = 0;
     if constexpr (BF16) {
         // pair (row r, row r+1) of column j: bytes [1:0] or [3:2] of each word
         const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-        q = cvt2_bf16(q, __builtin_amdgcn_perm(word_at(x[r0 + 1], j >> 1), word_at(x[r0], j >> 1), sel), sc, false);
-        q = cvt2_bf16(q, __builtin_amdgcn_perm(word_at(x[r0 + 3], j >> 1), word_at(x[r0 + 2], j >> 1), sel), sc, true);
+        q = cvt_pair_bf16<MODE>(q, __builtin_amdgcn_perm(word_at(x[r0 + 1], j >> 1), word_at(x[r0], j >> 1), sel), sc, false);
+        q = cvt_pair_bf16<MODE>(q, __builtin_amdgcn_perm(word_at(x[r0 + 3], j >> 1), word_at(x[r0 + 2], j >> 1), sel), sc, true);
     } else {
-        q = cvt2_f32(q, __uint_as_float(word_at(x[r0], j)), __uint_as_float(word_at(x[r0 + 1], j)), sc, false);
-        q = cvt2_f32(q, __uint_as_float(word_at(x[r0 + 2], j)), __uint_as_float(word_at(x[r0 + 3], j)), sc, true);
+        q = cvt_pair_f32<MODE>(q, __uint_as_float(word_at(x[r0], j)), __uint_as_float(word_at(x[r0 + 1], j)), sc, false);
+        q = cvt_pair_f32<MODE>(q, __uint_as_float(word_at(x[r0 + 2], j)), __uint_as_float(word_at(x[r0 + 3], j)), sc, true);
     }
     return q;
 }
 
-template <bool BF16, bool ROW, bool COL, bool TILED>
+template <bool BF16, bool ROW, bool COL, bool TILED, int MODE>
 __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     const uint8_t *__restrict__ src, int64_t rows, int64_t cols, int64_t ld_bytes,
     uint8_t *__restrict__ q_row, uint8_t *__restrict__ s_row, uint8_t *__restrict__ q_colT,
@@ -149,19 +169,19 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
             am = umax(am, dpp_xor2(am));
             if constexpr (!BF16)
                 am = umax(am, dpp_half_mirror(am));
-            const uint32_t sb = scale_byte<BF16>(am);
+            const uint32_t sb = scale_byte<BF16, MODE>(am);
             const float sc = scale_operand(sb);
             uint32_t q0 = 0, q1 = 0;
             if constexpr (BF16) {
-                q0 = cvt2_bf16(q0, x[i].x, sc, false);
-                q0 = cvt2_bf16(q0, x[i].y, sc, true);
-                q1 = cvt2_bf16(q1, x[i].z, sc, false);
-                q1 = cvt2_bf16(q1, x[i].w, sc, true);
+                q0 = cvt_pair_bf16<MODE>(q0, x[i].x, sc, false);
+                q0 = cvt_pair_bf16<MODE>(q0, x[i].y, sc, true);
+                q1 = cvt_pair_bf16<MODE>(q1, x[i].z, sc, false);
+                q1 = cvt_pair_bf16<MODE>(q1, x[i].w, sc, true);
             } else {
-                q0 = cvt2_f32(q0, __uint_as_float(x[i].x), __uint_as_float(x[i].y), sc, false);
-                q0 = cvt2_f32(q0, __uint_as_float(x[i].z), __uint_as_float(x[i].w), sc, true);
+                q0 = cvt_pair_f32<MODE>(q0, __uint_as_float(x[i].x), __uint_as_float(x[i].y), sc, false);
+                q0 = cvt_pair_f32<MODE>(q0, __uint_as_float(x[i].z), __uint_as_float(x[i].w), sc, true);
             }
-            if (sb >= 254) {  // block holds Inf or NaN: rare, handled byte by byte
+            if (MODE != 0 || sb >= 254) {  // recipe: only blocks with Inf or NaN (rare); ablation arms: every block
                 if (sb == 0xFF) {
                     q0 = 0x7F7F7F7Fu;
                     q1 = 0x7F7F7F7Fu;
@@ -169,9 +189,9 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
                     uint32_t f0 = 0, f1 = 0;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        f0 |= inf_byte<BF16>(elem_at<BF16>(x[i], j), (q0 >> (8 * j)) & 0xFFu) << (8 * j);
+                        f0 |= inf_byte<BF16, MODE>(elem_at<BF16>(x[i], j), (q0 >> (8 * j)) & 0xFFu) << (8 * j);
                         if constexpr (BF16)
-                            f1 |= inf_byte<BF16>(elem_at<BF16>(x[i], 4 + j), (q1 >> (8 * j)) & 0xFFu) << (8 * j);
+                            f1 |= inf_byte<BF16, MODE>(elem_at<BF16>(x[i], 4 + j), (q1 >> (8 * j)) & 0xFFu) << (8 * j);
                     }
                     q0 = f0;
                     q1 = f1;
@@ -219,13 +239,13 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
                 am = (j & 1) ? cm[j >> 1] >> 16 : cm[j >> 1] & 0xFFFFu;
             else
                 am = cm[j];
-            const uint32_t sb = scale_byte<BF16>(am);
+            const uint32_t sb = scale_byte<BF16, MODE>(am);
             const float sc = scale_operand(sb);
             uint32_t q[ROWS / 4];  // one byte per row of this lane, in row order
 #pragma unroll
             for (int r = 0; r < ROWS / 4; ++r)
-                q[r] = convert_down4<BF16, ROWS>(x, 4 * r, j, sc);
-            if (sb >= 254) {
+                q[r] = convert_down4<BF16, MODE, ROWS>(x, 4 * r, j, sc);
+            if (MODE != 0 || sb >= 254) {
 #pragma unroll
                 for (int r = 0; r < ROWS / 4; ++r) {
                     if (sb == 0xFF) {
@@ -234,7 +254,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
                         uint32_t f = 0;
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            f |= inf_byte<BF16>(elem_at<BF16>(x[4 * r + i], j), (q[r] >> (8 * i)) & 0xFFu) << (8 * i);
+                            f |= inf_byte<BF16, MODE>(elem_at<BF16>(x[4 * r + i], j), (q[r] >> (8 * i)) & 0xFFu) << (8 * i);
                         q[r] = f;
                     }
                 }
@@ -318,7 +338,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     }
 }
 
-template <bool BF16, bool TILED>
+template <bool BF16, bool TILED, int MODE>
 static hipError_t launch_quantize_t(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis,
                                     uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
                                     hipStream_t stream)
@@ -332,26 +352,40 @@ static hipError_t launch_quantize_t(const void *src, int64_t rows, int64_t cols,
     const uint8_t *s = static_cast<const uint8_t *>(src);
     const int64_t ldb = ld * (BF16 ? 2 : 4);
     if (axis == 1)
-        hipLaunchKernelGGL((quantize_kernel<BF16, true, false, TILED>), grid, block, 0, stream, s, rows, cols, ldb,
+        hipLaunchKernelGGL((quantize_kernel<BF16, true, false, TILED, MODE>), grid, block, 0, stream, s, rows, cols, ldb,
                            q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x);
     else if (axis == 2)
-        hipLaunchKernelGGL((quantize_kernel<BF16, false, true, TILED>), grid, block, 0, stream, s, rows, cols, ldb,
+        hipLaunchKernelGGL((quantize_kernel<BF16, false, true, TILED, MODE>), grid, block, 0, stream, s, rows, cols, ldb,
                            q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x);
     else
-        hipLaunchKernelGGL((quantize_kernel<BF16, true, true, TILED>), grid, block, 0, stream, s, rows, cols, ldb,
+        hipLaunchKernelGGL((quantize_kernel<BF16, true, true, TILED, MODE>), grid, block, 0, stream, s, rows, cols, ldb,
                            q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x);
     return hipGetLastError();
 }
 
-hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
-                           uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales,
-                           hipStream_t stream)
+template <int MODE>
+static hipError_t launch_quantize_mode(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
+                                       uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                                       bool tiled_scales, hipStream_t stream)
 {
     if (tiled_scales)
-        return bf16 ? launch_quantize_t<true, true>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream)
-                    : launch_quantize_t<false, true>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream);
-    return bf16 ? launch_quantize_t<true, false>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream)
-                : launch_quantize_t<false, false>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream);
+        return bf16 ? launch_quantize_t<true, true, MODE>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream)
+                    : launch_quantize_t<false, true, MODE>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream);
+    return bf16 ? launch_quantize_t<true, false, MODE>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream)
+                : launch_quantize_t<false, false, MODE>(src, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, stream);
+}
+
+// mode: bit 0 = E5M2 elements, bit 1 = OCP v1 scale rule (0 = the recipe)
+hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
+                           uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales,
+                           int mode, hipStream_t stream)
+{
+    switch (mode) {
+    case 1: return launch_quantize_mode<1>(src, bf16, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, tiled_scales, stream);
+    case 2: return launch_quantize_mode<2>(src, bf16, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, tiled_scales, stream);
+    case 3: return launch_quantize_mode<3>(src, bf16, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, tiled_scales, stream);
+    default: return launch_quantize_mode<0>(src, bf16, rows, cols, ld, axis, q_row, s_row, q_colT, s_colT, tiled_scales, stream);
+    }
 }
 
 }  // namespace mxfp8

@@ -359,6 +359,65 @@ inline v2s cvt_scalef32_pk_fp8_bf16(v2s old, v2bf p, float scale, bool hi)
 {
     return cvt_scalef32_pk_fp8_f32(old, (float)p[0], (float)p[1], scale, hi);
 }
+// ---- FP8 (OCP E5M2: 1-5-2, bias 15, subnormals, exponent field 31 = Inf / NaN) ------------------------
+inline double e5m2_value(uint8_t code)
+{
+    const int e = (code >> 2) & 31, m = code & 3;
+    double mag;
+    if (e == 31)
+        mag = m ? NAN : INFINITY;
+    else
+        mag = e == 0 ? std::ldexp((double)m, -16) : std::ldexp(4.0 + m, e - 17);
+    return (code & 0x80) ? -mag : mag;
+}
+// the E5M2 form of the scaled conversion: same scaling and rounding; what rounds beyond 57344 becomes Inf
+// (the kernels replace every code above the largest finite one, so only "above 0x7B" matters here)
+inline uint8_t cvt_scaled_e5m2(float x, float scale)
+{
+    uint32_t sbits;
+    memcpy(&sbits, &scale, 4);
+    const int field = (sbits >> 23) & 0xFF;
+    const uint8_t sign = std::signbit(x) ? 0x80 : 0;
+    if (std::isnan(x) || field == 0xFF)
+        return sign | 0x7F;
+    const double v = std::ldexp(std::fabs((double)x), -(field == 0 ? -127 : field - 127));
+    if (v == 0.0)
+        return sign;
+    if (std::isinf(v))
+        return sign | 0x7C;
+    int e;
+    std::frexp(v, &e);
+    int ue = e - 1;
+    if (ue < -14)
+        ue = -14;        // subnormal grid: multiples of 2^-16
+    const double q = std::nearbyint(std::ldexp(v, 2 - ue));  // in units of 2^(ue-2); RNE
+    int mant = (int)q, ex = ue;
+    if (mant >= 8) {
+        mant >>= 1;
+        ++ex;
+    }
+    if (mant < 4)
+        return sign | (uint8_t)mant;
+    if (ex > 15)
+        return sign | 0x7C;
+    return sign | (uint8_t)(((ex + 15) << 2) | (mant - 4));
+}
+inline v2s cvt_scalef32_pk_bf8_f32(v2s old, float a, float b, float scale, bool hi)
+{
+    const uint16_t w = (uint16_t)(cvt_scaled_e5m2(a, scale) | (cvt_scaled_e5m2(b, scale) << 8));
+    old[hi ? 1 : 0] = (short)w;
+    return old;
+}
+inline v2s cvt_scalef32_pk_bf8_bf16(v2s old, v2bf p, float scale, bool hi)
+{
+    return cvt_scalef32_pk_bf8_f32(old, (float)p[0], (float)p[1], scale, hi);
+}
+inline v2f cvt_pk_f32_bf8(int q, bool hi)
+{
+    const uint32_t u = (uint32_t)q >> (hi ? 16 : 0);
+    return v2f{(float)e5m2_value(u & 0xFF), (float)e5m2_value((u >> 8) & 0xFF)};
+}
+
 inline v2f cvt_pk_f32_fp8(int q, bool hi)
 {
     const uint32_t u = (uint32_t)q >> (hi ? 16 : 0);

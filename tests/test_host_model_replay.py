@@ -39,7 +39,7 @@ def replay(lib, files, select, extra_env=None):
 
 
 def test_gpu_parity_tests_pass_on_the_host_model(hostmodel_lib):
-    n = replay(hostmodel_lib, ["test_gpu_quantize.py", "test_gpu_gemm.py"],
+    n = replay(hostmodel_lib, ["test_gpu_quantize.py", "test_gpu_quantize_modes.py", "test_gpu_gemm.py"],
                "not full_size and not transformer_layer")
     assert n >= 50
 

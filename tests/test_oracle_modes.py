@@ -89,3 +89,35 @@ def test_rounding_the_scale_down_overflows_exactly_where_the_paper_says():
             assert 0.15 < over.mean() < 0.35                     # a quarter of a binade
             sat = (q.reshape(256, 32, 32) & 0x7F) == 0x7E
             assert (sat.any(-1) >= over).all()
+
+
+def test_e5m2_row_quantization_end_to_end_against_the_library_cast():
+    """The whole E5M2 path (block loop, E5M2 scale maximum, E5M2 encoder together): under Algorithm 1 every
+    scaled element lies inside +-57344, where the conversion is the standard round-to-nearest-even cast to
+    the OCP E5M2 type; PyTorch's CPU cast of x * 2^-n serves as the independent opinion. The scale byte n is
+    checked against its closed form (smallest n with amax <= 57344 * 2^n) in exact rational arithmetic."""
+    import torch
+    from fractions import Fraction
+    rng = np.random.default_rng(21)
+    x = (rng.standard_normal((64, 256)) * np.exp(3 * rng.standard_normal((64, 1)))).astype(np.float32)
+    x[3, 40:72] = 0.0                                    # a zero block
+    x[5, 7] = 57344.0 * 2.0 ** 3                         # amax exactly max * 2^k: not bumped
+    x[6, 7] = np.nextafter(np.float32(57344.0 * 2.0 ** 3), np.float32(np.inf))   # one ulp above: bumped
+    q, s = oracle.quantize_rowwise_mode(x, "e5m2", "up")
+    blocks = x.reshape(64, 8, 32)
+    for r in range(64):
+        for b in range(8):
+            amax = float(np.abs(blocks[r, b]).max())
+            n = int(s[r, b]) - 127
+            if amax == 0.0:
+                assert n == -127
+                continue
+            assert Fraction(amax) <= Fraction(57344) * Fraction(2) ** n                     # admissible ...
+            assert n == -127 or Fraction(amax) > Fraction(57344) * Fraction(2) ** (n - 1)   # ... and the smallest
+    scaled = (blocks.astype(np.float64) * np.exp2(127.0 - s.astype(np.float64))[:, :, None]).reshape(64, 256)
+    assert np.all(np.abs(scaled) <= 57344.0)
+    t = torch.from_numpy(scaled.astype(np.float32))      # exact: a power-of-two scaling inside the FP32 normal range
+    assert np.array_equal(t.numpy().astype(np.float64), scaled)
+    want = t.to(torch.float8_e5m2).view(torch.uint8).numpy()
+    assert np.array_equal(q, want)
+    assert int(s[5, 0]) + 1 == int(s[6, 0])
