@@ -31,8 +31,10 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_gemm", "mxfp8_gemm_ex",
-                                    "mxfp8_gemm_quantize_ex", "mxfp8_quantize", "mxfp8_quantize_ex", "mxfp8_scale_bytes", "mxfp8_status_string"]
+    assert declared_functions() == ["mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex", "mxfp8_gemm",
+                                    "mxfp8_gemm_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
+                                    "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_scale_bytes",
+                                    "mxfp8_status_string"]
 
 
 def test_library_exports_every_declared_function(lib):
@@ -49,6 +51,7 @@ def test_binding_mirrors_the_header():
     assert (mx.ROWWISE, mx.COLWISE, mx.BOTH) == (1, 2, 3)
     assert (mx.FPROP, mx.DGRAD, mx.WGRAD) == (0, 1, 2)
     assert (mx.SCALES_ROWMAJOR, mx.SCALES_TILED) == (0, 1)
+    assert (mx.E4M3, mx.E5M2) == (0, 1) and (mx.SCALE_ROUND_UP, mx.SCALE_OCP_V1) == (0, 1)
 
 
 def test_scale_bytes_is_host_arithmetic(lib):
@@ -68,25 +71,45 @@ def test_ex_entry_points_validate_the_layout(lib):
     assert q(FAKE, 0, 32, 32, 32, 1, FAKE, P(0x1004), None, None, 1, None) == 3     # tiled scales: 16-byte aligned
     assert q(FAKE, 0, 33, 32, 32, 3, FAKE, FAKE, FAKE, FAKE, 1, None) == 2
     g = lib.mxfp8_gemm_ex
-    g.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, P]
-    assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, 9, None) == 5
-    assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 96, FAKE, 0, 64, 1, None) == 2
+    g.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, ctypes.c_int32, P]
+    assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, 9, 0, None) == 5
+    assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, 1, -3, None) == 5   # negative workgroup bound
+    assert g(0, FAKE, FAKE, FAKE, FAKE, 64, 64, 96, FAKE, 0, 64, 1, 0, None) == 2
     f = lib.mxfp8_gemm_quantize_ex
-    f.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, I64, ctypes.c_int, P, P, P, P, ctypes.c_int, P]
+    f.argtypes = [ctypes.c_int, P, P, P, P, I64, I64, I64, P, I64, ctypes.c_int, P, P, P, P, ctypes.c_int,
+                  ctypes.c_int32, P]
     ok = (FAKE, FAKE, FAKE, FAKE)
     outs = (FAKE, FAKE, FAKE, FAKE)
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, 3, *outs, 3, None) == 5           # layout
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, 0, *outs, 0, None) == 5           # axis
-    assert f(0, *ok, 200, 256, 256, FAKE, 256, 3, *outs, 0, None) == 2           # M not a multiple of the tile
-    assert f(0, *ok, 256, 256, 128, FAKE, 256, 3, *outs, 0, None) == 2           # fewer than two K steps
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, 1, None, FAKE, None, None, 0, None) == 1
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, 2, None, None, FAKE, None, 0, None) == 1
-    assert f(0, *ok, 256, 256, 256, FAKE, 260, 3, *outs, 0, None) == 3           # ldc * 2 not a multiple of 16
-    assert f(0, *ok, 256, 256, 256, FAKE, 256, 1, FAKE, P(0x1004), None, None, 1, None) == 3
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 3, *outs, 3, 0, None) == 5           # layout
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 0, *outs, 0, 0, None) == 5           # axis
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 3, *outs, 0, -1, None) == 5          # negative workgroup bound
+    assert f(0, *ok, 200, 256, 256, FAKE, 256, 3, *outs, 0, 0, None) == 2           # M not a multiple of the tile
+    assert f(0, *ok, 256, 256, 128, FAKE, 256, 3, *outs, 0, 0, None) == 2           # fewer than two K steps
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 1, None, FAKE, None, None, 0, 0, None) == 1
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 2, None, None, FAKE, None, 0, 0, None) == 1
+    assert f(0, *ok, 256, 256, 256, FAKE, 260, 3, *outs, 0, 0, None) == 3           # ldc * 2 not a multiple of 16
+    assert f(0, *ok, 256, 256, 256, FAKE, 256, 1, FAKE, P(0x1004), None, None, 1, 0, None) == 3
     d = lib.mxfp8_dequantize_ex
     d.argtypes = [P, P, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, P]
     assert d(FAKE, FAKE, 4, 64, FAKE, 0, 64, -1, None) == 5
     assert d(FAKE, FAKE, 4, 48, FAKE, 0, 48, 1, None) == 2
+
+
+def test_mode_entry_points_and_rate_probe_validate(lib):
+    q = lib.mxfp8_quantize_mode_ex
+    q.argtypes = [P, ctypes.c_int, I64, I64, I64, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, P, P, ctypes.c_int, P]
+    assert q(FAKE, 0, 32, 32, 32, 3, 2, 0, FAKE, FAKE, FAKE, FAKE, 0, None) == 5   # element format
+    assert q(FAKE, 0, 32, 32, 32, 3, 1, 2, FAKE, FAKE, FAKE, FAKE, 0, None) == 5   # scale rule
+    assert q(FAKE, 0, 32, 40, 40, 3, 1, 1, FAKE, FAKE, FAKE, FAKE, 0, None) == 2
+    assert q(None, 0, 32, 32, 32, 1, 1, 1, FAKE, FAKE, None, None, 0, None) == 1
+    d = lib.mxfp8_dequantize_mode_ex
+    d.argtypes = [P, P, I64, I64, ctypes.c_int, P, ctypes.c_int, I64, ctypes.c_int, P]
+    assert d(FAKE, FAKE, 4, 64, 7, FAKE, 0, 64, 0, None) == 5
+    assert d(FAKE, FAKE, 4, 48, 1, FAKE, 0, 48, 0, None) == 2
+    r = lib.mxfp8_mfma_rate_probe
+    r.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P]
+    assert r(-1, 10, FAKE, None) == 2 and r(10, -1, FAKE, None) == 2 and r((1 << 20) + 1, 1, FAKE, None) == 2
+    assert r(4, 10, None, None) == 1 and r(4, 10, P(0x1002), None) == 3 and r(0, 10, None, None) == 0
 
 
 def test_status_strings(lib):
