@@ -19,6 +19,9 @@ step time, quantize and dequantize passes included. `roofline` describes the for
 stream inside the timed region. `roofline_quantize` (X, BF16, both axes) and `roofline_quantize_f32`
 (dY, FP32, both axes) are timed after the step loop over >= 100 launches that rotate over more than
 512 MB of distinct sources and destinations, so that the 256 MB memory-side cache cannot serve them.
+Two measured ceilings of the box stand beside the published peaks: `peak_sustained` in the GEMM rooflines is
+the rate a register-only loop of the matrix instruction sustains in this very run (mxfp8_mfma_rate_probe),
+`plain_copy_gbs` in the quantize rooflines is a plain device copy of the same tensor under the same rotation.
 `layer_set_16384` times the three products of each linear layer of an 8B-class transformer block at
 16384 tokens. `cpu_baseline` times the CPU oracle on a bounded sample.
 """
@@ -40,7 +43,6 @@ if ROOT not in sys.path:
 T, H, O = 8192, 4096, 14336
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP8_PEAK_TFLOPS = 5000.0  # dense FP8 / MX-FP8 matrix peak
-MFMA_SUSTAINED_TFLOPS = 4970.0  # what a register-only loop of the scaled MFMA instruction reached on an MI355X
 
 
 def _ensure_built():
@@ -235,12 +237,45 @@ def main():
         out["frac_of_peak"] = out["layer_tflops"] / MFMA_FP8_PEAK_TFLOPS
         return out
 
+    def sustained_mfma_tflops():
+        """What the matrix pipes of this GPU sustain on the scaled FP8 instruction alone (operands in registers,
+        pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling a GEMM
+        could reach on this machine if moving data were free. About 0.3 s of launches, the last two thirds timed."""
+        sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+        for _ in range(40):
+            mx.mxfp8_mfma_rate_probe(512, 1000, sink)
+        a, b = ev(), ev()
+        a.record()
+        flop = 0.0
+        for _ in range(80):
+            flop += mx.mxfp8_mfma_rate_probe(512, 1000, sink)
+        b.record()
+        torch.cuda.synchronize()
+        return flop / (a.elapsed_time(b) * 1e-3) / 1e12
+
+    def rotating_copy_gbs(src, sets, launches):
+        """A plain device-to-device copy of the same source with the same rotation: what the memory system of
+        this box gives the simplest possible stream (read + write bytes per second)."""
+        srcs = [src] + [src.clone() for _ in range(sets - 1)]
+        dsts = [torch.empty_like(t) for t in srcs]
+        for i in range(sets):
+            dsts[i].copy_(srcs[i])
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(launches):
+            dsts[i % sets].copy_(srcs[i % sets])
+        b.record()
+        torch.cuda.synchronize()
+        return 2.0 * src.numel() * src.element_size() / (a.elapsed_time(b) / launches * 1e-3) / 1e9
+
     extras = {}
+    mfma_sustained = sustained_mfma_tflops()
     if not args.no_extras:
         q_ms, q_fp = rotating_quantize(X, 8, 160)
         f_ms, f_fp = rotating_quantize(dY, 2, 100)
-        extras["quant_bf16"] = (q_ms, q_fp, 160)
-        extras["quant_f32"] = (f_ms, f_fp, 100)
+        extras["quant_bf16"] = (q_ms, q_fp, 160, rotating_copy_gbs(X, 8, 160))
+        extras["quant_f32"] = (f_ms, f_fp, 100, rotating_copy_gbs(dY, 2, 100))
         try:
             extras["layer_set"] = layer_set()
         except Exception as exc:   # the headline measurement must survive a problem in the extra one
@@ -264,8 +299,8 @@ def main():
         ms = float(np.mean([a.elapsed_time(b) for a, b in marks[name]]))
         tf = gemm_flop / (ms * 1e-3) / 1e12
         return {"bound": "mfma", "achieved": tf, "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": tf / MFMA_FP8_PEAK_TFLOPS, "peak_sustained": MFMA_SUSTAINED_TFLOPS,
-                "frac_sustained": tf / MFMA_SUSTAINED_TFLOPS, "traffic": traffic_from_profile(name + " "),
+                "frac": tf / MFMA_FP8_PEAK_TFLOPS, "peak_sustained": mfma_sustained,
+                "frac_sustained": tf / mfma_sustained, "traffic": traffic_from_profile(name + " "),
                 "algorithmic_bytes": gemm_bytes[name], "kernel": f"gemm_persistent_kernel ({name} {shapes[name]})",
                 "avg_ms": ms, "launches": len(marks[name])}
 
@@ -288,12 +323,13 @@ def main():
     for key, name, elems, bpe, prof in (("roofline_quantize", "quant_bf16", T * H, 4.0625, "quantize X BF16"),
                                         ("roofline_quantize_f32", "quant_f32", T * O, 6.0625, "quantize dY FP32")):
         if name in extras:
-            ms, footprint, launches = extras[name]
+            ms, footprint, launches, copy_gbs = extras[name]
             gbs = elems * bpe / (ms * 1e-3) / 1e9
             out[key] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                         "traffic": traffic_from_profile(prof), "algorithmic_bytes": elems * bpe,
                         "kernel": f"quantize_kernel ({'BF16 X 8192x4096' if name == 'quant_bf16' else 'FP32 dY 8192x14336'}, both axes)",
-                        "avg_ms": ms, "launches": launches, "rotating_footprint_mb": footprint / 1e6}
+                        "avg_ms": ms, "launches": launches, "rotating_footprint_mb": footprint / 1e6,
+                        "plain_copy_gbs": copy_gbs, "frac_of_plain_copy": gbs / copy_gbs}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
     if "layer_set" in extras:
