@@ -26,6 +26,7 @@
 namespace mxfp8 {
 
 constexpr int BK = 128;  // K bytes per step = 4 scale blocks = one MFMA
+constexpr int kStageBytes = 4608;  // per-wavefront LDS area of the persistent kernel's epilogue (16 rows x (256 + 32) bytes)
 
 template <int BM_, int BN_, int WAVES_M_, int WAVES_N_> struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
@@ -37,6 +38,7 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_> struct GemmCfg {
     // LDS map: A[2] | B[2] | A scales[2] (one dword = 4 scale bytes per row) | B scales[2]
     static constexpr int A_OFF = 0, B_OFF = 2 * A_BYTES, SA_OFF = B_OFF + 2 * B_BYTES, SB_OFF = SA_OFF + 2 * BM * 4;
     static constexpr int LDS_BYTES = SB_OFF + 2 * BN * 4;
+    static constexpr int LDS_BYTES_PERSISTENT = LDS_BYTES + WAVES * kStageBytes;  // + the epilogue's staging areas
     // one direct-to-LDS instruction moves 8 rows x 128 bytes (or 64 scale dwords) per wavefront
     static constexpr int A_LOADS = BM / 8 / WAVES, B_LOADS = BN / 8 / WAVES;
     static constexpr int SA_LOADS = (BM / 64 + WAVES - 1) / WAVES, SB_LOADS = (BN / 64 + WAVES - 1) / WAVES;
@@ -633,17 +635,42 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                         *reinterpret_cast<uint16_t *>(sp) = (uint16_t)scales;
                 }
             } else {
+                // Row group i of this wavefront (16 rows x WN columns) goes through a wavefront-private LDS area
+                // so that it leaves as whole rows: a lane holds 4 consecutive columns of one row per MFMA tile,
+                // and storing those directly costs one partial cache line per row and instruction (the address
+                // unit of the compute unit then needs ~7 us per 256 x 256 tile, during which the matrix pipes
+                // wait behind their own stores). Staged, every store instruction writes 1 KB of contiguous rows.
+                constexpr int ROWB = Cfg::WN * ESZ;                            // bytes of one row of the wavefront's part
+                constexpr int PITCH = ROWB + 32;                               // staged row pitch: spreads the rows over the banks
+                constexpr int RPP = ROWB * 16 <= 4096 ? 16 : 4096 / ROWB;      // rows per pass (at most 4 KB staged)
+                static_assert(RPP * PITCH <= kStageBytes && (RPP * ROWB) % 1024 == 0, "staging area");
+                uint8_t *stage = lds + Cfg::LDS_BYTES + wave * kStageBytes;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const v4f v = acc[i][j];
-                if constexpr (OUT_BF16) {
-                    v2bf p0 = {(__bf16)v[0], (__bf16)v[1]}, p1 = {(__bf16)v[2], (__bf16)v[3]};
-                    *reinterpret_cast<uint2 *>(crow + lane_off + j * 16 * ESZ) =
-                        make_uint2(__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1));
-                } else {
-                    *reinterpret_cast<float4 *>(crow + lane_off + j * 16 * ESZ) = make_float4(v[0], v[1], v[2], v[3]);
+                for (int pass = 0; pass < 16 / RPP; ++pass) {
+                    if (RPP == 16 || r16 / RPP == pass) {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const v4f v = acc[i][j];
+                            uint8_t *dst = stage + (r16 % RPP) * PITCH + (j * 16 + 4 * g) * ESZ;
+                            if constexpr (OUT_BF16) {
+                                v2bf p0 = {(__bf16)v[0], (__bf16)v[1]}, p1 = {(__bf16)v[2], (__bf16)v[3]};
+                                *reinterpret_cast<uint2 *>(dst) =
+                                    make_uint2(__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1));
+                            } else {
+                                *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();  // the reads below see the other lanes' writes (LDS serves a wavefront in order)
+#pragma unroll
+                    for (int t = 0; t < RPP * ROWB / 1024; ++t) {
+                        const int lin = t * 1024 + lane * 16, row = lin / ROWB, colb = lin % ROWB;
+                        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * PITCH + colb);
+                        *reinterpret_cast<uint4 *>(crow + (int64_t)(wm * Cfg::WM + pass * RPP + row) * ldc_bytes +
+                                                   wn * ROWB + colb) = v;
+                    }
+                    __builtin_amdgcn_wave_barrier();  // (the next pass overwrites the area after these reads)
                 }
-            }
             }
             MXFP8_PIN();
         }
@@ -781,10 +808,10 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
             return e;
         auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED, spread_fits<Cfg>()>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Cfg::LDS_BYTES);
+                                Cfg::LDS_BYTES_PERSISTENT);
         if (e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, a_q, a_s, b_q, b_s, M, N, K,
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES_PERSISTENT, stream, a_q, a_s, b_q, b_s, M, N, K,
                            static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, static_cast<uint8_t *>(nullptr),
                            static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr),
                            static_cast<uint8_t *>(nullptr));
@@ -845,10 +872,10 @@ static hipError_t launch_fused_cfg(const uint8_t *a_q, const uint8_t *a_s, const
     hipError_t e = persistent_grid(tiles_m * tiles_n, max_workgroups, grid);
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Cfg::LDS_BYTES);
+                                Cfg::LDS_BYTES_PERSISTENT);
     if (e != hipSuccess)
         return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, a_q, a_s, b_q, b_s, M, N, K,
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES_PERSISTENT, stream, a_q, a_s, b_q, b_s, M, N, K,
                        static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, cq, cs, cqT, csT);
     return hipGetLastError();
 }

@@ -54,6 +54,7 @@ inline uint32_t __float_as_uint(float f)
 #define __builtin_amdgcn_s_waitcnt(imm) ::wavesim::s_waitcnt(imm)
 #define __builtin_amdgcn_sched_barrier(mask) ((void)0)
 #define __builtin_amdgcn_s_barrier() ::wavesim::block_sync()
+#define __builtin_amdgcn_wave_barrier() ::wavesim::wave_sync()
 #define __builtin_amdgcn_update_dpp(old, src, ctrl, row_mask, bank_mask, bound_ctrl) \
     ::wavesim::update_dpp((old), (src), (ctrl), (row_mask), (bank_mask), (bound_ctrl))
 #define __builtin_amdgcn_perm(s0, s1, sel) ::wavesim::perm((s0), (s1), (sel))
