@@ -21,8 +21,9 @@
  *     NULL = the default stream) and the call returns immediately.
  *   - All tensors are row-major. "ld" arguments are leading dimensions in ELEMENTS.
  *   - A block is 32 consecutive elements along the quantization axis, so that axis must be a
- *     multiple of 32 (the paper defines no partial block); a dimension of 0 is accepted and
- *     does nothing.
+ *     multiple of 32 (the paper defines no partial block); the quantizer works on tiles made of
+ *     whole blocks in both directions and asks for both dimensions to be multiples of 32,
+ *     whichever axis is selected. A dimension of 0 is accepted and does nothing.
  *   - Scale bytes hold n + 127 for X = 2^n, n in [-127, 127]; 0xFF marks a NaN block.
  *     Element bytes are OCP E4M3 (bias 7, max 448, 0x7F/0xFF = NaN, no infinity).
  *   - Errors are reported by return code only, detected on the host before any launch; when a
