@@ -72,6 +72,8 @@ def _load():
     lib.mxo_quantize_rowwise_mode_f32.argtypes = [vp, i64, i64, i64, u8p, u8p, ctypes.c_int, ctypes.c_int]
     lib.mxo_dequantize_mode_f64.restype = None
     lib.mxo_dequantize_mode_f64.argtypes = [u8p, u8p, i64, i64, vp, ctypes.c_int]
+    lib.mxo_matmul_nt_bf16_rows.restype = None
+    lib.mxo_matmul_nt_bf16_rows.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, vp]
     lib.mxo_gemm_rows_f64.restype = ctypes.c_int
     lib.mxo_gemm_rows_f64.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, i64, vp, vp]
     _lib = lib
@@ -191,6 +193,44 @@ def gemm_rows(a_q, a_s, b_q, b_s, rows):
 def gemm(a_q, a_s, b_q, b_s):
     """All of C = A * B^T (see gemm_rows)."""
     return gemm_rows(a_q, a_s, b_q, b_s, np.arange(np.asarray(a_q).shape[0]))
+
+
+# ---- simulated MX path (Section 3.1): BF16 -> MXFP8 -> BF16 round trip, then a BF16 product -----------
+def roundtrip_bf16(src: np.ndarray, axis: str = "row") -> np.ndarray:
+    """BF16 source (uint16 bit patterns, [rows x cols]) converted to MXFP8 along `axis` and straight back
+    to BF16 (round to nearest even of Q_i * X): what the paper's simulated runs feed to the GEMM.
+    'row': blocks along a row, result [rows x cols]; 'col': blocks down a column, result stored
+    transposed [cols x rows] like the column copy itself."""
+    src = np.ascontiguousarray(src)
+    if src.dtype != np.uint16:
+        raise TypeError("BF16 bit patterns (uint16) expected")
+    q, s = quantize_rowwise(src) if axis == "row" else quantize_colwise(src)
+    return dequantize(q, s, "bf16")
+
+
+def matmul_nt_bf16_rows(a: np.ndarray, b: np.ndarray, rows):
+    """Rows ``rows`` of C = A * B^T for BF16 operands given as uint16 bit patterns ([M x K], [N x K]),
+    in double: returns (C, sum|a*b|)."""
+    a, b = np.ascontiguousarray(a), np.ascontiguousarray(b)
+    if a.dtype != np.uint16 or b.dtype != np.uint16 or a.ndim != 2 or b.ndim != 2:
+        raise TypeError("two 2-D arrays of BF16 bit patterns (uint16) expected")
+    M, K = a.shape
+    N, Kb = b.shape
+    if K != Kb:
+        raise ValueError("operands disagree on K")
+    idx = np.ascontiguousarray(rows, np.int64)
+    if idx.size and (idx.min() < 0 or idx.max() >= M):
+        raise ValueError("row index out of range")
+    C = np.empty((idx.size, N), np.float64)
+    A = np.empty((idx.size, N), np.float64)
+    _load().mxo_matmul_nt_bf16_rows(a.ctypes.data, b.ctypes.data, M, N, K, idx.ctypes.data, idx.size,
+                                    C.ctypes.data, A.ctypes.data)
+    return C, A
+
+
+def matmul_nt_bf16(a: np.ndarray, b: np.ndarray):
+    """All of C = A * B^T (see matmul_nt_bf16_rows)."""
+    return matmul_nt_bf16_rows(a, b, np.arange(np.asarray(a).shape[0]))
 
 
 # ---- ablation arms of the paper (E5M2 elements, OCP v1 scale rule): not part of the recipe ----------

@@ -441,3 +441,36 @@ int mxo_gemm_rows_f64(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q
     free(b);
     return 0;
 }
+
+/* ---- Simulated MX path (Section 3.1). ------------------------------------------------------- */
+
+/* The paper's own training runs emulate MX arithmetic: every BF16 GEMM input is converted to MXFP8
+ * and straight back to BF16, and an ordinary BF16 GEMM with FP32 accumulation follows. The round
+ * trip is mxo_quantize_{row,col}wise_bf16 followed by mxo_dequantize_bf16 (composed by the caller);
+ * this is the product that follows it: C[m, n] = sum_k a[m, k] * b[n, k] over BF16 operands given as
+ * bit patterns (both K-contiguous), summed in plain k order in double, absC = sum_k |a * b|.
+ * Every product of two BF16 values is exact in double. Only the rows listed in row_idx are computed:
+ * C and absC are [n_rows x N]. */
+void mxo_matmul_nt_bf16_rows(const uint16_t *a, const uint16_t *b, int64_t M, int64_t N, int64_t K,
+                             const int64_t *row_idx, int64_t n_rows, double *C, double *absC)
+{
+    int64_t idx;
+    (void)M;
+    for (idx = 0; idx < n_rows; ++idx) {
+        const uint16_t *arow = a + row_idx[idx] * K;
+        int64_t n;
+#pragma omp parallel for schedule(static)
+        for (n = 0; n < N; ++n) {
+            double acc = 0.0, aacc = 0.0;
+            int64_t k;
+            for (k = 0; k < K; ++k) {
+                double p = bf16_to_double(arow[k]) * bf16_to_double(b[n * K + k]);
+                acc += p;
+                aacc += fabs(p);
+            }
+            C[idx * N + n] = acc;
+            absC[idx * N + n] = aacc;
+        }
+    }
+}
+
