@@ -22,6 +22,9 @@ stream inside the timed region. `roofline_quantize` (X, BF16, both axes) and `ro
 Two measured ceilings of the box stand beside the published peaks: `peak_sustained` in the GEMM rooflines is
 the rate a register-only loop of the matrix instruction sustains in this very run (mxfp8_mfma_rate_probe),
 `plain_copy_gbs` in the quantize rooflines is a plain device copy of the same tensor under the same rotation.
+`fused_output_quantization` times the forward product with the MXFP8 copies of Y emitted from its epilogue
+against the product followed by a stand-alone quantize of Y; `simulated_path` times the BF16 product of the
+round-tripped operands (Section 3.1) against the BF16 matrix peak.
 `layer_set_16384` times the three products of each linear layer of an 8B-class transformer block at
 16384 tokens. `cpu_baseline` times the CPU oracle on a bounded sample.
 """
@@ -43,6 +46,7 @@ if ROOT not in sys.path:
 T, H, O = 8192, 4096, 14336
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP8_PEAK_TFLOPS = 5000.0  # dense FP8 / MX-FP8 matrix peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense BF16 matrix peak
 
 
 def _ensure_built():
@@ -237,6 +241,47 @@ def main():
         out["frac_of_peak"] = out["layer_tflops"] / MFMA_FP8_PEAK_TFLOPS
         return out
 
+    def ms_avg(fn, reps=20, warm=3):
+        for _ in range(warm):
+            fn()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def fused_output_quantization():
+        """fprop that also emits the MXFP8 copies of Y from its epilogue, against fprop followed by a
+        stand-alone quantize of Y (same outputs, one more pass over Y)."""
+        Yq = qbufs(T, O)
+        args_ = (Xq["q_row"], Xq["s_row"], Wq["q_row"], Wq["s_row"], Y)
+        res = {}
+        for axis, name in ((mx.ROWWISE, "rowwise"), (mx.BOTH, "both")):
+            sel = {k: v for k, v in Yq.items() if axis == mx.BOTH or k.endswith("row")}
+            fused = ms_avg(lambda: mx.mxfp8_gemm_quantize_ex(mx.FPROP, *args_, axis, **{"c" + k: v for k, v in sel.items()},
+                                                             scale_layout=lay))
+            separate = ms_avg(lambda: (mx.mxfp8_gemm_ex(mx.FPROP, *args_, lay),
+                                       mx.mxfp8_quantize_ex(Y, axis, **sel, scale_layout=lay)))
+            res[name] = {"fused_ms": fused, "gemm_then_quantize_ms": separate}
+        return res
+
+    def simulated_path():
+        """Section 3.1's simulated MX path for the forward product: the BF16 GEMM of the round-tripped operands
+        (bound: BF16 matrix peak), and the round trip itself (quantize + dequantize of X)."""
+        a16, b16 = torch.empty_like(X), torch.empty_like(W)
+        mx.mxfp8_dequantize_ex(Xq["q_row"], Xq["s_row"], a16, lay)
+        mx.mxfp8_dequantize_ex(Wq["q_row"], Wq["s_row"], b16, lay)
+        ms = ms_avg(lambda: mx.mxfp8_gemm_bf16(a16, b16, Y))
+        rt = ms_avg(lambda: (mx.mxfp8_quantize_ex(X, mx.ROWWISE, q_row=Xq["q_row"], s_row=Xq["s_row"], scale_layout=lay),
+                             mx.mxfp8_dequantize_ex(Xq["q_row"], Xq["s_row"], a16, lay)))
+        tf = gemm_flop / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "kernel": f"gemm_persistent_kernel, BF16 operands (fprop {T}x{O}x{H}, BF16 out)",
+                "avg_ms": ms, "launches": 20, "round_trip_X_ms": rt,
+                "round_trip_X_gbs": T * H * (2 + 1.03125 + 1.03125 + 2) / (rt * 1e-3) / 1e9}
+
     def sustained_mfma_tflops():
         """What the matrix pipes of this GPU sustain on the scaled FP8 instruction alone (operands in registers,
         pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling a GEMM
@@ -269,6 +314,7 @@ def main():
         torch.cuda.synchronize()
         return 2.0 * src.numel() * src.element_size() / (a.elapsed_time(b) / launches * 1e-3) / 1e9
 
+    gemm_flop = 2.0 * T * H * O
     extras = {}
     mfma_sustained = sustained_mfma_tflops()
     if not args.no_extras:
@@ -276,10 +322,12 @@ def main():
         f_ms, f_fp = rotating_quantize(dY, 2, 100)
         extras["quant_bf16"] = (q_ms, q_fp, 160, rotating_copy_gbs(X, 8, 160))
         extras["quant_f32"] = (f_ms, f_fp, 100, rotating_copy_gbs(dY, 2, 100))
-        try:
-            extras["layer_set"] = layer_set()
-        except Exception as exc:   # the headline measurement must survive a problem in the extra one
-            extras["layer_set"] = {"error": repr(exc)}
+        for key, fn in (("fused_output_quantization", fused_output_quantization), ("simulated_path", simulated_path),
+                        ("layer_set", layer_set)):
+            try:
+                extras[key] = fn()
+            except Exception as exc:   # the headline measurement must survive a problem in an extra one
+                extras[key] = {"error": repr(exc)}
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -289,7 +337,6 @@ def main():
         del src, dst
 
     ms_per_step = dt / args.steps * 1e3
-    gemm_flop = 2.0 * T * H * O
     step_flops = 3 * gemm_flop
     gemm_bytes = {"fprop": (T + O) * H * (1 + 1 / 32) + T * O * 2, "dgrad": (T + H) * O * (1 + 1 / 32) + T * H * 2,
                   "wgrad": (O + H) * T * (1 + 1 / 32) + O * H * 4}
@@ -332,6 +379,9 @@ def main():
                         "plain_copy_gbs": copy_gbs, "frac_of_plain_copy": gbs / copy_gbs}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
+    for key in ("fused_output_quantization", "simulated_path"):
+        if key in extras:
+            out[key] = extras[key]
     if "layer_set" in extras:
         out["layer_set_16384"] = extras["layer_set"]
     if not args.no_cpu_baseline:

@@ -169,6 +169,22 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
                            int32_t max_workgroups, void *hip_stream);
 
 /*
+ * The GEMM of the simulated MX path (Section 3.1: the paper's own training runs convert every BF16 GEMM
+ * input to MXFP8 and straight back to BF16 and then run an ordinary BF16 GEMM):
+ *   C[m, n] = sum_k A[m, k] * B[n, k],  A [M x K] and B [N x K] dense BF16, both K-contiguous,
+ * accumulated in FP32 by the BF16 matrix instructions (every product of two BF16 values is exact in FP32).
+ * The round trip itself is mxfp8_quantize followed by mxfp8_dequantize to BF16 of the copy that the pass
+ * uses (the operand table of mxfp8_gemm), so that "quantize -> dequantize -> mxfp8_gemm_bf16" and
+ * "quantize -> mxfp8_gemm" compute the same sums and differ only in how the hardware adds them.
+ * c is FP32 or BF16 (RNE), leading dimension ldc >= N. Requirements: K % 64 == 0 and K <= 2^23; a_bf16 and
+ * b_bf16 16-byte aligned; c, ldc, max_workgroups, zero sizes and the NaN / overflow behaviour as in
+ * mxfp8_gemm_ex.
+ */
+mxfp8_status mxfp8_gemm_bf16(const void *a_bf16, const void *b_bf16, int64_t M, int64_t N, int64_t K,
+                             void *c, mxfp8_dtype c_dtype, int64_t ldc, int32_t max_workgroups,
+                             void *hip_stream);
+
+/*
  * mxfp8_gemm_ex with BF16 output AND, from the same pass, MXFP8 copies of that output, i.e. the next
  * layer's operands (Section 2: the FP32 result is re-quantized when it is needed in MX format;
  * Section 3.2 for the two axes; Section 3.3, Appendix A.1/A.2 for the conversion). c_bf16 [M x N] is the

@@ -67,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_quantize_mode_ex.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, ci, vp]
     lib.mxfp8_dequantize_mode_ex.restype = ci
     lib.mxfp8_dequantize_mode_ex.argtypes = [vp, vp, i64, i64, ci, vp, ci, i64, ci, vp]
+    lib.mxfp8_gemm_bf16.restype = ci
+    lib.mxfp8_gemm_bf16.argtypes = [vp, vp, i64, i64, i64, vp, ci, i64, ctypes.c_int32, vp]
     lib.mxfp8_mfma_rate_probe.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_status_string.restype = ctypes.c_char_p
@@ -184,6 +186,23 @@ def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, ma
         raise MXFP8Error(rc, "mxfp8_gemm")
 
 
+def mxfp8_gemm_bf16(a, b, c, max_workgroups=0, stream=None) -> None:
+    """c [M x N] (float32 or bfloat16) = a [M x K] * b[N x K]^T for dense bfloat16 operands: the GEMM of the
+    simulated MX path."""
+    _need_cuda(a, b, c)
+    M, K = a.shape
+    N, Kb = b.shape
+    if K != Kb or a.dtype != torch.bfloat16 or b.dtype != torch.bfloat16 or not a.is_contiguous() or not b.is_contiguous():
+        raise ValueError("operands must be dense bfloat16 and agree in K")
+    if tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
+        raise ValueError("c must be [M x N] with contiguous rows")
+    ldc = c.stride(0) if M > 1 else max(N, 1)
+    rc = load().mxfp8_gemm_bf16(_ptr(a), _ptr(b), M, N, K, _ptr(c), _dtype_code(c.dtype), ldc, max_workgroups,
+                                _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_gemm_bf16")
+
+
 def mxfp8_gemm_quantize_ex(pass_, a_q, a_s, b_q, b_s, c, axis, cq_row=None, cs_row=None, cq_colT=None, cs_colT=None,
                            scale_layout=SCALES_ROWMAJOR, max_workgroups=0, stream=None) -> None:
     """mxfp8_gemm_ex with bfloat16 c [M x N] plus the MXFP8 copies of c selected by `axis`:
@@ -278,6 +297,12 @@ def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR, element=E4M3, rule=
 def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
     c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
     mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout, max_workgroups)
+    return c
+
+
+def gemm_bf16(a, b, out_dtype=torch.float32, max_workgroups=0):
+    c = torch.empty((a.shape[0], b.shape[0]), dtype=out_dtype, device=a.device)
+    mxfp8_gemm_bf16(a, b, c, max_workgroups)
     return c
 
 

@@ -17,6 +17,8 @@ hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8
                              int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
                              uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, int max_workgroups,
                              hipStream_t stream);
+hipError_t launch_gemm_bf16(const uint8_t *a, const uint8_t *b, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
+                            int64_t ldc, int max_workgroups, hipStream_t stream);
 hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream);
 }  // namespace mxfp8
 
@@ -121,6 +123,29 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
     const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16,
                                             scale_layout == MXFP8_SCALES_TILED, ldc, max_workgroups,
                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_gemm_bf16(const void *a_bf16, const void *b_bf16, int64_t M, int64_t N, int64_t K, void *c,
+                             mxfp8_dtype c_dtype, int64_t ldc, int32_t max_workgroups, void *hip_stream)
+{
+    if (!valid_dtype(c_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (max_workgroups < 0)
+        return MXFP8_ERR_MODE;
+    // rows are walked in 128-byte steps of 64 values; 2 * K bytes per row must fit the kernels' 32-bit offsets
+    if (M < 0 || N < 0 || K < 0 || M > kMaxGemmMN || N > kMaxGemmMN || K > kMaxGemmK / 2 || K % 64 || ldc < N ||
+        ((M + 127) / 128) * ((N + 127) / 128) > kMaxDim)
+        return MXFP8_ERR_SHAPE;
+    if (M == 0 || N == 0)
+        return MXFP8_OK;
+    if (!c || (K > 0 && (!a_bf16 || !b_bf16)))
+        return MXFP8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(c) % esize(c_dtype) || (K > 0 && (!aligned16(a_bf16) || !aligned16(b_bf16))))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_gemm_bf16(static_cast<const uint8_t *>(a_bf16), static_cast<const uint8_t *>(b_bf16),
+                                                 M, N, K, c, c_dtype == MXFP8_BF16, ldc, max_workgroups,
+                                                 static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

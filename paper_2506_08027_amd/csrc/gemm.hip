@@ -28,8 +28,12 @@ namespace mxfp8 {
 constexpr int BK = 128;  // K bytes per step = 4 scale blocks = one MFMA
 constexpr int kStageBytes = 4608;  // per-wavefront LDS area of the persistent kernel's epilogue (16 rows x (256 + 32) bytes)
 
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_> struct GemmCfg {
+// SCALED: MXFP8 operands with their scale bytes (the method itself); otherwise plain BF16 operands, 64 per
+// 128-byte K step, no scales (the product of the simulated path of Section 3.1). Everything about tiles,
+// buffers, requests and the schedule is counted in BYTES of a K-contiguous operand row and is the same.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool SCALED_ = true> struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr bool SCALED = SCALED_;
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile
@@ -41,7 +45,7 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_> struct GemmCfg {
     static constexpr int LDS_BYTES_PERSISTENT = LDS_BYTES + WAVES * kStageBytes;  // + the epilogue's staging areas
     // one direct-to-LDS instruction moves 8 rows x 128 bytes (or 64 scale dwords) per wavefront
     static constexpr int A_LOADS = BM / 8 / WAVES, B_LOADS = BN / 8 / WAVES;
-    static constexpr int SA_LOADS = (BM / 64 + WAVES - 1) / WAVES, SB_LOADS = (BN / 64 + WAVES - 1) / WAVES;
+    static constexpr int SA_LOADS = SCALED ? (BM / 64 + WAVES - 1) / WAVES : 0, SB_LOADS = SCALED ? (BN / 64 + WAVES - 1) / WAVES : 0;
     static constexpr int NA = A_LOADS + SA_LOADS, NB = B_LOADS + SB_LOADS;  // DMA slots per step
     static_assert(BM % (8 * WAVES) == 0 && BN % (8 * WAVES) == 0, "tile rows per wavefront");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "scale rows per instruction");
@@ -74,6 +78,23 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
 // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt is split over bits 3:0 and 15:14)
 #define MXFP8_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
+// One K step of one 16x16 output tile. MXFP8: one scaled matrix instruction over 128 k (4 blocks per
+// operand row, scale byte 0 of each lane's scale register). BF16: the lane's two 16-byte pieces are k
+// 8g..8g+7 and 32+8g..32+8g+7 of the row's 64 values: two 16x16x32 instructions.
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+template <bool SCALED>
+__device__ __forceinline__ v4f mma_step(const v8i &first, const v8i &second, v4f acc, int s_first, int s_second)
+{
+    if constexpr (SCALED) {
+        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(first, second, acc, 0, 0, 0, s_first, 0, s_second);
+    } else {
+        const v4i f0 = {first[0], first[1], first[2], first[3]}, f1 = {first[4], first[5], first[6], first[7]};
+        const v4i s0 = {second[0], second[1], second[2], second[3]}, s1 = {second[4], second[5], second[6], second[7]};
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, f0), __builtin_bit_cast(v8bf, s0), acc, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, f1), __builtin_bit_cast(v8bf, s1), acc, 0, 0, 0);
+    }
+}
+
 // The kernel. LDS holds two A buffers, two B buffers and their scale dwords; the software pipeline
 // is described at the step lambda below.
 template <class Cfg, bool OUT_BF16, bool TILED>
@@ -93,6 +114,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
+    // K is the length of an operand row in BYTES (= elements for MXFP8, 2 x elements for BF16 operands)
     const int nkb = K / kBlock;  // scale bytes per row
     const int KT = K / BK;
 
@@ -101,7 +123,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     // fetches the logical chunk that the XOR swizzle stores there. Offsets are relative to the
     // tile origin (32-bit: a tile spans at most 256 rows of K bytes).
     const int ld_r = lane >> 3, ld_c = lane & 7;
-    uint32_t a_goff[Cfg::A_LOADS], b_goff[Cfg::B_LOADS], as_goff[Cfg::SA_LOADS], bs_goff[Cfg::SB_LOADS];
+    uint32_t a_goff[Cfg::A_LOADS], b_goff[Cfg::B_LOADS], as_goff[Cfg::SA_LOADS + 1], bs_goff[Cfg::SB_LOADS + 1];
 #pragma unroll
     for (int i = 0; i < Cfg::A_LOADS; ++i) {
         const int row = (wave * Cfg::A_LOADS + i) * 8 + ld_r;
@@ -125,7 +147,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     // Tiled scales: the 64 dwords of a (64-row group, K step) are contiguous, so the instruction that
     // reads one cache line per lane from row-major scales reads 256 consecutive bytes here. A ragged
     // last tile re-reads the last valid group: its rows are never stored.
-    const uint8_t *as_grp[Cfg::SA_LOADS], *bs_grp[Cfg::SB_LOADS];
+    const uint8_t *as_grp[Cfg::SA_LOADS + 1], *bs_grp[Cfg::SB_LOADS + 1];
     if constexpr (TILED) {
 #pragma unroll
         for (int i = 0; i < Cfg::SA_LOADS; ++i)
@@ -223,7 +245,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 #pragma unroll
         for (int j = 0; j < NFB - 1 && j < TN; ++j) {
             fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
-            sb[j] = sbbuf[b_soff + j * 64];
+            sb[j] = Cfg::SCALED ? sbbuf[b_soff + j * 64] : 0;
         }
         MXFP8_PIN();
         int a_slot = 0;  // compile-time after unrolling
@@ -231,7 +253,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         for (int j = 0; j < TN; ++j) {
             if (j + NFB - 1 < TN) {
                 fb[(j + NFB - 1) % NFB] = read_frag(bbuf, b_off0 + (j + NFB - 1) * 2048, b_off1 + (j + NFB - 1) * 2048);
-                sb[(j + NFB - 1) % NFB] = sbbuf[b_soff + (j + NFB - 1) * 64];
+                sb[(j + NFB - 1) % NFB] = Cfg::SCALED ? sbbuf[b_soff + (j + NFB - 1) * 64] : 0;
             }
             if (j == TN - 1) {
                 MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);  // all but this step's requests: A(kt+1) is in LDS
@@ -240,8 +262,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
             MXFP8_PIN();
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j % NFB], fa[i], acc[i][j], 0, 0, 0,
-                                                                             sb[j % NFB], 0, sa[i]);
+                acc[i][j] = mma_step<Cfg::SCALED>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
                 MXFP8_PIN();
                 if (j == 0) {
                     issue_b(i, kt1, nxt);
@@ -254,7 +275,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
                 }
                 if (j == TN - 1) {
                     fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
-                    sa[i] = sanext[a_soff + i * 64];
+                    sa[i] = Cfg::SCALED ? sanext[a_soff + i * 64] : 0;
                 }
                 MXFP8_PIN();
             }
@@ -278,7 +299,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
-            sa[i] = (lds + Cfg::SA_OFF)[a_soff + i * 64];
+            sa[i] = Cfg::SCALED ? (lds + Cfg::SA_OFF)[a_soff + i * 64] : 0;
         }
         __syncthreads();  // A buffer 0 is refilled by the requests of step 0 from here on
     }
@@ -361,7 +382,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     static_assert(!FUSE_Q || (OUT_BF16 && (Cfg::TN == 8 || Cfg::TN == 4) && Cfg::TM == Cfg::TN), "fused output quantization");
     constexpr bool Q_ROW = (FUSE_Q & 1) != 0, Q_COL = (FUSE_Q & 2) != 0;
     static_assert(!Q_COL || Cfg::BM * Cfg::BN <= 2 * Cfg::B_BYTES, "transposed tile fits the two idle buffers");
-    static_assert(Cfg::SA_LOADS == 1 && Cfg::SB_LOADS == 1, "one scale request per wavefront and operand");
+    static_assert(!Cfg::SCALED || (Cfg::SA_LOADS == 1 && Cfg::SB_LOADS == 1), "one scale request per wavefront and operand");
+    static_assert(Cfg::SCALED || FUSE_Q == 0, "output quantization belongs to the MXFP8 product");
     MXFP8_DYNAMIC_LDS(lds);
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     const int tid = threadIdx.x;
@@ -462,7 +484,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
 #pragma unroll
         for (int j = 0; j < NFB - 1 && j < TN; ++j) {
             fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
-            sb[j] = sbbuf[b_soff + j * 64];
+            sb[j] = Cfg::SCALED ? sbbuf[b_soff + j * 64] : 0;
         }
         MXFP8_PIN();
         int a_slot = 0;
@@ -470,7 +492,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         for (int j = 0; j < TN; ++j) {
             if (j + NFB - 1 < TN) {
                 fb[(j + NFB - 1) % NFB] = read_frag(bbuf, b_off0 + (j + NFB - 1) * 2048, b_off1 + (j + NFB - 1) * 2048);
-                sb[(j + NFB - 1) % NFB] = sbbuf[b_soff + (j + NFB - 1) * 64];
+                sb[(j + NFB - 1) % NFB] = Cfg::SCALED ? sbbuf[b_soff + (j + NFB - 1) * 64] : 0;
             }
             if (j == TN - 1) {
                 MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);
@@ -479,8 +501,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             MXFP8_PIN();
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j % NFB], fa[i], acc[i][j], 0, 0, 0,
-                                                                             sb[j % NFB], 0, sa[i]);
+                acc[i][j] = mma_step<Cfg::SCALED>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
                 MXFP8_PIN();
                 if constexpr (SPREAD) {
                     constexpr int A_FIRST = 2 * Cfg::NB + 2;  // MFMA after which the first A request goes out
@@ -501,7 +522,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 }
                 if (j == TN - 1) {
                     fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
-                    sa[i] = sanext[a_soff + i * 64];
+                    sa[i] = Cfg::SCALED ? sanext[a_soff + i * 64] : 0;
                 }
                 MXFP8_PIN();
             }
@@ -528,7 +549,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
-        sa[i] = (lds + Cfg::SA_OFF)[a_soff + i * 64];
+        sa[i] = Cfg::SCALED ? (lds + Cfg::SA_OFF)[a_soff + i * 64] : 0;
     }
     __syncthreads();
 
@@ -852,6 +873,24 @@ hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_
                                stream);
     return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, max_workgroups,
                              stream);
+}
+
+// Product of two BF16 operands, [M x K] and [N x K], both K-contiguous, FP32 accumulation: the GEMM of the
+// simulated path (Section 3.1). Same kernels as the MXFP8 product with the BF16 matrix instruction and no
+// scales; K is counted in elements here and in bytes inside the kernels.
+hipError_t launch_gemm_bf16(const uint8_t *a, const uint8_t *b, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
+                            int64_t ldc, int max_workgroups, hipStream_t stream)
+{
+    using Big = GemmCfg<256, 256, 2, 2, false>;
+    using Small = GemmCfg<128, 128, 2, 2, false>;
+    const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
+    const uint8_t *none = nullptr;
+    const int m = (int)M, n = (int)N, kbytes = (int)(2 * K);
+    if (big)
+        return c_bf16 ? launch_cfg<Big, true, false>(a, none, b, none, m, n, kbytes, c, ldc, max_workgroups, stream)
+                      : launch_cfg<Big, false, false>(a, none, b, none, m, n, kbytes, c, ldc, max_workgroups, stream);
+    return c_bf16 ? launch_cfg<Small, true, false>(a, none, b, none, m, n, kbytes, c, ldc, max_workgroups, stream)
+                  : launch_cfg<Small, false, false>(a, none, b, none, m, n, kbytes, c, ldc, max_workgroups, stream);
 }
 
 // GEMM with BF16 output and MXFP8 copies of that output (axis bit 0: row-wise, bit 1: column-wise) from

@@ -6,6 +6,7 @@
 //   quantize   <f32|bf16> <rows> <cols> <ld> <axis 1|2|3> <src.bin> <out-prefix> [tiled]
 //   gemm       <pass 0|1|2> <M> <N> <K> <f32|bf16> <ldc> <a_q> <a_s> <b_q> <b_s> <c.bin> [tiled]
 //   dequantize <rows> <cols> <f32|bf16> <ld> <q.bin> <s.bin> <out.bin> [tiled]
+//   gemmbf16   <M> <N> <K> <f32|bf16> <ldc> <a.bin> <b.bin> <c.bin>      (BF16 operands, no scales)
 //   gemmq      <pass 0|1|2> <M> <N> <K> <ldc> <axis 1|2|3> <a_q> <a_s> <b_q> <b_s> <out-prefix> [tiled]
 //              (BF16 product <prefix>.c plus the MXFP8 copies of it: .q_row .s_row .q_colT .s_colT)
 // "tiled" selects MXFP8_SCALES_TILED for every scale buffer of the call (sizes from mxfp8_scale_bytes);
@@ -195,6 +196,19 @@ int main(int argc, char **argv)
             unchanged(sa, "a_s");
             unchanged(b, "b_q");
             unchanged(sb, "b_s");
+            report(st);
+            save(cout, c);
+        } else if (op == "gemmbf16") {
+            long M, N, K, ldc;
+            std::string dt, af, bf, cout;
+            ls >> M >> N >> K >> dt >> ldc >> af >> bf >> cout;
+            layout_of(ls);  // only wg=<n> means something here
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf a = load(af, (size_t)M * K * 2), b = load(bf, (size_t)N * K * 2);
+            Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * es : 0);
+            const int st = mxfp8_gemm_bf16(a.p, b.p, M, N, K, c.p, dtype_of(dt), ldc, g_max_workgroups, nullptr);
+            unchanged(a, "a");
+            unchanged(b, "b");
             report(st);
             save(cout, c);
         } else if (op == "gemmq") {

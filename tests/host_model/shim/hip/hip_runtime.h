@@ -69,6 +69,7 @@ inline uint32_t __float_as_uint(float f)
     ::wavesim::cvt_scalef32_pk_bf8_bf16((old), (p), (scale), (hi))
 #define __builtin_amdgcn_cvt_pk_f32_bf8(q, hi) ::wavesim::cvt_pk_f32_bf8((q), (hi))
 #define __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(...) ::wavesim::mfma_scale_16x16x128(__VA_ARGS__)
+#define __builtin_amdgcn_mfma_f32_16x16x32_bf16(...) ::wavesim::mfma_16x16x32_bf16(__VA_ARGS__)
 
 // ---- runtime calls of the launchers --------------------------------------------------------------
 typedef void *hipStream_t;

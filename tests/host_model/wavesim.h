@@ -46,6 +46,7 @@ namespace wavesim {
 typedef short v2s __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -476,6 +477,42 @@ inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp
             for (int k = 32 * kb; k < 32 * kb + 32; ++k)
                 part += xv[k] * yv[k];
             sum += part * xs[kb] * ys[kb];
+        }
+        out[v] = (float)((double)c[v] + sum);
+    }
+    unpublish();
+    return out;
+}
+
+// v_mfma_f32_16x16x32_bf16: lane 16g+r holds row r of its operand, k = 8g..8g+7; result register v of
+// lane (r, g) is D[4g+v][r] with D[x][y] = sum_k first[x][k] * second[y][k]. Every product is exact in
+// double; the sum is taken in double and rounded once, which is at least as accurate as the instruction.
+inline v4f mfma_16x16x32_bf16(v8bf16 first, v8bf16 second, v4f c, int cbsz, int abid, int blgp)
+{
+    if (cbsz != 0 || abid != 0 || blgp != 0)
+        fail("broadcast / permute modifiers of the BF16 matrix instruction are not modelled");
+    struct Pub {
+        v8bf16 first, second;
+    } pub{first, second};
+    Wave &w = publish(pub);
+    const int lane = g.cur->lane, r = lane & 15, gq = lane >> 4;
+    for (int l = 0; l < kWave; ++l)
+        if (!w.present[l])
+            fail("MFMA issued with lane %d inactive", l);
+    double yv[32];
+    for (int kg = 0; kg < 4; ++kg) {
+        const Pub p = peek<Pub>(w, 16 * kg + r);
+        for (int t = 0; t < 8; ++t)
+            yv[8 * kg + t] = (double)(float)p.second[t];
+    }
+    v4f out;
+    for (int v = 0; v < 4; ++v) {
+        const int x = 4 * gq + v;
+        double sum = 0.0;
+        for (int kg = 0; kg < 4; ++kg) {
+            const Pub p = peek<Pub>(w, 16 * kg + x);
+            for (int t = 0; t < 8; ++t)
+                sum += (double)(float)p.first[t] * yv[8 * kg + t];
         }
         out[v] = (float)((double)c[v] + sum);
     }

@@ -32,7 +32,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == ["mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex", "mxfp8_gemm",
-                                    "mxfp8_gemm_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
+                                    "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
                                     "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
 
@@ -154,6 +154,21 @@ def test_gemm_validation_needs_no_gpu(lib):
     assert f(0, P(0x1008), FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, None) == 3
     assert f(0, *ok, 64, 64, 128, P(0x1002), 0, 64, None) == 3                   # FP32 c needs 4-byte alignment
     assert f(0, *ok, 0, 64, 128, None, 0, 64, None) == 0
+
+
+def test_bf16_gemm_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_gemm_bf16
+    f.argtypes = [P, P, I64, I64, I64, P, ctypes.c_int, I64, ctypes.c_int32, P]
+    assert f(FAKE, FAKE, 64, 64, 64, FAKE, 2, 64, 0, None) == 4                  # output type
+    assert f(FAKE, FAKE, 64, 64, 64, FAKE, 0, 64, -1, None) == 5                 # negative workgroup bound
+    assert f(FAKE, FAKE, 64, 64, 96, FAKE, 0, 64, 0, None) == 2                  # K % 64
+    assert f(FAKE, FAKE, 64, 64, 64, FAKE, 0, 63, 0, None) == 2                  # ldc < N
+    assert f(FAKE, FAKE, 64, 64, (1 << 23) + 64, FAKE, 0, 64, 0, None) == 2      # row bytes beyond the 32-bit tile offsets
+    assert f(None, FAKE, 64, 64, 64, FAKE, 0, 64, 0, None) == 1
+    assert f(FAKE, FAKE, 64, 64, 64, None, 0, 64, 0, None) == 1
+    assert f(P(0x1008), FAKE, 64, 64, 64, FAKE, 0, 64, 0, None) == 3
+    assert f(FAKE, FAKE, 64, 64, 64, P(0x1002), 0, 64, 0, None) == 3
+    assert f(FAKE, FAKE, 0, 64, 64, None, 0, 64, 0, None) == 0
 
 
 def test_dequantize_validation_needs_no_gpu(lib):

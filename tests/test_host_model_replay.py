@@ -53,3 +53,11 @@ def test_layout_persistent_and_fused_gpu_tests_pass_on_the_host_model(hostmodel_
                "and not (persistent_gemm_matches and (shape2 or shape3 or shape4)) "
                "and not (fused_output and (shape2 or shape3))")
     assert n >= 34
+
+
+def test_simulated_path_gpu_tests_pass_on_the_host_model(hostmodel_lib):
+    """The BF16 product and the round trip of the simulated path; the long-K, 2048 x 4096 and full-size cases
+    are left to the GPU."""
+    n = replay(hostmodel_lib, ["test_gpu_simulated.py"],
+               "not full_size and not (matches_oracle and (shape3 or shape4 or shape5)) and not (small_integers and shape7)")
+    assert n >= 18
