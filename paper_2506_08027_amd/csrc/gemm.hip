@@ -372,7 +372,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 //                are transposed through the two LDS buffers that are idle between tiles (the B buffer the
 //                finished step read and the A buffer whose fragments already sit in registers) and leave
 //                as full lines of cqT.
-template <class Cfg, bool OUT_BF16, bool TILED, bool SPREAD, int FUSE_Q = 0>
+#ifndef MXFP8_GEMM_SCHED
+#define MXFP8_GEMM_SCHED 242  // B requests behind every 2nd MFMA, a gap of 2, A requests behind every 4th
+#endif
+template <class Cfg, bool OUT_BF16, bool TILED, bool SPREAD, int FUSE_Q = 0, int SCHED = MXFP8_GEMM_SCHED>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
@@ -504,13 +507,15 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 acc[i][j] = mma_step<Cfg::SCALED>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
                 MXFP8_PIN();
                 if constexpr (SPREAD) {
-                    constexpr int A_FIRST = 2 * Cfg::NB + 2;  // MFMA after which the first A request goes out
-                    static_assert(A_FIRST + 4 * (Cfg::NA - 1) < (TN - 1) * TM, "all requests before the last column");
+                    // SCHED = 100 * gap + 10 * A spacing + B spacing (in MFMAs)
+                    constexpr int B_EVERY = SCHED % 10, A_EVERY = SCHED / 10 % 10, GAP = SCHED / 100;
+                    constexpr int A_FIRST = B_EVERY * Cfg::NB + GAP;  // MFMA after which the first A request goes out
+                    static_assert(A_FIRST + A_EVERY * (Cfg::NA - 1) < (TN - 1) * TM, "all requests before the last column");
                     const int m = j * TM + i;  // compile-time after unrolling
-                    if (m % 2 == 0 && m / 2 < Cfg::NB)
-                        issue_b(m / 2, b_src, bs_src, nxt);
-                    else if (m >= A_FIRST && (m - A_FIRST) % 4 == 0 && (m - A_FIRST) / 4 < Cfg::NA)
-                        issue_a((m - A_FIRST) / 4, a_src, as_src, cur);
+                    if (m % B_EVERY == 0 && m / B_EVERY < Cfg::NB)
+                        issue_b(m / B_EVERY, b_src, bs_src, nxt);
+                    else if (m >= A_FIRST && (m - A_FIRST) % A_EVERY == 0 && (m - A_FIRST) / A_EVERY < Cfg::NA)
+                        issue_a((m - A_FIRST) / A_EVERY, a_src, as_src, cur);
                 } else if (j == 0) {
                     issue_b(i, b_src, bs_src, nxt);
                     if (i + TM < Cfg::NB)
@@ -585,15 +590,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             par ^= 1;
         }
         // ---- epilogue of this tile; the A requests of the next tile's second step are in flight.
-        // Every store of a lane has the same 32-bit offset from a wavefront-uniform base (row group i)
-        // plus a constant (column tile j): no per-store address arithmetic, few live registers next to
-        // the A fragments of the next tile. Rows are finished one after the other (pinned) so that the
-        // converted values of only one row group are live at a time.
+        // Row groups (16 rows of the wavefront's part) are finished one after the other (pinned), each through
+        // the wavefront's staging area, so that the converted values of only one row group are live at a
+        // time next to the A fragments of the next tile.
         constexpr int ESZ = OUT_BF16 ? 2 : 4;
         if constexpr (Q_COL)
             __syncthreads();  // every wavefront's fragment refills have left the A buffer that is reused below
         uint8_t *ctile = c + (int64_t)cur_tile.m0 * ldc_bytes + (int64_t)cur_tile.n0 * ESZ;
-        const uint32_t lane_off = (uint32_t)(wm * Cfg::WM + r16) * (uint32_t)ldc_bytes + (uint32_t)(wn * Cfg::WN + 4 * g) * ESZ;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             uint8_t *crow = ctile + (int64_t)(i * 16) * ldc_bytes;
@@ -603,9 +606,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             for (int j = 0; j < TN; ++j)
                 MXFP8_KEEP_IN_ACC(acc[i][j]);
             if constexpr (Q_ROW) {
+                // BF16 rows and their MXFP8 copy both leave through the wavefront's staging area (see the plain
+                // epilogue below for why): first the 16 BF16 rows, then, in the same area, the 16 byte rows.
                 const int64_t m = cur_tile.m0 + wm * Cfg::WM + i * 16 + r16;        // this lane's row of C
                 const int n_wave = cur_tile.n0 + wn * Cfg::WN;                       // first column of the wavefront
+                constexpr int ROWB = Cfg::WN * 2, PITCH = ROWB + 32;                 // BF16 row and its staged pitch
+                constexpr int QPITCH = Cfg::WN + 16;                                 // staged pitch of a byte row
+                static_assert(16 * PITCH <= kStageBytes && (16 * ROWB) % 1024 == 0 && (16 * Cfg::WN) % 1024 == 0, "staging area");
+                uint8_t *stage = lds + Cfg::LDS_BYTES + wave * kStageBytes;
                 uint32_t scales = 0;                                                 // scale bytes of the row's blocks
+                uint32_t q[TN];
 #pragma unroll
                 for (int blk = 0; blk < TN / 2; ++blk) {
                     uint32_t h[4];  // BF16 pairs: columns 4g..4g+3 of tile 2*blk, then of tile 2*blk+1
@@ -615,7 +625,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                         v2bf p0 = {(__bf16)v[0], (__bf16)v[1]}, p1 = {(__bf16)v[2], (__bf16)v[3]};
                         h[2 * t] = __builtin_bit_cast(uint32_t, p0);
                         h[2 * t + 1] = __builtin_bit_cast(uint32_t, p1);
-                        *reinterpret_cast<uint2 *>(crow + lane_off + (2 * blk + t) * 16 * ESZ) = make_uint2(h[2 * t], h[2 * t + 1]);
+                        *reinterpret_cast<uint2 *>(stage + r16 * PITCH + ((2 * blk + t) * 16 + 4 * g) * 2) = make_uint2(h[2 * t], h[2 * t + 1]);
                     }
                     // block amax on the magnitude bits: 8 values here, then the 3 other lanes of the row
                     uint32_t am = pk_max_u16(pk_max_u16(h[0] & 0x7FFF7FFFu, h[1] & 0x7FFF7FFFu),
@@ -625,27 +635,45 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                     am = umax(am, (uint32_t)__shfl_xor((int)am, 32, 64));
                     const uint32_t sb = scale_byte_from_bf16_bits(am);
                     const float sc = scale_operand(sb);
-                    uint32_t q[2];
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        q[t] = cvt2_bf16(cvt2_bf16(0, h[2 * t], sc, false), h[2 * t + 1], sc, true);
+                        uint32_t qt = cvt2_bf16(cvt2_bf16(0, h[2 * t], sc, false), h[2 * t + 1], sc, true);
                         if (sb >= 254) {  // NaN or Inf in the block: rare
                             if (sb == 0xFF) {
-                                q[t] = 0x7F7F7F7Fu;
+                                qt = 0x7F7F7F7Fu;
                             } else {
                                 uint32_t f = 0;
 #pragma unroll
                                 for (int e = 0; e < 4; ++e) {
                                     const uint32_t bits = (e & 1) ? h[2 * t + e / 2] >> 16 : h[2 * t + e / 2] & 0xFFFFu;
-                                    f |= inf_byte_bf16(bits, (q[t] >> (8 * e)) & 0xFFu) << (8 * e);
+                                    f |= inf_byte_bf16(bits, (qt >> (8 * e)) & 0xFFu) << (8 * e);
                                 }
-                                q[t] = f;
+                                qt = f;
                             }
                         }
-                        *reinterpret_cast<uint32_t *>(cq + m * N + n_wave + (2 * blk + t) * 16 + 4 * g) = q[t];
+                        q[2 * blk + t] = qt;
                     }
                     scales |= sb << (8 * blk);
                 }
+                __builtin_amdgcn_wave_barrier();  // the reads below see the other lanes' writes (LDS serves a wavefront in order)
+#pragma unroll
+                for (int t = 0; t < 16 * ROWB / 1024; ++t) {
+                    const int lin = t * 1024 + lane * 16, row = lin / ROWB, colb = lin % ROWB;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * PITCH + colb);
+                    *reinterpret_cast<uint4 *>(crow + (int64_t)(wm * Cfg::WM + row) * ldc_bytes + wn * ROWB + colb) = v;
+                }
+                __builtin_amdgcn_wave_barrier();  // the byte rows overwrite the area after these reads
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    *reinterpret_cast<uint32_t *>(stage + r16 * QPITCH + j * 16 + 4 * g) = q[j];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int t = 0; t < 16 * Cfg::WN / 1024; ++t) {
+                    const int lin = t * 1024 + lane * 16, row = lin / Cfg::WN, colb = lin % Cfg::WN;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * QPITCH + colb);
+                    *reinterpret_cast<uint4 *>(cq + (cur_tile.m0 + wm * Cfg::WM + i * 16 + row) * (int64_t)N + n_wave + colb) = v;
+                }
+                __builtin_amdgcn_wave_barrier();  // (the next row group overwrites the area after these reads)
                 if (g == 0) {  // the TN/2 scale bytes of this row and wavefront: one dword or halfword
                     const int64_t nb = N / kBlock, b0 = n_wave / kBlock;
                     uint8_t *sp = TILED ? cs + (((m >> 6) * ((nb + 3) / 4) + (b0 >> 2)) * 64 + (m & 63)) * 4 + (b0 & 3)
