@@ -195,6 +195,52 @@ def gemm(a_q, a_s, b_q, b_s):
     return gemm_rows(a_q, a_s, b_q, b_s, np.arange(np.asarray(a_q).shape[0]))
 
 
+# ---- grouped product (Appendix A.4: mixture-of-experts layers) ------------------------------------------
+def grouped_gemm(a_q, a_s, b_q, b_s, group_ends):
+    """Expert-batched tokens: the rows of A are sorted by expert, rows [group_ends[e-1], group_ends[e]) belong to
+    expert e, and every expert has its own B: b_q [E x N x K], b_s [E x N x K/32]. Row m of expert e gives
+    C[m, :] = A[m, :] . B_e^T, the same block-scaled dot products as gemm(). Returns (C, sum|a*b|), [M x N].
+    Rows at or beyond group_ends[-1] belong to no expert and come back as NaN."""
+    a_q, a_s = _check_qs(a_q, a_s)
+    b_q, b_s = np.ascontiguousarray(b_q), np.ascontiguousarray(b_s)
+    ends = [int(e) for e in group_ends]
+    if b_q.ndim != 3 or b_q.shape[0] != len(ends) or b_s.shape[:2] != b_q.shape[:2]:
+        raise ValueError("one B operand per group expected")
+    M = a_q.shape[0]
+    C = np.full((M, b_q.shape[1]), np.nan)
+    A = np.full((M, b_q.shape[1]), np.nan)
+    start = 0
+    for e, end in enumerate(ends):
+        if not start <= end <= M:
+            raise ValueError("group ends must be non-decreasing and at most M")
+        if end > start:
+            C[start:end], A[start:end] = gemm_rows(a_q, a_s, b_q[e], b_s[e], np.arange(start, end))
+        start = end
+    return C, A
+
+
+def grouped_gemm_wgrad(a_q, a_s, b_q, b_s, group_ends):
+    """The weight-gradient product of the same layer: A = dY_colT [M x T], B = X_colT [N x T], tokens (the
+    reduction axis) sorted by expert; expert e owns columns [group_ends[e-1], group_ends[e]) of both operands,
+    which must be whole 32-token blocks. Returns (C, sum|a*b|), each [E x M x N]: one dW per expert (zeros for an
+    expert without tokens)."""
+    a_q, a_s = _check_qs(a_q, a_s)
+    b_q, b_s = _check_qs(b_q, b_s)
+    ends = [int(e) for e in group_ends]
+    M, N = a_q.shape[0], b_q.shape[0]
+    C = np.zeros((len(ends), M, N))
+    A = np.zeros((len(ends), M, N))
+    start = 0
+    for e, end in enumerate(ends):
+        if not start <= end <= a_q.shape[1] or start % K_BLOCK or end % K_BLOCK:
+            raise ValueError("group ends must be non-decreasing multiples of 32 and at most K")
+        if end > start:
+            sl, bl = slice(start, end), slice(start // K_BLOCK, end // K_BLOCK)
+            C[e], A[e] = gemm(a_q[:, sl], a_s[:, bl], b_q[:, sl], b_s[:, bl])
+        start = end
+    return C, A
+
+
 # ---- simulated MX path (Section 3.1): BF16 -> MXFP8 -> BF16 round trip, then a BF16 product -----------
 def roundtrip_bf16(src: np.ndarray, axis: str = "row") -> np.ndarray:
     """BF16 source (uint16 bit patterns, [rows x cols]) converted to MXFP8 along `axis` and straight back
