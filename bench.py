@@ -24,7 +24,8 @@ the rate a register-only loop of the matrix instruction sustains in this very ru
 `plain_copy_gbs` in the quantize rooflines is a plain device copy of the same tensor under the same rotation.
 `fused_output_quantization` times the forward product with the MXFP8 copies of Y emitted from its epilogue
 against the product followed by a stand-alone quantize of Y; `simulated_path` times the BF16 product of the
-round-tripped operands (Section 3.1) against the BF16 matrix peak.
+round-tripped operands (Section 3.1) against the BF16 matrix peak; `grouped_moe` times the grouped forward
+product of a mixture-of-experts layer (Appendix A.4).
 `layer_set_16384` times the three products of each linear layer of an 8B-class transformer block at
 16384 tokens. `cpu_baseline` times the CPU oracle on a bounded sample.
 """
@@ -282,6 +283,42 @@ def main():
                 "avg_ms": ms, "launches": 20, "round_trip_X_ms": rt,
                 "round_trip_X_gbs": T * H * (2 + 1.03125 + 1.03125 + 2) / (rt * 1e-3) / 1e9}
 
+    def grouped_moe():
+        """Mixture-of-experts forward product (Appendix A.4): 16384 routed tokens sorted by expert, 8 experts of
+        the benchmark's shape (4096 -> 14336), uneven expert loads with one empty expert, group ends on the GPU."""
+        T5, E = 16384, 8
+        g = torch.Generator(device=dev)
+        g.manual_seed(8)
+        x = torch.randn((T5, H), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        xq = mx.quantize(x, "rowwise", scale_layout=lay)
+        wq, ws = [], []
+        for _ in range(E):
+            w = (0.02 * torch.randn((O, H), generator=g, device=dev, dtype=torch.float32)).to(torch.bfloat16)
+            q = mx.quantize(w, "rowwise", scale_layout=lay)
+            wq.append(q["q_row"]); ws.append(q["s_row"])
+            del w, q
+        b_q, b_s = torch.stack(wq), torch.cat(ws)
+        del wq, ws
+        ends = torch.tensor([1536, 4096, 4096, 7808, 9984, 12032, 14976, 16384], dtype=torch.int32, device=dev)
+        y = torch.empty((T5, O), dtype=torch.bfloat16, device=dev)
+        ms = ms_avg(lambda: mx.mxfp8_gemm_grouped_ex(mx.FPROP, xq["q_row"], xq["s_row"], b_q, b_s, ends, y, lay), reps=10)
+        tf = 2.0 * T5 * H * O / (ms * 1e-3) / 1e12
+        res = {"bound": "mfma", "achieved": tf, "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_FP8_PEAK_TFLOPS,
+               "kernel": f"gemm_persistent_kernel, grouped (fprop, {T5} tokens over {E} experts {H}->{O}, BF16 out)",
+               "avg_ms": ms, "launches": 10}
+        del b_q, b_s, xq
+        # weight gradient of the same layer: dW_e [O x H] for every expert, FP32
+        dy = (1e-3 * torch.randn((T5, O), generator=g, device=dev, dtype=torch.float32)).to(torch.bfloat16)
+        dyq, xcq = mx.quantize(dy, "colwise", scale_layout=lay), mx.quantize(x, "colwise", scale_layout=lay)
+        del dy, x, y
+        dw = torch.empty((E, O, H), dtype=torch.float32, device=dev)
+        ms_w = ms_avg(lambda: mx.mxfp8_gemm_grouped_ex(mx.WGRAD, dyq["q_colT"], dyq["s_colT"], xcq["q_colT"], xcq["s_colT"], ends,
+                                                       dw, lay), reps=10)
+        res["wgrad_tflops"] = 2.0 * T5 * H * O / (ms_w * 1e-3) / 1e12
+        res["wgrad_ms"] = ms_w
+        res["wgrad_kernel"] = "gemm_kernel, reduction axis grouped (one workgroup per expert and tile, FP32 out)"
+        return res
+
     def sustained_mfma_tflops():
         """What the matrix pipes of this GPU sustain on the scaled FP8 instruction alone (operands in registers,
         pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling a GEMM
@@ -323,7 +360,7 @@ def main():
         extras["quant_bf16"] = (q_ms, q_fp, 160, rotating_copy_gbs(X, 8, 160))
         extras["quant_f32"] = (f_ms, f_fp, 100, rotating_copy_gbs(dY, 2, 100))
         for key, fn in (("fused_output_quantization", fused_output_quantization), ("simulated_path", simulated_path),
-                        ("layer_set", layer_set)):
+                        ("grouped_moe", grouped_moe), ("layer_set", layer_set)):
             try:
                 extras[key] = fn()
             except Exception as exc:   # the headline measurement must survive a problem in an extra one
@@ -379,7 +416,7 @@ def main():
                         "plain_copy_gbs": copy_gbs, "frac_of_plain_copy": gbs / copy_gbs}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
-    for key in ("fused_output_quantization", "simulated_path"):
+    for key in ("fused_output_quantization", "simulated_path", "grouped_moe"):
         if key in extras:
             out[key] = extras[key]
     if "layer_set" in extras:

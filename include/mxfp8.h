@@ -169,6 +169,39 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
                            int32_t max_workgroups, void *hip_stream);
 
 /*
+ * Grouped products for mixture-of-experts layers (Appendix A.4: the recipe applies unchanged to the expert
+ * GEMMs). Tokens are sorted by expert: tokens [group_ends[e-1], group_ends[e]) (from 0 for e = 0) belong to
+ * expert e. group_ends is a DEVICE array of `groups` int32 (token counts come from the router on the GPU;
+ * nothing is copied back): non-decreasing, the last at most the number of tokens. The library cannot check
+ * its contents: ends are clamped to [previous end, number of tokens] on the device so that no access leaves
+ * a buffer, but ends that break the alignment rules below give undefined values. An expert may be empty.
+ *
+ * MXFP8_FPROP (A = X_row, B_e = W_e_row) and MXFP8_DGRAD (A = dY_row, B_e = W_e_colT): tokens are the M rows of A,
+ *   a_q [M x K], a_s            one operand, as in mxfp8_gemm_ex
+ *   b_q [groups x N x K]        expert e's operand starts N*K bytes after expert e-1's
+ *   b_s                         expert e's scales start mxfp8_scale_bytes(N, K, scale_layout) bytes after e-1's
+ *   c   [M x N], ldc            C[m, :] = A[m, :] . B_e^T for the expert e that owns row m; rows at or beyond
+ *                               group_ends[groups-1] are not written.
+ *   With MXFP8_SCALES_TILED every end must be a multiple of 64 (the scale layout's row group). Requirements:
+ *   N % 128 == 0, K % 128 == 0, K >= 256; c 16-byte aligned, ldc * sizeof(element) a multiple of 16. One resident
+ *   workgroup per compute unit (at most max_workgroups if positive) walks over the tiles; the result does
+ *   not depend on that number.
+ * MXFP8_WGRAD (A = dY_colT [M x K], B = X_colT [N x K]): tokens are the reduction axis K of both operands,
+ *   every end must be a multiple of 128 (whole K steps; ends in between are cut down to one), and each expert
+ *   gets its own product over its own tokens:
+ *   c   [groups x M x N]        dW_e starts M*ldc elements after dW_(e-1); an expert without tokens gets zeros.
+ *   Requirements: K % 128 == 0; c aligned to its element size (128-bit stores when c is 16-byte aligned and
+ *   ldc * sizeof(element) and M * ldc * sizeof(element) are multiples of 16). One workgroup per expert and tile;
+ *   max_workgroups is ignored.
+ * All passes: groups <= 4096; a_q, a_s, b_q, b_s 16-byte aligned, group_ends 4-byte aligned.
+ */
+mxfp8_status mxfp8_gemm_grouped_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s,
+                                   const uint8_t *b_q, const uint8_t *b_s, const int32_t *group_ends,
+                                   int32_t groups, int64_t M, int64_t N, int64_t K, void *c,
+                                   mxfp8_dtype c_dtype, int64_t ldc, mxfp8_scale_layout scale_layout,
+                                   int32_t max_workgroups, void *hip_stream);
+
+/*
  * The GEMM of the simulated MX path (Section 3.1: the paper's own training runs convert every BF16 GEMM
  * input to MXFP8 and straight back to BF16 and then run an ordinary BF16 GEMM):
  *   C[m, n] = sum_k A[m, k] * B[n, k],  A [M x K] and B [N x K] dense BF16, both K-contiguous,

@@ -67,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_quantize_mode_ex.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, ci, vp]
     lib.mxfp8_dequantize_mode_ex.restype = ci
     lib.mxfp8_dequantize_mode_ex.argtypes = [vp, vp, i64, i64, ci, vp, ci, i64, ci, vp]
+    lib.mxfp8_gemm_grouped_ex.restype = ci
+    lib.mxfp8_gemm_grouped_ex.argtypes = [ci, vp, vp, vp, vp, vp, ctypes.c_int32, i64, i64, i64, vp, ci, i64, ci, ctypes.c_int32, vp]
     lib.mxfp8_gemm_bf16.restype = ci
     lib.mxfp8_gemm_bf16.argtypes = [vp, vp, i64, i64, i64, vp, ci, i64, ctypes.c_int32, vp]
     lib.mxfp8_mfma_rate_probe.restype = ci
@@ -186,6 +188,42 @@ def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, ma
         raise MXFP8Error(rc, "mxfp8_gemm")
 
 
+def mxfp8_gemm_grouped_ex(pass_, a_q, a_s, b_q, b_s, group_ends, c, scale_layout=SCALES_ROWMAJOR, max_workgroups=0,
+                          stream=None) -> None:
+    """Grouped products over expert-sorted tokens; group_ends = int32 GPU tensor of E non-decreasing token numbers.
+    fprop / dgrad: a_q [M x K] (tokens are rows), b_q [E x N x K] and b_s (E scale operands, each in `scale_layout`),
+    c [M x N]. wgrad: a_q [M x K], b_q [N x K] (tokens are the K axis of both), c [E x M x N]."""
+    _need_cuda(a_q, a_s, b_q, b_s, group_ends, c)
+    wgrad = _PASS[pass_] == WGRAD
+    M, K = a_q.shape
+    E = group_ends.numel()
+    if group_ends.dtype != torch.int32 or not group_ends.is_contiguous():
+        raise ValueError("group_ends must be contiguous int32")
+    _check_scales(a_s, M, K, scale_layout, "a_s")
+    if wgrad:
+        N, Kb = b_q.shape
+        _check_scales(b_s, N, K, scale_layout, "b_s")
+        if tuple(c.shape) != (E, M, N) or (c.numel() and (c.stride(2) != 1 or c.stride(0) != M * c.stride(1))):
+            raise ValueError("c must be [E x M x N] with contiguous rows and experts M rows apart")
+        ldc = c.stride(1) if M > 1 else max(N, 1)
+    else:
+        Eb, N, Kb = b_q.shape
+        if Eb != E or b_s.numel() != E * mxfp8_scale_bytes(N, K, scale_layout):
+            raise ValueError("b_q must be [E x N x K] with one scale operand per group in b_s")
+        if tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
+            raise ValueError("c must be [M x N] with contiguous rows")
+        ldc = c.stride(0) if M > 1 else max(N, 1)
+    if K != Kb:
+        raise ValueError("operands disagree on K")
+    for t in (a_q, a_s, b_q, b_s):
+        if not t.is_contiguous() or t.dtype != torch.uint8:
+            raise ValueError("quantized operands must be dense uint8")
+    rc = load().mxfp8_gemm_grouped_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), _ptr(group_ends), E, M, N, K,
+                                      _ptr(c), _dtype_code(c.dtype), ldc, scale_layout, max_workgroups, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_gemm_grouped_ex")
+
+
 def mxfp8_gemm_bf16(a, b, c, max_workgroups=0, stream=None) -> None:
     """c [M x N] (float32 or bfloat16) = a [M x K] * b[N x K]^T for dense bfloat16 operands: the GEMM of the
     simulated MX path."""
@@ -297,6 +335,17 @@ def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR, element=E4M3, rule=
 def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
     c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
     mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout, max_workgroups)
+    return c
+
+
+def gemm_grouped(pass_, a_q, a_s, b_q, b_s, group_ends, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
+    """Allocates the output of mxfp8_gemm_grouped_ex and calls it: c [M x N] for fprop / dgrad (filled with NaN
+    first: rows that belong to no group are not written), c [E x M x N] for wgrad."""
+    if _PASS[pass_] == WGRAD:
+        c = torch.empty((group_ends.numel(), a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
+    else:
+        c = torch.full((a_q.shape[0], b_q.shape[1]), float("nan"), dtype=out_dtype, device=a_q.device)
+    mxfp8_gemm_grouped_ex(pass_, a_q, a_s, b_q, b_s, group_ends, c, scale_layout, max_workgroups)
     return c
 
 

@@ -17,6 +17,13 @@ hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8
                              int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
                              uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, int max_workgroups,
                              hipStream_t stream);
+hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                               const int32_t *group_ends, int groups, int64_t b_group_bytes, int64_t bs_group_bytes,
+                               int64_t M, int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                               int max_workgroups, hipStream_t stream);
+hipError_t launch_gemm_kgrouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                                const int32_t *group_ends, int groups, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
+                                bool tiled_scales, int64_t ldc, hipStream_t stream);
 hipError_t launch_gemm_bf16(const uint8_t *a, const uint8_t *b, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
                             int64_t ldc, int max_workgroups, hipStream_t stream);
 hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream);
@@ -32,6 +39,7 @@ constexpr int64_t kMaxDim = 0x7FFFFFFF;  // kernels index rows and columns with 
 // a 256-row operand tile (255 * K + 127) stays in 32 bits unsigned, and the grid (one workgroup per
 // 128x128 tile at the finest) fits the launch
 constexpr int64_t kMaxGemmMN = int64_t(1) << 30, kMaxGemmK = int64_t(1) << 24;
+constexpr int32_t kMaxGroups = 4096;  // every tile lookup of the grouped product scans the group ends
 }  // namespace
 
 extern "C" {
@@ -123,6 +131,40 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
     const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16,
                                             scale_layout == MXFP8_SCALES_TILED, ldc, max_workgroups,
                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_gemm_grouped_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
+                                   const uint8_t *b_s, const int32_t *group_ends, int32_t groups, int64_t M, int64_t N,
+                                   int64_t K, void *c, mxfp8_dtype c_dtype, int64_t ldc, mxfp8_scale_layout scale_layout,
+                                   int32_t max_workgroups, void *hip_stream)
+{
+    if (!valid_dtype(c_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout) || max_workgroups < 0 || (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD))
+        return MXFP8_ERR_MODE;
+    const bool wgrad = pass == MXFP8_WGRAD;  // experts split the reduction axis; otherwise the rows of A
+    if (groups < 0 || groups > kMaxGroups || M < 0 || N < 0 || K < 0 || M > kMaxGemmMN || N > kMaxGemmMN || K > kMaxGemmK ||
+        K % 128 || ldc < N)
+        return MXFP8_ERR_SHAPE;
+    if (wgrad ? ((M + 127) / 128) * ((N + 127) / 128) * groups > kMaxDim
+              : (K < 256 || N % 128 || ((M + 127) / 128 + groups) * ((N + 127) / 128) > kMaxDim))
+        return MXFP8_ERR_SHAPE;
+    if (M == 0 || N == 0 || groups == 0)
+        return MXFP8_OK;
+    if (!c || !group_ends || (K > 0 && (!a_q || !a_s || !b_q || !b_s)))
+        return MXFP8_ERR_NULL;
+    if ((K > 0 && (!aligned16(a_q) || !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))) ||
+        reinterpret_cast<uintptr_t>(group_ends) % 4)
+        return MXFP8_ERR_ALIGN;
+    if (wgrad ? reinterpret_cast<uintptr_t>(c) % esize(c_dtype) != 0 : (!aligned16(c) || (ldc * esize(c_dtype)) % 16))
+        return MXFP8_ERR_ALIGN;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool tiled = scale_layout == MXFP8_SCALES_TILED;
+    const hipError_t e =
+        wgrad ? mxfp8::launch_gemm_kgrouped(a_q, a_s, b_q, b_s, group_ends, groups, M, N, K, c, c_dtype == MXFP8_BF16, tiled, ldc, stream)
+              : mxfp8::launch_gemm_grouped(a_q, a_s, b_q, b_s, group_ends, groups, N * K, mxfp8_scale_bytes(N, K, scale_layout), M,
+                                           N, K, c, c_dtype == MXFP8_BF16, tiled, ldc, max_workgroups, stream);
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

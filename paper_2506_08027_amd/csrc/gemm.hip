@@ -56,14 +56,14 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool SCALED_ = true> str
 // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2. Renumber them so
 // that consecutive logical ids run on the same XCD, then walk the tile grid in column panels of
 // `PANEL` tiles so that the workgroups resident on one XCD share A rows and B rows in its L2.
-__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int &tm,
-                                              int &tn)
+__device__ __forceinline__ int xcd_logical_id(int bid, int nblocks)
 {
     constexpr int XCDS = 8;
-    int lid = bid;
     const int full = (nblocks / XCDS) * XCDS;
-    if (bid < full)
-        lid = (bid % XCDS) * (nblocks / XCDS) + bid / XCDS;
+    return bid < full ? (bid % XCDS) * (nblocks / XCDS) + bid / XCDS : bid;
+}
+__device__ __forceinline__ void panel_tile(int lid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
     constexpr int PANEL = 8;
     const int per_panel = PANEL * tiles_m;
     const int panel = lid / per_panel;
@@ -71,6 +71,11 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
     const int width = min(PANEL, tiles_n - panel * PANEL);
     tm = in_panel / width;
     tn = panel * PANEL + in_panel % width;
+}
+__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int &tm,
+                                              int &tn)
+{
+    panel_tile(xcd_logical_id(bid, nblocks), tiles_m, tiles_n, tm, tn);
 }
 
 // Nothing may be scheduled across this point: the instruction order below is the schedule.
@@ -95,13 +100,26 @@ __device__ __forceinline__ v4f mma_step(const v8i &first, const v8i &second, v4f
     }
 }
 
+// Expert groups of the grouped products (Appendix A.4), see gemm_persistent_kernel (rows of A grouped) and
+// gemm_kernel (the reduction axis grouped).
+struct GemmGroups {
+    const int32_t *ends;  // device memory, `count` non-decreasing row numbers, the last one <= M
+    int count;
+    int64_t b_group_bytes, bs_group_bytes;
+};
+
 // The kernel. LDS holds two A buffers, two B buffers and their scale dwords; the software pipeline
 // is described at the step lambda below.
-template <class Cfg, bool OUT_BF16, bool TILED>
+// KGROUPED (Appendix A.4, weight gradient of a mixture-of-experts layer): the reduction axis is the token
+// axis, sorted by expert; expert e owns K range [group_ends[e-1], group_ends[e]) of both operands and gets its
+// own output [M x N], `M * ldc` elements after the previous expert's. Workgroup = (expert, tile); the K range
+// comes from device memory, is clamped to [previous end, K] and cut down to whole K steps (ends have to be
+// multiples of 128 tokens); an expert without tokens stores zeros.
+template <class Cfg, bool OUT_BF16, bool TILED, bool KGROUPED = false>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
-    const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
-    int tiles_m, int tiles_n, bool vec_store)
+    const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c_all, int64_t ldc_bytes,
+    int tiles_m, int tiles_n, bool vec_store, GemmGroups groups)
 {
     MXFP8_DYNAMIC_LDS(lds);
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -112,11 +130,28 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     const int r16 = lane & 15, g = lane >> 4;
 
     int tile_m, tile_n;
-    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
+    int k0 = 0, k_len = K;  // the K range this workgroup reduces over
+    uint8_t *c = c_all;
+    if constexpr (KGROUPED) {
+        const int per_expert = tiles_m * tiles_n;
+        const int e = (int)blockIdx.x / per_expert;
+        int prev = 0, end = 0;
+        for (int i = 0; i <= e; ++i) {
+            prev = end;
+            end = min(max(groups.ends[i], prev), K);
+        }
+        k0 = prev / BK * BK;
+        k_len = max(end / BK * BK - k0, 0);
+        c += (int64_t)e * M * ldc_bytes;
+        tile_of_block((int)blockIdx.x - e * per_expert, per_expert, tiles_m, tiles_n, tile_m, tile_n);
+    } else {
+        tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
+    }
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     // K is the length of an operand row in BYTES (= elements for MXFP8, 2 x elements for BF16 operands)
     const int nkb = K / kBlock;  // scale bytes per row
-    const int KT = K / BK;
+    const int KT = k_len / BK;   // steps of this workgroup
+    const int KT_row = K / BK;   // steps in a whole operand row (the pitch of the tiled scale layout)
 
     // ---- global -> LDS addressing: wavefront w owns 8-row groups w*LOADS.. of each tile; one
     // instruction fills 8 consecutive rows, lane l lands at row l/8, physical chunk l%8, and
@@ -142,8 +177,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 #pragma unroll
     for (int i = 0; i < Cfg::SB_LOADS; ++i)
         bs_goff[i] = (uint32_t)min(((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 64 + lane, N - 1 - n0) * (uint32_t)nkb;
-    const uint8_t *a_tile = a_q + (int64_t)m0 * K, *b_tile = b_q + (int64_t)n0 * K;
-    const uint8_t *as_tile = a_s + (int64_t)m0 * nkb, *bs_tile = b_s + (int64_t)n0 * nkb;
+    const uint8_t *a_tile = a_q + (int64_t)m0 * K + k0, *b_tile = b_q + (int64_t)n0 * K + k0;
+    const uint8_t *as_tile = a_s + (int64_t)m0 * nkb + k0 / kBlock, *bs_tile = b_s + (int64_t)n0 * nkb + k0 / kBlock;
     // Tiled scales: the 64 dwords of a (64-row group, K step) are contiguous, so the instruction that
     // reads one cache line per lane from row-major scales reads 256 consecutive bytes here. A ragged
     // last tile re-reads the last valid group: its rows are never stored.
@@ -151,10 +186,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     if constexpr (TILED) {
 #pragma unroll
         for (int i = 0; i < Cfg::SA_LOADS; ++i)
-            as_grp[i] = a_s + (int64_t)min(m0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BM / 64), (M + 63) / 64 - 1) * KT * 256;
+            as_grp[i] = a_s + ((int64_t)min(m0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BM / 64), (M + 63) / 64 - 1) * KT_row + k0 / BK) * 256;
 #pragma unroll
         for (int i = 0; i < Cfg::SB_LOADS; ++i)
-            bs_grp[i] = b_s + (int64_t)min(n0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BN / 64), (N + 63) / 64 - 1) * KT * 256;
+            bs_grp[i] = b_s + ((int64_t)min(n0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BN / 64), (N + 63) / 64 - 1) * KT_row + k0 / BK) * 256;
     }
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
 
@@ -375,13 +410,22 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 #ifndef MXFP8_GEMM_SCHED
 #define MXFP8_GEMM_SCHED 242  // B requests behind every 2nd MFMA, a gap of 2, A requests behind every 4th
 #endif
-template <class Cfg, bool OUT_BF16, bool TILED, bool SPREAD, int FUSE_Q = 0, int SCHED = MXFP8_GEMM_SCHED>
+// GROUPED (Appendix A.4, mixture-of-experts layers): the rows of A are tokens sorted by expert, rows
+// [group_ends[e-1], group_ends[e]) belong to expert e, whose B operand starts b_group_bytes (scales:
+// bs_group_bytes) after the previous expert's. group_ends lives in DEVICE memory (routing happens on the
+// GPU), so the host cannot count the tiles: every workgroup sums them up itself, walks over its share and
+// finds the expert of a tile by scanning the ends (wavefront-uniform scalar code, a few hundred cycles per
+// 100 k-cycle tile). An expert's last tile may be partial: its surplus rows are computed from whatever
+// rows follow (the next expert's, or re-reads of the last row of A) and not stored. N stays a multiple of
+// the tile. Ends are clamped to [previous end, M], so bad ends cannot send a load out of A.
+template <class Cfg, bool OUT_BF16, bool TILED, bool SPREAD, int FUSE_Q = 0, int SCHED = MXFP8_GEMM_SCHED, bool GROUPED = false>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_s, const uint8_t *__restrict__ b_q,
     const uint8_t *__restrict__ b_s, int M, int N, int K, uint8_t *__restrict__ c, int64_t ldc_bytes,
     int tiles_m, int tiles_n, uint8_t *__restrict__ cq, uint8_t *__restrict__ cs, uint8_t *__restrict__ cqT,
-    uint8_t *__restrict__ csT)
+    uint8_t *__restrict__ csT, GemmGroups groups)
 {
+    static_assert(!GROUPED || (FUSE_Q == 0 && Cfg::SCALED), "grouped products: MXFP8 operands, plain epilogue");
     static_assert(!FUSE_Q || (OUT_BF16 && (Cfg::TN == 8 || Cfg::TN == 4) && Cfg::TM == Cfg::TN), "fused output quantization");
     constexpr bool Q_ROW = (FUSE_Q & 1) != 0, Q_COL = (FUSE_Q & 2) != 0;
     static_assert(!Q_COL || Cfg::BM * Cfg::BN <= 2 * Cfg::B_BYTES, "transposed tile fits the two idle buffers");
@@ -396,9 +440,20 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const int r16 = lane & 15, g = lane >> 4;
     const int nkb = K / kBlock;
     const int KT = K / BK;
-    const int ntiles = tiles_m * tiles_n;
+    int ntiles = tiles_m * tiles_n;
+    if constexpr (GROUPED) {
+        ntiles = 0;
+        for (int e = 0, prev = 0; e < groups.count; ++e) {
+            const int end = min(max(groups.ends[e], prev), M);
+            ntiles += (end - prev + Cfg::BM - 1) / Cfg::BM * tiles_n;
+            prev = end;
+        }
+    }
     const int stride = gridDim.x;
-    const int my_tiles = (ntiles - (int)blockIdx.x + stride - 1) / stride;  // >= 1: the grid has at most ntiles workgroups
+    // >= 1 when the host knows the number of tiles (the grid has at most that many workgroups)
+    const int my_tiles = (ntiles - (int)blockIdx.x + stride - 1) / stride;
+    if (GROUPED && my_tiles <= 0)
+        return;  // the whole workgroup, before any barrier
 
     // ---- DMA offsets inside an operand tile (see the kernel above). Without ragged rows they do not
     // depend on the tile, and with square tiles the A and the B tile use the same ones.
@@ -419,31 +474,68 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     struct Tile {
         const uint8_t *a, *b, *as, *bs;
         int m0, n0;
+        int rows;  // GROUPED: rows of the tile that belong to its expert (stored)
+        int lim;   // GROUPED: last row of the tile, counted from m0, that may be read from A
     };
     auto tile_at = [&](int index) __attribute__((always_inline)) {
         int tm, tn;
-        tile_of_block((int)blockIdx.x + index * stride, ntiles, tiles_m, tiles_n, tm, tn);
         Tile t;
-        t.m0 = tm * Cfg::BM;
+        const uint8_t *bq = b_q, *bsc = b_s;
+        if constexpr (GROUPED) {
+            // The workgroups that run side by side have consecutive ids: they work on the same expert (all
+            // XCDs then stream the same B operand), and inside the expert's tiles the XCD-aware order applies.
+            int u = (int)blockIdx.x + index * stride;
+            int e = 0, prev = 0, end = 0, tiles_e = 0;
+            for (; e < groups.count; ++e) {  // u < ntiles = the sum of the groups' tiles: the scan ends inside
+                end = min(max(groups.ends[e], prev), M);
+                tiles_e = (end - prev + Cfg::BM - 1) / Cfg::BM * tiles_n;
+                if (u < tiles_e)
+                    break;
+                u -= tiles_e;
+                prev = end;
+            }
+            panel_tile(xcd_logical_id(u, tiles_e), tiles_e / tiles_n, tiles_n, tm, tn);
+            t.m0 = prev + tm * Cfg::BM;
+            t.rows = min(Cfg::BM, end - t.m0);
+            t.lim = M - 1 - t.m0;
+            bq += e * groups.b_group_bytes;
+            bsc += e * groups.bs_group_bytes;
+        } else {
+            tile_of_block((int)blockIdx.x + index * stride, ntiles, tiles_m, tiles_n, tm, tn);
+            t.m0 = tm * Cfg::BM;
+            t.rows = Cfg::BM;
+            t.lim = Cfg::BM;
+        }
         t.n0 = tn * Cfg::BN;
         t.a = a_q + (int64_t)t.m0 * K;
-        t.b = b_q + (int64_t)t.n0 * K;
+        t.b = bq + (int64_t)t.n0 * K;
         if constexpr (TILED) {
-            t.as = a_s + (int64_t)(t.m0 / 64 + grp) * KT * 256;
-            t.bs = b_s + (int64_t)(t.n0 / 64 + grp) * KT * 256;
+            // (grouped: group starts are multiples of 64 rows; 64-row groups past the end of A re-read the last one)
+            const int ag = GROUPED ? min(t.m0 / 64 + grp, (M + 63) / 64 - 1) : t.m0 / 64 + grp;
+            t.as = a_s + (int64_t)ag * KT * 256;
+            t.bs = bsc + (int64_t)(t.n0 / 64 + grp) * KT * 256;
         } else {
             t.as = a_s + (int64_t)t.m0 * nkb;
-            t.bs = b_s + (int64_t)t.n0 * nkb;
+            t.bs = bsc + (int64_t)t.n0 * nkb;
         }
         return t;
     };
 
-    // DMA slot t of the A / B requests of one K step, from the step's source pointers into buffer buf
-    auto issue_a = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
-        if (t < Cfg::A_LOADS)
-            dma_load<16>(src, goff[t], lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
-        else if (t < Cfg::NA)
-            dma_load<4>(ssrc, sgoff, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + grp * 256);
+    // DMA slot t of the A / B requests of one K step, from the step's source pointers into buffer buf.
+    // GROUPED: rows of the A tile past `lim` (the end of A) re-read row lim.
+    const int row0 = wave * Cfg::A_LOADS * 8 + ld_r;  // this lane's row in DMA slot 0
+    auto issue_a = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf, int lim) __attribute__((always_inline)) {
+        if (t < Cfg::A_LOADS) {
+            uint32_t off = goff[t];
+            if constexpr (GROUPED)
+                off -= (uint32_t)max(row0 + 8 * t - lim, 0) * (uint32_t)K;
+            dma_load<16>(src, off, lds_base + Cfg::A_OFF + buf * Cfg::A_BYTES + (wave * Cfg::A_LOADS + t) * 1024);
+        } else if (t < Cfg::NA) {
+            uint32_t off = sgoff;
+            if constexpr (GROUPED && !TILED)
+                off -= (uint32_t)max(grp * 64 + lane - lim, 0) * (uint32_t)nkb;
+            dma_load<4>(ssrc, off, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + grp * 256);
+        }
     };
     auto issue_b = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::B_LOADS)
@@ -477,7 +569,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     constexpr int A_LO = (TN - 2) * (TM - TM / 2) >= Cfg::NA ? TM / 2 : 0;
     static_assert((TN - 2) * (TM - A_LO) >= Cfg::NA, "A requests fit into columns 1..TN-2");
     auto step = [&](int cur, const uint8_t *b_src, const uint8_t *bs_src, const uint8_t *a_src,
-                    const uint8_t *as_src) __attribute__((always_inline)) {
+                    const uint8_t *as_src, int a_lim) __attribute__((always_inline)) {
         const int nxt = cur ^ 1;
         const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
         const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::BM * 4;
@@ -515,14 +607,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                     if (m % B_EVERY == 0 && m / B_EVERY < Cfg::NB)
                         issue_b(m / B_EVERY, b_src, bs_src, nxt);
                     else if (m >= A_FIRST && (m - A_FIRST) % A_EVERY == 0 && (m - A_FIRST) / A_EVERY < Cfg::NA)
-                        issue_a((m - A_FIRST) / A_EVERY, a_src, as_src, cur);
+                        issue_a((m - A_FIRST) / A_EVERY, a_src, as_src, cur, a_lim);
                 } else if (j == 0) {
                     issue_b(i, b_src, bs_src, nxt);
                     if (i + TM < Cfg::NB)
                         issue_b(i + TM, b_src, bs_src, nxt);
                 } else if (j < TN - 1 && i >= A_LO) {
                     if (a_slot < Cfg::NA)
-                        issue_a(a_slot, a_src, as_src, cur);
+                        issue_a(a_slot, a_src, as_src, cur, a_lim);
                     ++a_slot;
                 }
                 if (j == TN - 1) {
@@ -542,13 +634,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     // prologue of the workgroup's first tile: A(0), B(0) into buffers 0, A(1) into A buffer 1
 #pragma unroll
     for (int t = 0; t < Cfg::NA; ++t)
-        issue_a(t, cur_tile.a, cur_tile.as, 0);
+        issue_a(t, cur_tile.a, cur_tile.as, 0, cur_tile.lim);
 #pragma unroll
     for (int t = 0; t < Cfg::NB; ++t)
         issue_b(t, cur_tile.b, cur_tile.bs, 0);
 #pragma unroll
     for (int t = 0; t < Cfg::NA; ++t)
-        issue_a(t, cur_tile.a + BK, cur_tile.as + s_step, 1);
+        issue_a(t, cur_tile.a + BK, cur_tile.as + s_step, 1, cur_tile.lim);
     MXFP8_WAIT_VMCNT(0);
     __syncthreads();
 #pragma unroll
@@ -566,6 +658,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             // source of the step after this one (B) and of the one after that (A): this tile, else the
             // first steps of the next tile, else (last tile) this tile's last step once more
             const uint8_t *b_src, *bs_src, *a_src, *as_src;
+            int a_lim = cur_tile.lim;
             if (kt + 1 < KT) {
                 b_src = cur_tile.b + (int64_t)(kt + 1) * BK;
                 bs_src = cur_tile.bs + (int64_t)(kt + 1) * s_step;
@@ -582,11 +675,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             } else if (has_next) {
                 a_src = next_tile.a + (int64_t)(kt + 2 - KT) * BK;
                 as_src = next_tile.as + (int64_t)(kt + 2 - KT) * s_step;
+                a_lim = next_tile.lim;
             } else {
                 a_src = cur_tile.a + (int64_t)(KT - 1) * BK;
                 as_src = cur_tile.as + (int64_t)(KT - 1) * s_step;
             }
-            step(par, b_src, bs_src, a_src, as_src);
+            step(par, b_src, bs_src, a_src, as_src, a_lim);
             par ^= 1;
         }
         // ---- epilogue of this tile; the A requests of the next tile's second step are in flight.
@@ -715,8 +809,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                     for (int t = 0; t < RPP * ROWB / 1024; ++t) {
                         const int lin = t * 1024 + lane * 16, row = lin / ROWB, colb = lin % ROWB;
                         const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * PITCH + colb);
-                        *reinterpret_cast<uint4 *>(crow + (int64_t)(wm * Cfg::WM + pass * RPP + row) * ldc_bytes +
-                                                   wn * ROWB + colb) = v;
+                        if (!GROUPED || wm * Cfg::WM + i * 16 + pass * RPP + row < cur_tile.rows)
+                            *reinterpret_cast<uint4 *>(crow + (int64_t)(wm * Cfg::WM + pass * RPP + row) * ldc_bytes +
+                                                       wn * ROWB + colb) = v;
                     }
                     __builtin_amdgcn_wave_barrier();  // (the next pass overwrites the area after these reads)
                 }
@@ -863,7 +958,7 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES_PERSISTENT, stream, a_q, a_s, b_q, b_s, M, N, K,
                            static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, static_cast<uint8_t *>(nullptr),
                            static_cast<uint8_t *>(nullptr), static_cast<uint8_t *>(nullptr),
-                           static_cast<uint8_t *>(nullptr));
+                           static_cast<uint8_t *>(nullptr), GemmGroups{nullptr, 0, 0, 0});
         return hipGetLastError();
     }
     auto kern = gemm_kernel<Cfg, OUT_BF16, TILED>;
@@ -872,7 +967,8 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
     if (e != hipSuccess)
         return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream,
-                       a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, vec_store);
+                       a_q, a_s, b_q, b_s, M, N, K, static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, vec_store,
+                       GemmGroups{nullptr, 0, 0, 0});
     return hipGetLastError();
 }
 
@@ -901,6 +997,93 @@ hipError_t launch_gemm(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_
                                stream);
     return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, max_workgroups,
                              stream);
+}
+
+// Grouped product over expert-sorted rows of A (see GemmGroups). Always the persistent kernel: N a multiple of
+// the tile (256 when the problem is large and N allows it, else 128), K >= 2 steps, C vector-storable; returns
+// hipErrorInvalidConfiguration (nothing launched) otherwise. The host does not know the number of tiles: the
+// grid is one workgroup per compute unit (or max_workgroups), capped by the largest number there can be.
+template <class Cfg, bool OUT_BF16, bool TILED>
+static hipError_t launch_grouped_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                                     const GemmGroups &groups, int M, int N, int K, void *c, int64_t ldc,
+                                     int max_workgroups, hipStream_t stream)
+{
+    const int64_t ldc_bytes = ldc * (OUT_BF16 ? 2 : 4);
+    const bool vec_store = (reinterpret_cast<uintptr_t>(c) % 16 == 0) && (ldc_bytes % 16 == 0);
+    if (N % Cfg::BN || K < 2 * BK || !vec_store || ldc_bytes * Cfg::BM >= (int64_t(1) << 31))
+        return hipErrorInvalidConfiguration;
+    const int tiles_n = N / Cfg::BN;
+    const int64_t most_tiles = ((int64_t)(M + Cfg::BM - 1) / Cfg::BM + groups.count) * tiles_n;
+    int grid = 0;
+    hipError_t e = persistent_grid((int)(most_tiles < 0x7FFFFFFF ? most_tiles : 0x7FFFFFFF), max_workgroups, grid);
+    if (e != hipSuccess)
+        return e;
+    auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED, spread_fits<Cfg>(), 0, MXFP8_GEMM_SCHED, true>;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            Cfg::LDS_BYTES_PERSISTENT);
+    if (e != hipSuccess)
+        return e;
+    uint8_t *none = nullptr;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES_PERSISTENT, stream, a_q, a_s, b_q, b_s, M, N, K,
+                       static_cast<uint8_t *>(c), ldc_bytes, 0, tiles_n, none, none, none, none, groups);
+    return hipGetLastError();
+}
+
+// Weight-gradient form of the grouped product (see gemm_kernel, KGROUPED): one workgroup per (expert, tile).
+template <class Cfg, bool OUT_BF16, bool TILED>
+static hipError_t launch_kgrouped_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                                      const GemmGroups &groups, int M, int N, int K, void *c, int64_t ldc, hipStream_t stream)
+{
+    const int tiles_m = (M + Cfg::BM - 1) / Cfg::BM, tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
+    const int64_t ldc_bytes = ldc * (OUT_BF16 ? 2 : 4);
+    const bool vec_store = (reinterpret_cast<uintptr_t>(c) % 16 == 0) && (ldc_bytes % 16 == 0) && ((int64_t)M * ldc_bytes) % 16 == 0;
+    const int64_t grid = (int64_t)groups.count * tiles_m * tiles_n;
+    if (grid > 0x7FFFFFFF)
+        return hipErrorInvalidConfiguration;
+    auto kern = gemm_kernel<Cfg, OUT_BF16, TILED, true>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    if (e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, stream, a_q, a_s, b_q, b_s, M, N, K,
+                       static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, vec_store, groups);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_kgrouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                                const int32_t *group_ends, int groups, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
+                                bool tiled_scales, int64_t ldc, hipStream_t stream)
+{
+    using Big = GemmCfg<256, 256, 2, 2>;
+    using Small = GemmCfg<128, 128, 2, 2>;
+    const GemmGroups g{group_ends, groups, 0, 0};
+    const bool big = ((M + 255) / 256) * ((N + 255) / 256) * groups >= 128;
+    const int m = (int)M, n = (int)N, k = (int)K;
+#define MXFP8_KGROUPED(CFG)                                                                                        \
+    (c_bf16 ? (tiled_scales ? launch_kgrouped_cfg<CFG, true, true>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, stream)   \
+                            : launch_kgrouped_cfg<CFG, true, false>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, stream)) \
+            : (tiled_scales ? launch_kgrouped_cfg<CFG, false, true>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, stream)  \
+                            : launch_kgrouped_cfg<CFG, false, false>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, stream)))
+    return big ? MXFP8_KGROUPED(Big) : MXFP8_KGROUPED(Small);
+#undef MXFP8_KGROUPED
+}
+
+hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
+                               const int32_t *group_ends, int groups, int64_t b_group_bytes, int64_t bs_group_bytes,
+                               int64_t M, int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                               int max_workgroups, hipStream_t stream)
+{
+    using Big = GemmCfg<256, 256, 2, 2>;
+    using Small = GemmCfg<128, 128, 2, 2>;
+    const GemmGroups g{group_ends, groups, b_group_bytes, bs_group_bytes};
+    const bool big = N % 256 == 0 && ((M + 255) / 256) * (N / 256) >= 128;
+    const int m = (int)M, n = (int)N, k = (int)K;
+#define MXFP8_GROUPED(CFG)                                                                                                     \
+    (c_bf16 ? (tiled_scales ? launch_grouped_cfg<CFG, true, true>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, max_workgroups, stream)   \
+                            : launch_grouped_cfg<CFG, true, false>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, max_workgroups, stream)) \
+            : (tiled_scales ? launch_grouped_cfg<CFG, false, true>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, max_workgroups, stream)  \
+                            : launch_grouped_cfg<CFG, false, false>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, max_workgroups, stream)))
+    return big ? MXFP8_GROUPED(Big) : MXFP8_GROUPED(Small);
+#undef MXFP8_GROUPED
 }
 
 // Product of two BF16 operands, [M x K] and [N x K], both K-contiguous, FP32 accumulation: the GEMM of the
@@ -943,7 +1126,7 @@ static hipError_t launch_fused_cfg(const uint8_t *a_q, const uint8_t *a_s, const
     if (e != hipSuccess)
         return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES_PERSISTENT, stream, a_q, a_s, b_q, b_s, M, N, K,
-                       static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, cq, cs, cqT, csT);
+                       static_cast<uint8_t *>(c), ldc_bytes, tiles_m, tiles_n, cq, cs, cqT, csT, GemmGroups{nullptr, 0, 0, 0});
     return hipGetLastError();
 }
 

@@ -7,6 +7,10 @@
 //   gemm       <pass 0|1|2> <M> <N> <K> <f32|bf16> <ldc> <a_q> <a_s> <b_q> <b_s> <c.bin> [tiled]
 //   dequantize <rows> <cols> <f32|bf16> <ld> <q.bin> <s.bin> <out.bin> [tiled]
 //   gemmbf16   <M> <N> <K> <f32|bf16> <ldc> <a.bin> <b.bin> <c.bin>      (BF16 operands, no scales)
+//   gemmgrp    <M> <N> <K> <f32|bf16> <ldc> <groups> <a_q> <a_s> <b_q> <b_s> <ends.bin (int32)> <c.bin> [tiled]
+//              (b_q = groups x N x K bytes, b_s = groups scale operands; rows outside every group keep 0xA5)
+//   gemmgrpk   <M> <N> <K> <f32|bf16> <ldc> <groups> <a_q> <a_s> <b_q> <b_s> <ends.bin (int32)> <c.bin> [tiled]
+//              (weight-gradient form: the ends split K; c = groups x M x ldc elements)
 //   gemmq      <pass 0|1|2> <M> <N> <K> <ldc> <axis 1|2|3> <a_q> <a_s> <b_q> <b_s> <out-prefix> [tiled]
 //              (BF16 product <prefix>.c plus the MXFP8 copies of it: .q_row .s_row .q_colT .s_colT)
 // "tiled" selects MXFP8_SCALES_TILED for every scale buffer of the call (sizes from mxfp8_scale_bytes);
@@ -196,6 +200,44 @@ int main(int argc, char **argv)
             unchanged(sa, "a_s");
             unchanged(b, "b_q");
             unchanged(sb, "b_s");
+            report(st);
+            save(cout, c);
+        } else if (op == "gemmgrp") {
+            long M, N, K, ldc, groups;
+            std::string dt, aq, as, bq, bs, ends, cout;
+            ls >> M >> N >> K >> dt >> ldc >> groups >> aq >> as >> bq >> bs >> ends >> cout;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)mxfp8_scale_bytes(M, K, lay));
+            Buf b = load(bq, (size_t)groups * N * K), sb = load(bs, (size_t)groups * mxfp8_scale_bytes(N, K, lay));
+            Buf e = load(ends, (size_t)groups * 4);
+            Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * es : 0);
+            const int st = mxfp8_gemm_grouped_ex(MXFP8_FPROP, a.p, sa.p, b.p, sb.p, (const int32_t *)e.p, (int32_t)groups, M, N, K,
+                                                 c.p, dtype_of(dt), ldc, lay, g_max_workgroups, nullptr);
+            unchanged(a, "a_q");
+            unchanged(sa, "a_s");
+            unchanged(b, "b_q");
+            unchanged(sb, "b_s");
+            unchanged(e, "group_ends");
+            report(st);
+            save(cout, c);
+        } else if (op == "gemmgrpk") {
+            long M, N, K, ldc, groups;
+            std::string dt, aq, as, bq, bs, ends, cout;
+            ls >> M >> N >> K >> dt >> ldc >> groups >> aq >> as >> bq >> bs >> ends >> cout;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)mxfp8_scale_bytes(M, K, lay));
+            Buf b = load(bq, (size_t)N * K), sb = load(bs, (size_t)mxfp8_scale_bytes(N, K, lay));
+            Buf e = load(ends, (size_t)groups * 4);
+            Buf c = output(M > 0 && groups > 0 ? (((size_t)groups * M - 1) * ldc + N) * es : 0);
+            const int st = mxfp8_gemm_grouped_ex(MXFP8_WGRAD, a.p, sa.p, b.p, sb.p, (const int32_t *)e.p, (int32_t)groups, M, N, K,
+                                                 c.p, dtype_of(dt), ldc, lay, 0, nullptr);
+            unchanged(a, "a_q");
+            unchanged(sa, "a_s");
+            unchanged(b, "b_q");
+            unchanged(sb, "b_s");
+            unchanged(e, "group_ends");
             report(st);
             save(cout, c);
         } else if (op == "gemmbf16") {

@@ -32,7 +32,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == ["mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex", "mxfp8_gemm",
-                                    "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
+                                    "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
                                     "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
 
@@ -154,6 +154,29 @@ def test_gemm_validation_needs_no_gpu(lib):
     assert f(0, P(0x1008), FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, None) == 3
     assert f(0, *ok, 64, 64, 128, P(0x1002), 0, 64, None) == 3                   # FP32 c needs 4-byte alignment
     assert f(0, *ok, 0, 64, 128, None, 0, 64, None) == 0
+
+
+def test_grouped_gemm_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_gemm_grouped_ex
+    f.argtypes = [ctypes.c_int, P, P, P, P, P, ctypes.c_int32, I64, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, ctypes.c_int32, P]
+    ok = (FAKE, FAKE, FAKE, FAKE, FAKE)
+    assert f(0, *ok, 4, 512, 256, 256, FAKE, 2, 256, 0, 0, None) == 4             # output type
+    assert f(2, *ok, 4, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 5             # the weight gradient is not a grouped-rows product
+    assert f(0, *ok, 4, 512, 256, 256, FAKE, 0, 256, 2, 0, None) == 5             # scale layout
+    assert f(0, *ok, 4, 512, 256, 256, FAKE, 0, 256, 0, -1, None) == 5
+    assert f(0, *ok, 4, 512, 192, 256, FAKE, 0, 192, 0, 0, None) == 2             # N % 128
+    assert f(0, *ok, 4, 512, 256, 128, FAKE, 0, 256, 0, 0, None) == 2             # K < 256
+    assert f(0, *ok, 4, 512, 256, 320, FAKE, 0, 256, 0, 0, None) == 2             # K % 128
+    assert f(0, *ok, 4097, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 2          # too many groups
+    assert f(0, *ok, -1, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 2
+    assert f(0, *ok, 4, 512, 256, 256, FAKE, 0, 255, 0, 0, None) == 2             # ldc < N
+    assert f(0, FAKE, FAKE, FAKE, FAKE, None, 4, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 1
+    assert f(0, *ok, 4, 512, 256, 256, None, 0, 256, 0, 0, None) == 1
+    assert f(0, *ok, 4, 512, 256, 256, P(0x1008), 0, 256, 0, 0, None) == 3        # c must take 128-bit stores
+    assert f(0, *ok, 4, 512, 256, 256, FAKE, 1, 260, 0, 0, None) == 3             # BF16 rows of 520 bytes
+    assert f(0, FAKE, FAKE, FAKE, FAKE, P(0x1002), 4, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 3
+    assert f(0, *ok, 0, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 0             # no groups: nothing to do
+    assert f(0, *ok, 4, 0, 256, 256, None, 0, 256, 0, 0, None) == 0
 
 
 def test_bf16_gemm_validation_needs_no_gpu(lib):

@@ -61,3 +61,9 @@ def test_simulated_path_gpu_tests_pass_on_the_host_model(hostmodel_lib):
     n = replay(hostmodel_lib, ["test_gpu_simulated.py"],
                "not full_size and not (matches_oracle and (shape3 or shape4 or shape5)) and not (small_integers and shape7)")
     assert n >= 18
+
+
+def test_grouped_gpu_tests_pass_on_the_host_model(hostmodel_lib):
+    """The grouped (mixture-of-experts) product; the 4096-token and full-size cases are left to the GPU."""
+    n = replay(hostmodel_lib, ["test_gpu_grouped.py"], "not full_size and not equals_the_plain_product")
+    assert n >= 6
