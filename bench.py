@@ -21,7 +21,8 @@ stream inside the timed region. `roofline_quantize` (X, BF16, both axes) and `ro
 512 MB of distinct sources and destinations, so that the 256 MB memory-side cache cannot serve them.
 Two measured ceilings of the box stand beside the published peaks: `peak_sustained` in the GEMM rooflines is
 the rate a register-only loop of the matrix instruction sustains in this very run (mxfp8_mfma_rate_probe),
-`plain_copy_gbs` in the quantize rooflines is a plain device copy of the same tensor under the same rotation.
+`plain_copy_gbs` in the quantize rooflines is the library's plain copy kernel (mxfp8_copy_rate_probe, one workgroup
+per compute unit) on the same tensor under the same rotation, `torch_copy_gbs` torch's copy_ of it.
 `fused_output_quantization` times the forward product with the MXFP8 copies of Y emitted from its epilogue
 against the product followed by a stand-alone quantize of Y; `simulated_path` times the BF16 product of the
 round-tripped operands (Section 3.1) against the BF16 matrix peak; `grouped_moe` times the grouped forward
@@ -337,19 +338,26 @@ def main():
 
     def rotating_copy_gbs(src, sets, launches):
         """A plain device-to-device copy of the same source with the same rotation: what the memory system of
-        this box gives the simplest possible stream (read + write bytes per second)."""
+        this box gives the simplest possible stream (read + write bytes per second). Two copies: the library's own
+        copy kernel in the configuration that measured fastest (one workgroup per compute unit, grid-stride,
+        128-bit streaming loads and stores), and torch's copy_."""
         srcs = [src] + [src.clone() for _ in range(sets - 1)]
         dsts = [torch.empty_like(t) for t in srcs]
-        for i in range(sets):
-            dsts[i].copy_(srcs[i])
-        a, b = ev(), ev()
-        torch.cuda.synchronize()
-        a.record()
-        for i in range(launches):
-            dsts[i % sets].copy_(srcs[i % sets])
-        b.record()
-        torch.cuda.synchronize()
-        return 2.0 * src.numel() * src.element_size() / (a.elapsed_time(b) / launches * 1e-3) / 1e9
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        res = []
+        for fn in (lambda i: mx.mxfp8_copy_rate_probe(srcs[i % sets], dsts[i % sets], cus, 0),
+                   lambda i: dsts[i % sets].copy_(srcs[i % sets])):
+            for i in range(sets):
+                fn(i)
+            a, b = ev(), ev()
+            torch.cuda.synchronize()
+            a.record()
+            for i in range(launches):
+                fn(i)
+            b.record()
+            torch.cuda.synchronize()
+            res.append(2.0 * src.numel() * src.element_size() / (a.elapsed_time(b) / launches * 1e-3) / 1e9)
+        return res
 
     gemm_flop = 2.0 * T * H * O
     extras = {}
@@ -413,7 +421,7 @@ def main():
                         "traffic": traffic_from_profile(prof), "algorithmic_bytes": elems * bpe,
                         "kernel": f"quantize_kernel ({'BF16 X 8192x4096' if name == 'quant_bf16' else 'FP32 dY 8192x14336'}, both axes)",
                         "avg_ms": ms, "launches": launches, "rotating_footprint_mb": footprint / 1e6,
-                        "plain_copy_gbs": copy_gbs, "frac_of_plain_copy": gbs / copy_gbs}
+                        "plain_copy_gbs": copy_gbs[0], "frac_of_plain_copy": gbs / copy_gbs[0], "torch_copy_gbs": copy_gbs[1]}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
     for key in ("fused_output_quantization", "simulated_path", "grouped_moe"):

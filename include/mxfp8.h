@@ -268,6 +268,17 @@ mxfp8_status mxfp8_dequantize_mode_ex(const uint8_t *q, const uint8_t *s, int64_
  */
 mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float *sink, void *hip_stream);
 
+/*
+ * Second measurement aid (no operation of the paper): copies `bytes` bytes from src to dst (device memory, both
+ * 16-byte aligned, not overlapping, bytes a multiple of 16) with 128-bit streaming loads and stores on
+ * `workgroups` workgroups of 256 work-items. mode 0 / 1: grid-stride with 4 / 8 units in flight per work-item;
+ * mode 2: one contiguous slab per workgroup. Timing it gives the rate the memory system sustains for one read
+ * and one write stream issued the way the quantizer issues its own: 2 * bytes per call.
+ * workgroups in [1, 2^20], else MXFP8_ERR_SHAPE; an unknown mode is MXFP8_ERR_MODE; bytes == 0 does nothing.
+ */
+mxfp8_status mxfp8_copy_rate_probe(const void *src, void *dst, int64_t bytes, int32_t workgroups, int32_t mode,
+                                   void *hip_stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp8_status_string(mxfp8_status status);
 

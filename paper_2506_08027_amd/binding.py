@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_gemm_bf16.argtypes = [vp, vp, i64, i64, i64, vp, ci, i64, ctypes.c_int32, vp]
     lib.mxfp8_mfma_rate_probe.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.mxfp8_copy_rate_probe.restype = ci
+    lib.mxfp8_copy_rate_probe.argtypes = [vp, vp, i64, ctypes.c_int32, ctypes.c_int32, vp]
     lib.mxfp8_status_string.restype = ctypes.c_char_p
     lib.mxfp8_status_string.argtypes = [ci]
     _lib = lib
@@ -301,6 +303,19 @@ def mxfp8_mfma_rate_probe(workgroups: int, iterations: int, sink, stream=None) -
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_mfma_rate_probe")
     return workgroups * 4.0 * iterations * 64 * 65536
+
+
+def mxfp8_copy_rate_probe(src, dst, workgroups, mode=0, stream=None) -> int:
+    """Copies src to dst (dense GPU tensors of the same size in bytes) with the library's plain copy kernel;
+    returns the bytes moved (read + written)."""
+    _need_cuda(src, dst)
+    nbytes = src.numel() * src.element_size()
+    if not src.is_contiguous() or not dst.is_contiguous() or dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst must be dense and of the same size")
+    rc = load().mxfp8_copy_rate_probe(_ptr(src), _ptr(dst), nbytes, workgroups, mode, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_copy_rate_probe")
+    return 2 * nbytes
 
 
 def mxfp8_dequantize_mode_ex(q, s, element, dst, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:

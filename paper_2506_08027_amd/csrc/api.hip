@@ -27,6 +27,7 @@ hipError_t launch_gemm_kgrouped(const uint8_t *a_q, const uint8_t *a_s, const ui
 hipError_t launch_gemm_bf16(const uint8_t *a, const uint8_t *b, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
                             int64_t ldc, int max_workgroups, hipStream_t stream);
 hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream);
+hipError_t launch_copy_rate(const void *src, void *dst, int64_t bytes, int workgroups, int mode, hipStream_t stream);
 }  // namespace mxfp8
 
 namespace {
@@ -270,6 +271,22 @@ mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float
     if (reinterpret_cast<uintptr_t>(sink) % 4)
         return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_mfma_rate(workgroups, iterations, sink, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_copy_rate_probe(const void *src, void *dst, int64_t bytes, int32_t workgroups, int32_t mode, void *hip_stream)
+{
+    if (mode < 0 || mode > 2)
+        return MXFP8_ERR_MODE;
+    if (bytes < 0 || bytes % 16 || workgroups < 1 || workgroups > (1 << 20))
+        return MXFP8_ERR_SHAPE;
+    if (bytes == 0)
+        return MXFP8_OK;
+    if (!src || !dst)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(src) || !aligned16(dst))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_copy_rate(src, dst, bytes, workgroups, mode, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

@@ -41,6 +41,55 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iterations, float *_
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Second measurement aid: a plain copy, the simplest stream the memory system can be given, written the way
+// the quantizer moves its data (128-bit streaming loads and stores, several in flight per work-item). The
+// benchmark times it next to the quantizer on the same tensors: what it reaches is what HBM gives this chip's
+// compute units for one read and one write stream, and the quantizer is reported against it as well as against
+// the published bandwidth. `mode` picks how the 16-byte units are spread over the grid:
+//   0  grid-stride, 4 units in flight per work-item;   1  grid-stride, 8 in flight;
+//   2  each workgroup copies one contiguous slab, 4 in flight per work-item.
+template <int UNROLL, bool SLAB>
+__global__ __launch_bounds__(256) void copy_rate_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int64_t units)
+{
+    int64_t i, end, step;
+    if constexpr (SLAB) {
+        const int64_t per = (units + gridDim.x - 1) / gridDim.x;
+        i = per * blockIdx.x + threadIdx.x;
+        end = min(per * (blockIdx.x + 1), units);
+        step = 256;
+    } else {
+        i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        end = units;
+        step = (int64_t)gridDim.x * 256;
+    }
+    for (; i + (UNROLL - 1) * step < end; i += UNROLL * step) {
+        uint4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            v[u] = stream_load(src + i + u * step);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            stream_store(dst + i + u * step, v[u]);
+    }
+    for (; i < end; i += step)
+        stream_store(dst + i, stream_load(src + i));
+}
+
+hipError_t launch_copy_rate(const void *src, void *dst, int64_t bytes, int workgroups, int mode, hipStream_t stream)
+{
+    const uint4 *s = static_cast<const uint4 *>(src);
+    uint4 *d = static_cast<uint4 *>(dst);
+    const int64_t units = bytes / 16;
+    const dim3 grid((unsigned)workgroups), block(256);
+    if (mode == 0)
+        hipLaunchKernelGGL((copy_rate_kernel<4, false>), grid, block, 0, stream, s, d, units);
+    else if (mode == 1)
+        hipLaunchKernelGGL((copy_rate_kernel<8, false>), grid, block, 0, stream, s, d, units);
+    else
+        hipLaunchKernelGGL((copy_rate_kernel<4, true>), grid, block, 0, stream, s, d, units);
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream)
 {
     hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, iterations, sink);

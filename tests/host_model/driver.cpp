@@ -11,6 +11,7 @@
 //              (b_q = groups x N x K bytes, b_s = groups scale operands; rows outside every group keep 0xA5)
 //   gemmgrpk   <M> <N> <K> <f32|bf16> <ldc> <groups> <a_q> <a_s> <b_q> <b_s> <ends.bin (int32)> <c.bin> [tiled]
 //              (weight-gradient form: the ends split K; c = groups x M x ldc elements)
+//   copy       <bytes> <workgroups> <mode 0|1|2> <src.bin> <dst.bin>      (the plain-copy rate probe)
 //   gemmq      <pass 0|1|2> <M> <N> <K> <ldc> <axis 1|2|3> <a_q> <a_s> <b_q> <b_s> <out-prefix> [tiled]
 //              (BF16 product <prefix>.c plus the MXFP8 copies of it: .q_row .s_row .q_colT .s_colT)
 // "tiled" selects MXFP8_SCALES_TILED for every scale buffer of the call (sizes from mxfp8_scale_bytes);
@@ -240,6 +241,16 @@ int main(int argc, char **argv)
             unchanged(e, "group_ends");
             report(st);
             save(cout, c);
+        } else if (op == "copy") {
+            long bytes, wgs, mode;
+            std::string src, dst;
+            ls >> bytes >> wgs >> mode >> src >> dst;
+            Buf a = load(src, (size_t)bytes);
+            Buf d = output((size_t)bytes);
+            const int st = mxfp8_copy_rate_probe(a.p, d.p, bytes, (int32_t)wgs, (int32_t)mode, nullptr);
+            unchanged(a, "src");
+            report(st);
+            save(dst, d);
         } else if (op == "gemmbf16") {
             long M, N, K, ldc;
             std::string dt, af, bf, cout;

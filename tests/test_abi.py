@@ -31,7 +31,7 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex", "mxfp8_gemm",
+    assert declared_functions() == ["mxfp8_copy_rate_probe", "mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex", "mxfp8_gemm",
                                     "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
                                     "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
@@ -106,6 +106,10 @@ def test_mode_entry_points_and_rate_probe_validate(lib):
     d.argtypes = [P, P, I64, I64, ctypes.c_int, P, ctypes.c_int, I64, ctypes.c_int, P]
     assert d(FAKE, FAKE, 4, 64, 7, FAKE, 0, 64, 0, None) == 5
     assert d(FAKE, FAKE, 4, 48, 1, FAKE, 0, 48, 0, None) == 2
+    cp = lib.mxfp8_copy_rate_probe
+    cp.argtypes = [P, P, I64, ctypes.c_int32, ctypes.c_int32, P]
+    assert cp(FAKE, FAKE, 1024, 4, 3, None) == 5 and cp(FAKE, FAKE, 1000, 4, 0, None) == 2 and cp(FAKE, FAKE, 1024, 0, 0, None) == 2
+    assert cp(None, FAKE, 1024, 4, 0, None) == 1 and cp(P(0x1008), FAKE, 1024, 4, 0, None) == 3 and cp(None, None, 0, 4, 0, None) == 0
     r = lib.mxfp8_mfma_rate_probe
     r.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P]
     assert r(-1, 10, FAKE, None) == 2 and r(10, -1, FAKE, None) == 2 and r((1 << 20) + 1, 1, FAKE, None) == 2
@@ -161,7 +165,11 @@ def test_grouped_gemm_validation_needs_no_gpu(lib):
     f.argtypes = [ctypes.c_int, P, P, P, P, P, ctypes.c_int32, I64, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, ctypes.c_int32, P]
     ok = (FAKE, FAKE, FAKE, FAKE, FAKE)
     assert f(0, *ok, 4, 512, 256, 256, FAKE, 2, 256, 0, 0, None) == 4             # output type
-    assert f(2, *ok, 4, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 5             # the weight gradient is not a grouped-rows product
+    assert f(3, *ok, 4, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 5             # no such pass
+    assert f(2, *ok, 4, 512, 256, 320, FAKE, 0, 256, 0, 0, None) == 2             # weight-gradient form: K % 128
+    assert f(2, *ok, 4, 512, 256, 256, P(0x1002), 0, 256, 0, 0, None) == 3        # ... c aligned to its element
+    assert f(2, FAKE, FAKE, FAKE, FAKE, None, 4, 512, 256, 256, FAKE, 0, 256, 0, 0, None) == 1
+    assert f(2, *ok, 4, 1 << 30, 1 << 30, 256, FAKE, 0, 1 << 30, 0, 0, None) == 2 # more workgroups than a grid holds
     assert f(0, *ok, 4, 512, 256, 256, FAKE, 0, 256, 2, 0, None) == 5             # scale layout
     assert f(0, *ok, 4, 512, 256, 256, FAKE, 0, 256, 0, -1, None) == 5
     assert f(0, *ok, 4, 512, 192, 256, FAKE, 0, 192, 0, 0, None) == 2             # N % 128

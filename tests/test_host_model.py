@@ -79,7 +79,7 @@ def _compare_scales(path, want, tiled):
     assert (dwords[row_of >= rows] == SENTINEL).all(), "scale dwords of rows past the end were written"
 
 
-def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None, tiled=False):
+def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None, tiled=False, groups=None, **env):
     rows, cols = x.shape
     ld = ld or cols
     stored = np.zeros((rows, ld), x.dtype)
@@ -89,10 +89,10 @@ def _quantize_and_compare(hostmodel, tmp_path, x, bf16, axis, ld=None, tiled=Fal
     prefix = str(tmp_path / "out")
     _, calls = run_case(hostmodel, tmp_path,
                         [f"quantize {'bf16' if bf16 else 'f32'} {rows} {cols} {ld} {axis} {src} {prefix}"
-                         + (" tiled" if tiled else "")])
+                         + (" tiled" if tiled else "")], **env)
     assert calls[0][0] == 0
     tiles = ((rows + 127) // 128) * ((cols + 127) // 128)
-    assert calls[0][1] == list(range(tiles))
+    assert calls[0][1] == list(range(groups or tiles))
     xin = np.ascontiguousarray(x)          # the oracle takes FP32 values or BF16 bit patterns (uint16)
     if axis & 1:
         q, s = oracle.quantize_rowwise(xin)
@@ -142,6 +142,14 @@ def test_quantize_tiled_scales(hostmodel, tmp_path, bf16, shape):
 
 
 # ---- dequantize -----------------------------------------------------------------------------------
+@pytest.mark.parametrize("tiled", [False, True])
+def test_quantize_resident_grid_walks_over_several_tiles(hostmodel, tmp_path, tiled):
+    """The both-axes pass over a BF16 source runs on 4 workgroups per compute unit: on a one-unit device the 30
+    tiles (ragged in both directions) of a 736 x 608 source go to 4 workgroups, 7 or 8 tiles each."""
+    x = si.to_bf16_bits(np.random.default_rng(4).standard_normal((736, 608)).astype(np.float32) * 3)
+    _quantize_and_compare(hostmodel, tmp_path, x, True, 3, tiled=tiled, groups=4, WAVESIM_CUS=1)
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_dequantize_all_codes_and_padding_untouched(hostmodel, tmp_path, bf16):
     scales = np.array([0, 1, 100, 126, 127, 128, 200, 253, 254, 255], np.uint8)
@@ -436,3 +444,20 @@ def test_fused_output_quantization_large_tiles_sampled_workgroups(hostmodel, tmp
     """256x256 configuration, 128 tiles on 64 workgroups: the first and the last workgroup, two tiles each."""
     n = _fused_case(hostmodel, tmp_path, 2048, 4096, 384, axis, tiled, seed=320, wg=64, WAVESIM_BLOCKS=2)
     assert n == 4 * 256 * 256
+
+
+# ---- measurement aids ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_copy_rate_probe_copies_exactly_its_bytes(hostmodel, tmp_path, mode):
+    """Sizes that leave a tail for the unrolled loop, fewer units than work-items, and a single unit."""
+    rng = np.random.default_rng(mode)
+    lines, want = [], []
+    for i, (units, wgs) in enumerate([(3 * 256 * 4 * 3 + 777, 3), (100, 2), (1, 5)]):
+        data = rng.integers(0, 256, units * 16, dtype=np.uint8)
+        out = str(tmp_path / f"d{i}.bin")
+        lines.append(f"copy {units * 16} {wgs} {mode} {put(tmp_path, f's{i}.bin', data)} {out}")
+        want.append((out, data))
+    _, calls = run_case(hostmodel, tmp_path, lines)
+    assert [c[0] for c in calls] == [0, 0, 0]
+    for out, data in want:
+        assert np.array_equal(np.fromfile(out, np.uint8), data)
