@@ -272,7 +272,9 @@ mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float
  * Second measurement aid (no operation of the paper): copies `bytes` bytes from src to dst (device memory, both
  * 16-byte aligned, not overlapping, bytes a multiple of 16) with 128-bit streaming loads and stores on
  * `workgroups` workgroups of 256 work-items. mode 0 / 1: grid-stride with 4 / 8 units in flight per work-item;
- * mode 2: one contiguous slab per workgroup. Timing it gives the rate the memory system sustains for one read
+ * mode 2: one contiguous slab per workgroup; mode 3 / 4: as mode 0 but dst is written in runs of 128 / 256 bytes that
+ * lie far apart (consecutive runs go to 64 interleaved regions: dst ends up a permutation of src; bytes must be
+ * a multiple of 64 runs), the write pattern of a transposed tile. Timing it gives the rate the memory system sustains for one read
  * and one write stream issued the way the quantizer issues its own: 2 * bytes per call.
  * workgroups in [1, 2^20], else MXFP8_ERR_SHAPE; an unknown mode is MXFP8_ERR_MODE; bytes == 0 does nothing.
  */

@@ -276,9 +276,10 @@ mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float
 
 mxfp8_status mxfp8_copy_rate_probe(const void *src, void *dst, int64_t bytes, int32_t workgroups, int32_t mode, void *hip_stream)
 {
-    if (mode < 0 || mode > 2)
+    if (mode < 0 || mode > 4)
         return MXFP8_ERR_MODE;
-    if (bytes < 0 || bytes % 16 || workgroups < 1 || workgroups > (1 << 20))
+    if (bytes < 0 || bytes % 16 || workgroups < 1 || workgroups > (1 << 20) || (mode == 3 && bytes % (64 * 128)) ||
+        (mode == 4 && bytes % (64 * 256)))
         return MXFP8_ERR_SHAPE;
     if (bytes == 0)
         return MXFP8_OK;

@@ -48,7 +48,10 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iterations, float *_
 // the published bandwidth. `mode` picks how the 16-byte units are spread over the grid:
 //   0  grid-stride, 4 units in flight per work-item;   1  grid-stride, 8 in flight;
 //   2  each workgroup copies one contiguous slab, 4 in flight per work-item.
-template <int UNROLL, bool SLAB>
+//   3 / 4  as 0, but the destination is written in runs of 128 / 256 bytes that lie far apart (consecutive
+//          runs go to 64 interleaved regions), the way a transposed tile leaves a kernel: the same bytes end up
+//          permuted in dst. For comparing write patterns; bytes must be a multiple of 64 runs.
+template <int UNROLL, bool SLAB, int RUN_UNITS>
 __global__ __launch_bounds__(256) void copy_rate_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int64_t units)
 {
     int64_t i, end, step;
@@ -62,6 +65,14 @@ __global__ __launch_bounds__(256) void copy_rate_kernel(const uint4 *__restrict_
         end = units;
         step = (int64_t)gridDim.x * 256;
     }
+    auto where = [&](int64_t u) __attribute__((always_inline)) {
+        if constexpr (RUN_UNITS == 0) {
+            return u;
+        } else {
+            const int64_t run = u / RUN_UNITS, nruns = units / RUN_UNITS;  // nruns % 64 == 0 (checked by the caller)
+            return ((run % 64) * (nruns / 64) + run / 64) * RUN_UNITS + u % RUN_UNITS;
+        }
+    };
     for (; i + (UNROLL - 1) * step < end; i += UNROLL * step) {
         uint4 v[UNROLL];
 #pragma unroll
@@ -69,10 +80,10 @@ __global__ __launch_bounds__(256) void copy_rate_kernel(const uint4 *__restrict_
             v[u] = stream_load(src + i + u * step);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
-            stream_store(dst + i + u * step, v[u]);
+            stream_store(dst + where(i + u * step), v[u]);
     }
     for (; i < end; i += step)
-        stream_store(dst + i, stream_load(src + i));
+        stream_store(dst + where(i), stream_load(src + i));
 }
 
 hipError_t launch_copy_rate(const void *src, void *dst, int64_t bytes, int workgroups, int mode, hipStream_t stream)
@@ -82,11 +93,15 @@ hipError_t launch_copy_rate(const void *src, void *dst, int64_t bytes, int workg
     const int64_t units = bytes / 16;
     const dim3 grid((unsigned)workgroups), block(256);
     if (mode == 0)
-        hipLaunchKernelGGL((copy_rate_kernel<4, false>), grid, block, 0, stream, s, d, units);
+        hipLaunchKernelGGL((copy_rate_kernel<4, false, 0>), grid, block, 0, stream, s, d, units);
     else if (mode == 1)
-        hipLaunchKernelGGL((copy_rate_kernel<8, false>), grid, block, 0, stream, s, d, units);
+        hipLaunchKernelGGL((copy_rate_kernel<8, false, 0>), grid, block, 0, stream, s, d, units);
+    else if (mode == 2)
+        hipLaunchKernelGGL((copy_rate_kernel<4, true, 0>), grid, block, 0, stream, s, d, units);
+    else if (mode == 3)
+        hipLaunchKernelGGL((copy_rate_kernel<4, false, 8>), grid, block, 0, stream, s, d, units);
     else
-        hipLaunchKernelGGL((copy_rate_kernel<4, true>), grid, block, 0, stream, s, d, units);
+        hipLaunchKernelGGL((copy_rate_kernel<4, false, 16>), grid, block, 0, stream, s, d, units);
     return hipGetLastError();
 }
 

@@ -108,7 +108,7 @@ def test_mode_entry_points_and_rate_probe_validate(lib):
     assert d(FAKE, FAKE, 4, 48, 1, FAKE, 0, 48, 0, None) == 2
     cp = lib.mxfp8_copy_rate_probe
     cp.argtypes = [P, P, I64, ctypes.c_int32, ctypes.c_int32, P]
-    assert cp(FAKE, FAKE, 1024, 4, 3, None) == 5 and cp(FAKE, FAKE, 1000, 4, 0, None) == 2 and cp(FAKE, FAKE, 1024, 0, 0, None) == 2
+    assert cp(FAKE, FAKE, 1024, 4, 5, None) == 5 and cp(FAKE, FAKE, 1024, 4, 3, None) == 2 and cp(FAKE, FAKE, 1000, 4, 0, None) == 2 and cp(FAKE, FAKE, 1024, 0, 0, None) == 2
     assert cp(None, FAKE, 1024, 4, 0, None) == 1 and cp(P(0x1008), FAKE, 1024, 4, 0, None) == 3 and cp(None, None, 0, 4, 0, None) == 0
     r = lib.mxfp8_mfma_rate_probe
     r.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P]

@@ -461,3 +461,18 @@ def test_copy_rate_probe_copies_exactly_its_bytes(hostmodel, tmp_path, mode):
     assert [c[0] for c in calls] == [0, 0, 0]
     for out, data in want:
         assert np.array_equal(np.fromfile(out, np.uint8), data)
+
+
+@pytest.mark.parametrize("mode,run", [(3, 128), (4, 256)])
+def test_copy_rate_probe_scattered_runs_permute_the_bytes(hostmodel, tmp_path, mode, run):
+    rng = np.random.default_rng(mode)
+    nruns = 64 * 5
+    data = rng.integers(0, 256, nruns * run, dtype=np.uint8)
+    out = str(tmp_path / "d.bin")
+    _, calls = run_case(hostmodel, tmp_path, [f"copy {data.size} 3 {mode} {put(tmp_path, 's.bin', data)} {out}"])
+    assert calls[0][0] == 0
+    r = np.arange(nruns)
+    where = (r % 64) * (nruns // 64) + r // 64
+    want = np.empty_like(data).reshape(nruns, run)
+    want[where] = data.reshape(nruns, run)
+    assert np.array_equal(np.fromfile(out, np.uint8), want.ravel())
