@@ -195,6 +195,18 @@ def gemm(a_q, a_s, b_q, b_s):
     return gemm_rows(a_q, a_s, b_q, b_s, np.arange(np.asarray(a_q).shape[0]))
 
 
+# ---- single-copy storage (Section 5): the column copy derived from the row copy -----------------------------
+def requantize_colwise(q_row: np.ndarray, s_row: np.ndarray):
+    """Column copy of a tensor of which only the MXFP8 row copy (q_row [rows x cols], s_row) was kept: every
+    element is decoded exactly (Q_i * X, in double, then FP32 without rounding) and the decoded tensor is
+    quantized down its columns like any FP32 source. Returns (qT [cols x rows], sT [cols x rows/32])."""
+    v = dequantize(q_row, s_row, "f64")
+    v32 = v.astype(np.float32)
+    if not np.array_equal(v32.astype(np.float64)[np.isfinite(v)], v[np.isfinite(v)]):
+        raise ValueError("a decoded value is not an FP32 number")   # cannot happen: 4 significant bits, 2^-136 .. 2^135
+    return quantize_colwise(v32)
+
+
 # ---- grouped product (Appendix A.4: mixture-of-experts layers) ------------------------------------------
 def grouped_gemm(a_q, a_s, b_q, b_s, group_ends):
     """Expert-batched tokens: the rows of A are sorted by expert, rows [group_ends[e-1], group_ends[e]) belong to
