@@ -320,6 +320,15 @@ def main():
         res["wgrad_kernel"] = "gemm_kernel, reduction axis grouped (one workgroup per expert and tile, FP32 out)"
         return res
 
+    def single_copy():
+        """Section 5: the column copy of X derived from its row copy when the backward pass needs it, against
+        what it replaces (keeping q_colT of X from the forward pass costs its bytes; making it again from the
+        BF16 source costs that pass)."""
+        ms = ms_avg(lambda: mx.mxfp8_requantize_colwise_ex(Xq["q_row"], Xq["s_row"], Xq["q_colT"], Xq["s_colT"], lay))
+        ms_src = ms_avg(lambda: mx.mxfp8_quantize_ex(X, mx.COLWISE, q_colT=Xq["q_colT"], s_colT=Xq["s_colT"], scale_layout=lay))
+        return {"requantize_ms": ms, "requantize_gbs": T * H * 2 * (1 + 1 / 32) / (ms * 1e-3) / 1e9,
+                "colwise_quantize_from_bf16_ms": ms_src}
+
     def sustained_mfma_tflops():
         """What the matrix pipes of this GPU sustain on the scaled FP8 instruction alone (operands in registers,
         pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling a GEMM
@@ -368,7 +377,7 @@ def main():
         extras["quant_bf16"] = (q_ms, q_fp, 160, rotating_copy_gbs(X, 8, 160))
         extras["quant_f32"] = (f_ms, f_fp, 100, rotating_copy_gbs(dY, 2, 100))
         for key, fn in (("fused_output_quantization", fused_output_quantization), ("simulated_path", simulated_path),
-                        ("grouped_moe", grouped_moe), ("layer_set", layer_set)):
+                        ("grouped_moe", grouped_moe), ("single_copy", single_copy), ("layer_set", layer_set)):
             try:
                 extras[key] = fn()
             except Exception as exc:   # the headline measurement must survive a problem in an extra one
@@ -424,7 +433,7 @@ def main():
                         "plain_copy_gbs": copy_gbs[0], "frac_of_plain_copy": gbs / copy_gbs[0], "torch_copy_gbs": copy_gbs[1]}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
-    for key in ("fused_output_quantization", "simulated_path", "grouped_moe"):
+    for key in ("fused_output_quantization", "simulated_path", "grouped_moe", "single_copy"):
         if key in extras:
             out[key] = extras[key]
     if "layer_set" in extras:

@@ -169,6 +169,21 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
                            int32_t max_workgroups, void *hip_stream);
 
 /*
+ * Single-copy storage (Section 5 names the two stored copies per tensor as the overhead to remove): keep
+ * only the row copy of a tensor and derive the column copy from it when the backward pass needs it. Every
+ * element of q_row [rows x cols] / s_row is decoded exactly (Q_i * X) and the decoded tensor is quantized along
+ * its columns exactly as mxfp8_quantize_ex(MXFP8_COLWISE) would quantize an FP32 source holding those values:
+ *   q_colT [cols x rows], s_colT = scales of the transposed copy (mxfp8_scale_bytes(cols, rows, layout)).
+ * The result differs from the column copy of the ORIGINAL tensor by one more rounding (values that the row
+ * copy represents exactly come out identical). s_row and s_colT are in `scale_layout`. Requirements: rows % 32
+ * == 0, cols % 32 == 0, q_row and q_colT 16-byte aligned, nothing overlaps. A 0xFF scale or NaN code in the row
+ * copy makes the column blocks it touches NaN blocks.
+ */
+mxfp8_status mxfp8_requantize_colwise_ex(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols,
+                                         uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout,
+                                         void *hip_stream);
+
+/*
  * Grouped products for mixture-of-experts layers (Appendix A.4: the recipe applies unchanged to the expert
  * GEMMs). Tokens are sorted by expert: tokens [group_ends[e-1], group_ends[e]) (from 0 for e = 0) belong to
  * expert e. group_ends is a DEVICE array of `groups` int32 (token counts come from the router on the GPU;

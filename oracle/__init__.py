@@ -199,11 +199,14 @@ def gemm(a_q, a_s, b_q, b_s):
 def requantize_colwise(q_row: np.ndarray, s_row: np.ndarray):
     """Column copy of a tensor of which only the MXFP8 row copy (q_row [rows x cols], s_row) was kept: every
     element is decoded exactly (Q_i * X, in double, then FP32 without rounding) and the decoded tensor is
-    quantized down its columns like any FP32 source. Returns (qT [cols x rows], sT [cols x rows/32])."""
+    quantized down its columns like any FP32 source (FP32 being the widest source format of Section 3.3, a
+    decoded magnitude beyond it counts as +-Inf, as it would in such a source). Returns (qT [cols x rows], sT [cols x rows/32])."""
     v = dequantize(q_row, s_row, "f64")
-    v32 = v.astype(np.float32)
-    if not np.array_equal(v32.astype(np.float64)[np.isfinite(v)], v[np.isfinite(v)]):
-        raise ValueError("a decoded value is not an FP32 number")   # cannot happen: 4 significant bits, 2^-136 .. 2^135
+    with np.errstate(over="ignore"):
+        v32 = v.astype(np.float32)  # exact, except that magnitudes beyond FP32 (scale bytes >= 247 only) become +-Inf
+    ok = np.isfinite(v32)
+    if not np.array_equal(v32[ok].astype(np.float64), v[ok]):
+        raise ValueError("a decoded value is not an FP32 number")   # cannot happen: 4 significant bits, >= 2^-136
     return quantize_colwise(v32)
 
 

@@ -67,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_quantize_mode_ex.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, ci, vp]
     lib.mxfp8_dequantize_mode_ex.restype = ci
     lib.mxfp8_dequantize_mode_ex.argtypes = [vp, vp, i64, i64, ci, vp, ci, i64, ci, vp]
+    lib.mxfp8_requantize_colwise_ex.restype = ci
+    lib.mxfp8_requantize_colwise_ex.argtypes = [vp, vp, i64, i64, vp, vp, ci, vp]
     lib.mxfp8_gemm_grouped_ex.restype = ci
     lib.mxfp8_gemm_grouped_ex.argtypes = [ci, vp, vp, vp, vp, vp, ctypes.c_int32, i64, i64, i64, vp, ci, i64, ci, ctypes.c_int32, vp]
     lib.mxfp8_gemm_bf16.restype = ci
@@ -188,6 +190,23 @@ def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, ma
                               _dtype_code(c.dtype), ldc, scale_layout, max_workgroups, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_gemm")
+
+
+def mxfp8_requantize_colwise_ex(q_row, s_row, q_colT, s_colT, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """Column copy (q_colT [cols x rows], s_colT) derived from the row copy (q_row [rows x cols], s_row) of a tensor."""
+    _need_cuda(q_row, s_row, q_colT, s_colT)
+    rows, cols = q_row.shape
+    _check_scales(s_row, rows, cols, scale_layout, "s_row")
+    _check_scales(s_colT, cols, rows, scale_layout, "s_colT")
+    if tuple(q_colT.shape) != (cols, rows):
+        raise ValueError("q_colT must be [cols x rows]")
+    for t in (q_row, s_row, q_colT, s_colT):
+        if not t.is_contiguous() or t.dtype != torch.uint8:
+            raise ValueError("quantized tensors must be dense uint8")
+    rc = load().mxfp8_requantize_colwise_ex(_ptr(q_row), _ptr(s_row), rows, cols, _ptr(q_colT), _ptr(s_colT), scale_layout,
+                                            _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_requantize_colwise_ex")
 
 
 def mxfp8_gemm_grouped_ex(pass_, a_q, a_s, b_q, b_s, group_ends, c, scale_layout=SCALES_ROWMAJOR, max_workgroups=0,
@@ -351,6 +370,17 @@ def gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES
     c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
     mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout, max_workgroups)
     return c
+
+
+def requantize_colwise(q_row, s_row, scale_layout=SCALES_ROWMAJOR):
+    """Allocate and return {'q_colT', 's_colT'} derived from a row copy (see mxfp8_requantize_colwise_ex)."""
+    rows, cols = q_row.shape
+    u8 = dict(dtype=torch.uint8, device=q_row.device)
+    tiled = scale_layout != SCALES_ROWMAJOR
+    out = {"q_colT": torch.empty((cols, rows), **u8),
+           "s_colT": torch.empty((mxfp8_scale_bytes(cols, rows, scale_layout),) if tiled else (cols, rows // K_BLOCK), **u8)}
+    mxfp8_requantize_colwise_ex(q_row, s_row, out["q_colT"], out["s_colT"], scale_layout)
+    return out
 
 
 def gemm_grouped(pass_, a_q, a_s, b_q, b_s, group_ends, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):

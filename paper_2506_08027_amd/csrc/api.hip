@@ -17,6 +17,8 @@ hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8
                              int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
                              uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, int max_workgroups,
                              hipStream_t stream);
+hipError_t launch_requantize_colwise(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols, uint8_t *q_colT,
+                                     uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
 hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
                                const int32_t *group_ends, int groups, int64_t b_group_bytes, int64_t bs_group_bytes,
                                int64_t M, int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
@@ -99,6 +101,24 @@ mxfp8_status mxfp8_quantize_mode_ex(const void *src, mxfp8_dtype src_dtype, int6
                                                 q_row, s_row, q_colT, s_colT, tiled,
                                                 (element == MXFP8_E5M2 ? 1 : 0) | (rule == MXFP8_SCALE_OCP_V1 ? 2 : 0),
                                                 static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_requantize_colwise_ex(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols,
+                                         uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout, void *hip_stream)
+{
+    if (!valid_layout(scale_layout))
+        return MXFP8_ERR_MODE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || rows % 32 || cols % 32)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    if (!q_row || !s_row || !q_colT || !s_colT)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(q_row) || !aligned16(q_colT))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_requantize_colwise(q_row, s_row, rows, cols, q_colT, s_colT,
+                                                          scale_layout == MXFP8_SCALES_TILED, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

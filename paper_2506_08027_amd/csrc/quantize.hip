@@ -120,12 +120,30 @@ __device__ __forceinline__ uint32_t convert_down4(const uint4 (&x)[NROWS], int r
     return q;
 }
 
-template <bool BF16, bool ROW, bool COL, bool TILED, int MODE>
+// Four E4M3 codes and the scale byte of their block as four FP32 values (exact: a code has 4 significant bits
+// and FP32 holds every Q * 2^n down to its subnormals); a 0xFF scale gives NaN.
+__device__ __forceinline__ uint4 decode_mx4(uint32_t q, uint32_t sb)
+{
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    const v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)q, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)q, true);
+    const int e = (int)sb - 127;
+    if (sb == 0xFF)
+        return make_uint4(0x7FC00000u, 0x7FC00000u, 0x7FC00000u, 0x7FC00000u);
+    return make_uint4(__float_as_uint(ldexpf(lo[0], e)), __float_as_uint(ldexpf(lo[1], e)), __float_as_uint(ldexpf(hi[0], e)),
+                      __float_as_uint(ldexpf(hi[1], e)));
+}
+
+// MXSRC (BF16 = false): the source is itself an MXFP8 row copy, src = its element bytes [rows x cols] (dense),
+// src_s = its scale bytes in the same layout as the outputs. Every value is decoded exactly on load and then
+// treated like an FP32 source: this derives the column copy of a tensor from its row copy (single-copy
+// storage, Section 5) at the price of a second rounding.
+template <bool BF16, bool ROW, bool COL, bool TILED, int MODE, bool MXSRC = false>
 __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     const uint8_t *__restrict__ src, int64_t rows, int64_t cols, int64_t ld_bytes,
     uint8_t *__restrict__ q_row, uint8_t *__restrict__ s_row, uint8_t *__restrict__ q_colT,
-    uint8_t *__restrict__ s_colT, uint32_t tiles_x, uint32_t ntiles)
+    uint8_t *__restrict__ s_colT, uint32_t tiles_x, uint32_t ntiles, const uint8_t *__restrict__ src_s)
 {
+    static_assert(!MXSRC || !BF16, "an MXFP8 source goes through the FP32 register layout");
     using T = QTraits<BF16>;
     constexpr int VEC = T::VEC, ROWS = T::ROWS, CC = T::CC;
     constexpr int ESIZE = BF16 ? 2 : 4;
@@ -136,6 +154,10 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     __shared__ __attribute__((aligned(16))) uint8_t lds_q[COL ? kTile * kTile : 16];
     __shared__ __attribute__((aligned(16))) uint8_t lds_rs[ROW ? kTile * 4 : 16];
     __shared__ __attribute__((aligned(16))) uint8_t lds_cs[COL ? kTile * 4 : 16];
+    // MXFP8 source: the tile's element bytes (full 128-byte rows, loaded 16 bytes per work-item) and one dword
+    // of scale bytes per row; the lanes pick their 4 codes per row from here
+    __shared__ __attribute__((aligned(16))) uint8_t lds_src[MXSRC ? kTile * kTile : 16];
+    __shared__ uint32_t lds_src_s[MXSRC ? kTile : 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -155,12 +177,40 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
         // ragged tile, and whole 32-column blocks (groups of LANES_PER_BLOCK lanes) are too.
         const bool active = col0 < cols && row0 < rows;
 
+        if constexpr (MXSRC) {
+#pragma unroll
+            for (int k = 0; k < kTile * kTile / 16 / kQuantThreads; ++k) {
+                const int idx = k * kQuantThreads + tid, r = idx / (kTile / 16), c = (idx % (kTile / 16)) * 16;
+                if (wg_row0 + r < rows && wg_col0 + c < cols)   // cols % 32 == 0: a 16-byte piece is wholly inside or outside
+                    *reinterpret_cast<uint4 *>(lds_src + r * kTile + c) =
+                        stream_load(reinterpret_cast<const uint4 *>(src + (wg_row0 + r) * cols + wg_col0 + c));
+            }
+            if (tid < kTile && wg_row0 + tid < rows) {
+                const int64_t r = wg_row0 + tid, b0 = wg_col0 / kBlock;  // b0 % 4 == 0
+                uint32_t w = 0;
+                if constexpr (TILED) {
+                    w = *reinterpret_cast<const uint32_t *>(src_s + (((r >> 6) * ((nb_row + 3) / 4) + (b0 >> 2)) * 64 + (r & 63)) * 4);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if (b0 + b < nb_row)
+                            w |= (uint32_t)src_s[r * nb_row + b0 + b] << (8 * b);
+                }
+                lds_src_s[tid] = w;
+            }
+            __syncthreads();
+        }
         uint4 x[ROWS];
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
             x[i] = make_uint4(0, 0, 0, 0);
-            if (active)
+            if constexpr (MXSRC) {
+                if (active)
+                    x[i] = decode_mx4(*reinterpret_cast<const uint32_t *>(lds_src + (lrow0 + i) * kTile + lcol0),
+                                      (lds_src_s[lrow0 + i] >> (8 * (lcol0 / kBlock))) & 0xFFu);
+            } else if (active) {
                 x[i] = stream_load(reinterpret_cast<const uint4 *>(src + (row0 + i) * ld_bytes + col0 * ESIZE));
+            }
         }
 
         if constexpr (ROW) {
@@ -371,13 +421,13 @@ static hipError_t launch_quantize_t(const void *src, int64_t rows, int64_t cols,
     const int64_t ldb = ld * (BF16 ? 2 : 4);
     if (axis == 1)
         hipLaunchKernelGGL((quantize_kernel<BF16, true, false, TILED, MODE>), grid, block, 0, stream, s, rows, cols, ldb,
-                           q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y));
+                           q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y), static_cast<const uint8_t *>(nullptr));
     else if (axis == 2)
         hipLaunchKernelGGL((quantize_kernel<BF16, false, true, TILED, MODE>), grid, block, 0, stream, s, rows, cols, ldb,
-                           q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y));
+                           q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y), static_cast<const uint8_t *>(nullptr));
     else
         hipLaunchKernelGGL((quantize_kernel<BF16, true, true, TILED, MODE>), grid, block, 0, stream, s, rows, cols, ldb,
-                           q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y));
+                           q_row, s_row, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y), static_cast<const uint8_t *>(nullptr));
     return hipGetLastError();
 }
 
@@ -394,6 +444,24 @@ static hipError_t launch_quantize_mode(const void *src, bool bf16, int64_t rows,
 }
 
 // mode: bit 0 = E5M2 elements, bit 1 = OCP v1 scale rule (0 = the recipe)
+// Column copy of a tensor derived from its MXFP8 row copy (see quantize_kernel, MXSRC).
+hipError_t launch_requantize_colwise(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols, uint8_t *q_colT,
+                                     uint8_t *s_colT, bool tiled_scales, hipStream_t stream)
+{
+    const int64_t tiles_x = (cols + kTile - 1) / kTile, tiles_y = (rows + kTile - 1) / kTile;
+    if (tiles_x * tiles_y > 0x7FFFFFFF)
+        return hipErrorInvalidConfiguration;
+    const dim3 grid((unsigned)(tiles_x * tiles_y)), block(kQuantThreads);
+    uint8_t *none = nullptr;
+    if (tiled_scales)
+        hipLaunchKernelGGL((quantize_kernel<false, false, true, true, 0, true>), grid, block, 0, stream, q_row, rows, cols, cols, none,
+                           none, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y), s_row);
+    else
+        hipLaunchKernelGGL((quantize_kernel<false, false, true, false, 0, true>), grid, block, 0, stream, q_row, rows, cols, cols, none,
+                           none, q_colT, s_colT, (uint32_t)tiles_x, (uint32_t)(tiles_x * tiles_y), s_row);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis,
                            uint8_t *q_row, uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales,
                            int mode, hipStream_t stream)

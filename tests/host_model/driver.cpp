@@ -11,6 +11,7 @@
 //              (b_q = groups x N x K bytes, b_s = groups scale operands; rows outside every group keep 0xA5)
 //   gemmgrpk   <M> <N> <K> <f32|bf16> <ldc> <groups> <a_q> <a_s> <b_q> <b_s> <ends.bin (int32)> <c.bin> [tiled]
 //              (weight-gradient form: the ends split K; c = groups x M x ldc elements)
+//   requant    <rows> <cols> <q_row.bin> <s_row.bin> <out-prefix> [tiled]   (column copy from the row copy: .q_colT .s_colT)
 //   copy       <bytes> <workgroups> <mode 0|1|2> <src.bin> <dst.bin>      (the plain-copy rate probe)
 //   gemmq      <pass 0|1|2> <M> <N> <K> <ldc> <axis 1|2|3> <a_q> <a_s> <b_q> <b_s> <out-prefix> [tiled]
 //              (BF16 product <prefix>.c plus the MXFP8 copies of it: .q_row .s_row .q_colT .s_colT)
@@ -241,6 +242,19 @@ int main(int argc, char **argv)
             unchanged(e, "group_ends");
             report(st);
             save(cout, c);
+        } else if (op == "requant") {
+            long rows, cols;
+            std::string q, sc, prefix;
+            ls >> rows >> cols >> q >> sc >> prefix;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            Buf qb = load(q, (size_t)rows * cols), sb = load(sc, (size_t)mxfp8_scale_bytes(rows, cols, lay));
+            Buf qc = output((size_t)rows * cols), scT = output((size_t)mxfp8_scale_bytes(cols, rows, lay));
+            const int st = mxfp8_requantize_colwise_ex(qb.p, sb.p, rows, cols, qc.p, scT.p, lay, nullptr);
+            unchanged(qb, "q_row");
+            unchanged(sb, "s_row");
+            report(st);
+            save(prefix + ".q_colT", qc);
+            save(prefix + ".s_colT", scT);
         } else if (op == "copy") {
             long bytes, wgs, mode;
             std::string src, dst;

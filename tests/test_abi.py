@@ -33,7 +33,7 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == ["mxfp8_copy_rate_probe", "mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex", "mxfp8_gemm",
                                     "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
-                                    "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_scale_bytes",
+                                    "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_requantize_colwise_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
 
 
@@ -158,6 +158,16 @@ def test_gemm_validation_needs_no_gpu(lib):
     assert f(0, P(0x1008), FAKE, FAKE, FAKE, 64, 64, 128, FAKE, 0, 64, None) == 3
     assert f(0, *ok, 64, 64, 128, P(0x1002), 0, 64, None) == 3                   # FP32 c needs 4-byte alignment
     assert f(0, *ok, 0, 64, 128, None, 0, 64, None) == 0
+
+
+def test_requantize_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_requantize_colwise_ex
+    f.argtypes = [P, P, I64, I64, P, P, ctypes.c_int, P]
+    assert f(FAKE, FAKE, 64, 64, FAKE, FAKE, 2, None) == 5
+    assert f(FAKE, FAKE, 48, 64, FAKE, FAKE, 0, None) == 2 and f(FAKE, FAKE, 64, 48, FAKE, FAKE, 0, None) == 2
+    assert f(None, FAKE, 64, 64, FAKE, FAKE, 0, None) == 1 and f(FAKE, FAKE, 64, 64, FAKE, None, 0, None) == 1
+    assert f(P(0x1004), FAKE, 64, 64, FAKE, FAKE, 0, None) == 3
+    assert f(None, None, 0, 64, None, None, 0, None) == 0
 
 
 def test_grouped_gemm_validation_needs_no_gpu(lib):

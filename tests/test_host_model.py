@@ -150,6 +150,20 @@ def test_quantize_resident_grid_walks_over_several_tiles(hostmodel, tmp_path, ti
     _quantize_and_compare(hostmodel, tmp_path, x, True, 3, tiled=tiled, groups=4, WAVESIM_CUS=1)
 
 
+@pytest.mark.parametrize("tiled", [False, True])
+def test_requantize_column_copy_from_row_copy(hostmodel, tmp_path, tiled):
+    """Single-copy storage: ragged tiles, every special block of the tiny configuration in the row copy."""
+    x = np.ascontiguousarray(si.tiny_with_specials(256, seed=0)[:160, :224])
+    q, s = oracle.quantize_rowwise(x)
+    prefix = str(tmp_path / "rq")
+    _, calls = run_case(hostmodel, tmp_path, [f"requant 160 224 {put(tmp_path, 'q.bin', q)} "
+                                              f"{put(tmp_path, 's.bin', sl.tile(s) if tiled else s)} {prefix}" + (" tiled" if tiled else "")])
+    assert calls[0] == (0, [0, 1, 2, 3])
+    qT, sT = oracle.requantize_colwise(q, s)
+    assert np.array_equal(get(prefix + ".q_colT", np.uint8, qT.shape), qT)
+    _compare_scales(prefix + ".s_colT", sT, tiled)
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_dequantize_all_codes_and_padding_untouched(hostmodel, tmp_path, bf16):
     scales = np.array([0, 1, 100, 126, 127, 128, 200, 253, 254, 255], np.uint8)

@@ -67,3 +67,8 @@ def test_grouped_gpu_tests_pass_on_the_host_model(hostmodel_lib):
     """The grouped (mixture-of-experts) product; the 4096-token and full-size cases are left to the GPU."""
     n = replay(hostmodel_lib, ["test_gpu_grouped.py"], "not full_size and not equals_the_plain_product")
     assert n >= 6
+
+
+def test_single_copy_gpu_tests_pass_on_the_host_model(hostmodel_lib):
+    n = replay(hostmodel_lib, ["test_gpu_single_copy.py"], "not full_size")
+    assert n >= 5
