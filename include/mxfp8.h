@@ -274,6 +274,36 @@ mxfp8_status mxfp8_dequantize_mode_ex(const uint8_t *q, const uint8_t *s, int64_
                                       mxfp8_scale_layout scale_layout, void *hip_stream);
 
 /*
+ * MXFP4 (Table 1: E2M1 elements, largest magnitude 6, 32-element blocks with a UE8M0 scale), the narrower
+ * format of the family that the conversion of Section 3.3 / Algorithm 1 / Appendix A.1 and A.2 covers with
+ * other constants: X = 2^n for the smallest n with amax <= 6 * 2^n (clamped to [-127, 127]), Q_i = V_i / X
+ * rounded to the nearest of 0, 0.5, 1, 1.5, 2, 3, 4, 6 (ties to the code with an even mantissa bit), saturating
+ * at +-6, sign kept. Two elements per byte: element 2k of a block in the low nibble of byte k, element 2k + 1
+ * in the high nibble (code = sign << 3 | exponent << 1 | mantissa).
+ *   MXFP8_ROWWISE   q_row  [rows x cols/2] bytes, s_row  [rows x cols/32] bytes
+ *   MXFP8_COLWISE   q_colT [cols x rows/2] bytes, s_colT [cols x rows/32] bytes  (stored transposed)
+ *   MXFP8_BOTH      both, each from the source itself.
+ * Scale bytes are in `scale_layout`, sized by mxfp8_scale_bytes as for MXFP8. Requirements as for
+ * mxfp8_quantize_ex: rows % 32 == 0, cols % 32 == 0, src 16-byte aligned with ld_src a multiple of 16 bytes,
+ * q_row and q_colT 16-byte aligned, nothing overlaps. E2M1 has neither NaN nor Inf: a block with a NaN gets
+ * scale 0xFF and all codes 0 (the scale alone marks it), a block with +-Inf and no NaN gets scale 254, its
+ * infinities become +-6 and its finite values are divided by 2^127 (they round to +-0).
+ */
+mxfp8_status mxfp8_fp4_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                                   int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
+                                   uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout,
+                                   void *hip_stream);
+
+/* dst[r, c] = E2M1(code(r, c)) * 2^(s[r, c/32] - 127) for an MXFP4 operand q [rows x cols/2], s (Section 2:
+ * value = X * P_i). dst is FP32 or BF16 with leading dimension ld_dst >= cols; every decoded value is exact in
+ * BF16 unless it lies below 2^-133 or above the format's range (then RNE / +-Inf as the conversion gives).
+ * A 0xFF scale decodes to NaN. Requirements: cols % 32 == 0; q and dst 16-byte aligned, ld_dst a multiple of
+ * 16 bytes. */
+mxfp8_status mxfp8_fp4_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
+                                     mxfp8_dtype dst_dtype, int64_t ld_dst, mxfp8_scale_layout scale_layout,
+                                     void *hip_stream);
+
+/*
  * Measurement aid for benchmarks (no operation of the paper): `workgroups` workgroups of 4 wavefronts each
  * issue iterations * 64 independent scaled FP8 matrix instructions (16x16x128, 65536 flop each) on register
  * operands, without memory traffic, and then store one float per work-item to sink[workgroups * 256]

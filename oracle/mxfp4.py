@@ -105,3 +105,15 @@ def dequantize(q, s):
     s = np.asarray(s, np.uint8)
     scale = np.repeat(np.where(s == 0xFF, np.nan, np.exp2(s.astype(np.float64) - 127.0)), K_BLOCK, axis=1)
     return e2m1_decode(codes) * scale
+
+
+def gemm(a_q, a_s, b_q, b_s):
+    """C = A * B^T for MXFP4 operands A [M x K/2], B [N x K/2] (blocks along K): the block-scaled sum of Section 2
+    and Appendix A.3, C[m, n] = sum_b 2^(a_s[m,b] + b_s[n,b] - 254) * sum_{i<32} P_a[m,32b+i] * P_b[n,32b+i], written
+    as the product of the decoded operands in float64 (every decoded value and every product of two is exact there;
+    the sum rounds at 2^-53 per addition). Returns (C, sum|a*b|) for tolerances; a 0xFF scale makes its row NaN."""
+    da, db = dequantize(a_q, a_s), dequantize(b_q, b_s)
+    if da.shape[1] != db.shape[1]:
+        raise ValueError("operands disagree on K")
+    with np.errstate(invalid="ignore", over="ignore"):
+        return da @ db.T, np.abs(da) @ np.abs(db).T

@@ -74,6 +74,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_gemm_bf16.restype = ci
     lib.mxfp8_gemm_bf16.argtypes = [vp, vp, i64, i64, i64, vp, ci, i64, ctypes.c_int32, vp]
     lib.mxfp8_mfma_rate_probe.restype = ci
+    lib.mxfp8_fp4_quantize_ex.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, vp, ci, vp]
+    lib.mxfp8_fp4_quantize_ex.restype = ci
+    lib.mxfp8_fp4_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
+    lib.mxfp8_fp4_dequantize_ex.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_copy_rate_probe.restype = ci
     lib.mxfp8_copy_rate_probe.argtypes = [vp, vp, i64, ctypes.c_int32, ctypes.c_int32, vp]
@@ -342,6 +346,43 @@ def mxfp8_dequantize_mode_ex(q, s, element, dst, scale_layout=SCALES_ROWMAJOR, s
     mxfp8_dequantize_ex(q, s, dst, scale_layout, stream, element)
 
 
+def mxfp8_fp4_quantize_ex(src, axis, q_row=None, s_row=None, q_colT=None, s_colT=None,
+                          scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """src [rows x cols] float32/bfloat16 -> MXFP4 copies: q_row [rows x cols/2], q_colT [cols x rows/2] (two E2M1
+    codes per byte), scales as for MXFP8."""
+    _need_cuda(src, q_row, s_row, q_colT, s_colT)
+    if src.dim() != 2 or (src.numel() and src.stride(1) != 1):
+        raise ValueError("src must be 2-D with contiguous rows")
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else max(cols, 1)
+    ax = _AXIS[axis]
+    for want, q, s, r, c, what in ((ax & ROWWISE, q_row, s_row, rows, cols, "row"), (ax & COLWISE, q_colT, s_colT, cols, rows, "colT")):
+        if want and q is not None and s is not None:   # the library cannot see buffer sizes: check them here
+            if q.dtype != torch.uint8 or not q.is_contiguous() or q.numel() != r * c // 2:
+                raise ValueError(f"q_{what} must be dense uint8 with {r * c // 2} bytes")
+            _check_scales(s, r, c, scale_layout, f"s_{what}")
+    rc = load().mxfp8_fp4_quantize_ex(_ptr(src), _dtype_code(src.dtype), rows, cols, ld, ax, _ptr(q_row), _ptr(s_row),
+                                      _ptr(q_colT), _ptr(s_colT), scale_layout, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_fp4_quantize_ex")
+
+
+def mxfp8_fp4_dequantize_ex(q, s, dst, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """q [rows x cols/2] packed E2M1 codes, s its scales -> dst [rows x cols] float32/bfloat16."""
+    _need_cuda(q, s, dst)
+    rows, cols = dst.shape
+    if q.dtype != torch.uint8 or not q.is_contiguous() or tuple(q.shape) != (rows, cols // 2):
+        raise ValueError(f"q must be dense uint8 [{rows} x {cols // 2}]")
+    _check_scales(s, rows, cols, scale_layout, "s")
+    if dst.numel() and dst.stride(1) != 1:
+        raise ValueError("dst rows must be contiguous")
+    ld = dst.stride(0) if rows > 1 else max(cols, 1)
+    rc = load().mxfp8_fp4_dequantize_ex(_ptr(q), _ptr(s), rows, cols, _ptr(dst), _dtype_code(dst.dtype), ld, scale_layout,
+                                        _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_fp4_dequantize_ex")
+
+
 # ---- conveniences that only allocate the outputs ----------------------------------------------
 
 def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR, element=E4M3, rule=SCALE_ROUND_UP):
@@ -422,4 +463,27 @@ def gemm_quantize(pass_, a_q, a_s, b_q, b_s, axis="both", scale_layout=SCALES_RO
 def dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, element=E4M3):
     dst = torch.empty(tuple(q.shape), dtype=out_dtype, device=q.device)
     mxfp8_dequantize_ex(q, s, dst, scale_layout, element=element)
+    return dst
+
+
+def fp4_quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR):
+    """Allocate outputs and call mxfp8_fp4_quantize_ex; keys as for quantize(), element buffers half as wide."""
+    rows, cols = src.shape
+    ax = _AXIS[axis]
+    out = {}
+    u8 = dict(dtype=torch.uint8, device=src.device)
+    tiled = scale_layout != SCALES_ROWMAJOR
+    if ax & ROWWISE:
+        out["q_row"] = torch.empty((rows, cols // 2), **u8)
+        out["s_row"] = torch.empty((mxfp8_scale_bytes(rows, cols, scale_layout),) if tiled else (rows, cols // K_BLOCK), **u8)
+    if ax & COLWISE:
+        out["q_colT"] = torch.empty((cols, rows // 2), **u8)
+        out["s_colT"] = torch.empty((mxfp8_scale_bytes(cols, rows, scale_layout),) if tiled else (cols, rows // K_BLOCK), **u8)
+    mxfp8_fp4_quantize_ex(src, ax, out.get("q_row"), out.get("s_row"), out.get("q_colT"), out.get("s_colT"), scale_layout)
+    return out
+
+
+def fp4_dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):
+    dst = torch.empty((q.shape[0], q.shape[1] * 2), dtype=out_dtype, device=q.device)
+    mxfp8_fp4_dequantize_ex(q, s, dst, scale_layout)
     return dst

@@ -17,6 +17,10 @@ hipError_t launch_gemm_fused(const uint8_t *a_q, const uint8_t *a_s, const uint8
                              int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int axis, uint8_t *cq,
                              uint8_t *cs, uint8_t *cqT, uint8_t *csT, bool tiled_scales, int max_workgroups,
                              hipStream_t stream);
+hipError_t launch_quantize_fp4(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis, uint8_t *q_row,
+                               uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
+hipError_t launch_dequantize_fp4(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst, bool bf16,
+                                 bool tiled_scales, int64_t ld, hipStream_t stream);
 hipError_t launch_requantize_colwise(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols, uint8_t *q_colT,
                                      uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
 hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
@@ -277,6 +281,53 @@ mxfp8_status mxfp8_dequantize_mode_ex(const uint8_t *q, const uint8_t *s, int64_
     const hipError_t e = mxfp8::launch_dequantize(q, s, rows, cols, dst, dst_dtype == MXFP8_BF16,
                                                   scale_layout == MXFP8_SCALES_TILED, element == MXFP8_E5M2, ld_dst,
                                                   static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_fp4_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                                   int64_t ld_src, mxfp8_axis axis, uint8_t *q_row, uint8_t *s_row,
+                                   uint8_t *q_colT, uint8_t *s_colT, mxfp8_scale_layout scale_layout,
+                                   void *hip_stream)
+{
+    if (!valid_dtype(src_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout) || (axis != MXFP8_ROWWISE && axis != MXFP8_COLWISE && axis != MXFP8_BOTH))
+        return MXFP8_ERR_MODE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || rows % 32 || cols % 32 || ld_src < cols)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    const bool want_row = axis & MXFP8_ROWWISE, want_col = axis & MXFP8_COLWISE;
+    if (!src || (want_row && (!q_row || !s_row)) || (want_col && (!q_colT || !s_colT)))
+        return MXFP8_ERR_NULL;
+    if (!aligned16(src) || (ld_src * esize(src_dtype)) % 16 || (want_row && !aligned16(q_row)) ||
+        (want_col && !aligned16(q_colT)))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_quantize_fp4(src, src_dtype == MXFP8_BF16, rows, cols, ld_src, (int)axis, q_row, s_row,
+                                                    q_colT, s_colT, scale_layout == MXFP8_SCALES_TILED,
+                                                    static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_fp4_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst,
+                                     mxfp8_dtype dst_dtype, int64_t ld_dst, mxfp8_scale_layout scale_layout,
+                                     void *hip_stream)
+{
+    if (!valid_dtype(dst_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout))
+        return MXFP8_ERR_MODE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || cols % 32 || ld_dst < cols)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    if (!q || !s || !dst)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(q) || !aligned16(dst) || (ld_dst * esize(dst_dtype)) % 16)
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_dequantize_fp4(q, s, rows, cols, dst, dst_dtype == MXFP8_BF16,
+                                                      scale_layout == MXFP8_SCALES_TILED, ld_dst,
+                                                      static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

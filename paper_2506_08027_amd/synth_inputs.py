@@ -121,3 +121,33 @@ def tiny_with_specials(n: int = 256, seed: int = 0) -> np.ndarray:
     for (name, v), (b, c) in zip(blocks, slots_col):
         x[b * K_BLOCK:(b + 1) * K_BLOCK, c] = v
     return x
+
+
+def fp4_hard_cases(rows: int, cols: int, seed: int) -> np.ndarray:
+    """N(0,1) with outliers, plus blocks whose elements sit on every rounding tie and whose amax sits on, just
+    above and just below the scale boundary 6 * 2^k, for k over the whole exponent range; NaN / Inf blocks."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, cols), dtype=np.float32)
+    x[rng.random((rows, cols)) < 0.01] *= np.float32(100.0)
+    ties = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, 0.0, 0.24999999, 0.25000003,
+                     2.4999998, 2.5000002, 4.9999995, 5.0000005, 5.9999995], np.float64)
+    ks = [-149, -140, -129, -128, -127, -126, -125, -60, -1, 0, 1, 50, 124, 125]
+    slot = 0
+    for k in ks:
+        for top in (6.0, np.nextafter(np.float32(6.0), np.float32(7.0)), np.nextafter(np.float32(6.0), np.float32(0.0)), 4.0, 3.0):
+            blk = rng.choice(ties, 32) * rng.choice([-1.0, 1.0], 32)
+            blk[rng.integers(32)] = float(top)
+            with np.errstate(over="ignore", under="ignore"):
+                v = np.ldexp(blk, k).astype(np.float32)
+            r, b = (slot * 7) % rows, (slot * 3) % (cols // 32)
+            x[r, 32 * b:32 * b + 32] = v                                   # along a row
+            c, rb = (slot * 5 + 1) % cols, (slot * 2 + 1) % (rows // 32)
+            x[32 * rb:32 * rb + 32, c] = v                                 # down a column
+            slot += 1
+    x[1, 0] = np.nan
+    x[3, 40] = np.inf
+    x[rows - 1, cols - 1] = -np.inf
+    x[rows - 2, cols - 2] = np.nan
+    x[5, 64:96] = 0.0
+    x[5, 65] = -0.0
+    return x

@@ -59,8 +59,8 @@ PERSISTENT_MUTANTS = [
      "                a_src = next_tile.a + (int64_t)(kt + 2 - KT) * BK;", "                a_src = cur_tile.a + (int64_t)(kt + 2 - KT) * BK;"),
     ("persistent: accumulators not cleared between tiles", "                acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};\n        cur_tile = next_tile;",
      "                ;\n        cur_tile = next_tile;"),
-    ("persistent: buffer parity not carried across tiles", "            step(par, b_src, bs_src, a_src, as_src);\n            par ^= 1;",
-     "            step(kt & 1, b_src, bs_src, a_src, as_src);\n            par ^= 1;"),
+    ("persistent: buffer parity not carried across tiles", "            step(par, b_src, bs_src, a_src, as_src, a_lim);\n            par ^= 1;",
+     "            step(kt & 1, b_src, bs_src, a_src, as_src, a_lim);\n            par ^= 1;"),
 ]
 MODES = [{}, {"WAVESIM_ORDER": "down"}, {"WAVESIM_DMA": "eager"}, {"WAVESIM_DMA": "eager", "WAVESIM_ORDER": "down"}]
 
@@ -77,7 +77,7 @@ def build(work, gemm_text):
     binary = os.path.join(work, "hostmodel")
     cmd = ["/opt/rocm/llvm/bin/clang++", "-std=c++17", "-x", "c++", "-I", os.path.join(HERE, "shim"), "-O2",
            "-Wno-unknown-pragmas", "-Wno-psabi", "-o", binary, os.path.join(work, "driver.cpp")]
-    cmd += [os.path.join(csrc, f) for f in ("api.hip", "quantize.hip", "dequantize.hip", "gemm.hip", "diagnostics.hip")]
+    cmd += [os.path.join(csrc, f) for f in sorted(os.listdir(csrc)) if f.endswith(".hip")]
     subprocess.run(cmd, check=True, capture_output=True)
     return binary
 

@@ -31,8 +31,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["mxfp8_copy_rate_probe", "mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex", "mxfp8_gemm",
-                                    "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
+    assert declared_functions() == ["mxfp8_copy_rate_probe", "mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex",
+                                    "mxfp8_fp4_dequantize_ex", "mxfp8_fp4_quantize_ex", "mxfp8_gemm", "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
                                     "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_requantize_colwise_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
 
@@ -168,6 +168,23 @@ def test_requantize_validation_needs_no_gpu(lib):
     assert f(None, FAKE, 64, 64, FAKE, FAKE, 0, None) == 1 and f(FAKE, FAKE, 64, 64, FAKE, None, 0, None) == 1
     assert f(P(0x1004), FAKE, 64, 64, FAKE, FAKE, 0, None) == 3
     assert f(None, None, 0, 64, None, None, 0, None) == 0
+
+
+def test_fp4_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_fp4_quantize_ex
+    f.argtypes = [P, ctypes.c_int, I64, I64, I64, ctypes.c_int, P, P, P, P, ctypes.c_int, P]
+    assert f(FAKE, 2, 64, 64, 64, 3, FAKE, FAKE, FAKE, FAKE, 0, None) == 4
+    assert f(FAKE, 0, 64, 64, 64, 0, FAKE, FAKE, FAKE, FAKE, 0, None) == 5 and f(FAKE, 0, 64, 64, 64, 3, FAKE, FAKE, FAKE, FAKE, 2, None) == 5
+    assert f(FAKE, 0, 48, 64, 64, 3, FAKE, FAKE, FAKE, FAKE, 0, None) == 2 and f(FAKE, 0, 64, 64, 32, 3, FAKE, FAKE, FAKE, FAKE, 0, None) == 2
+    assert f(FAKE, 0, 64, 64, 64, 1, None, FAKE, None, None, 0, None) == 1 and f(FAKE, 0, 64, 64, 64, 2, None, None, FAKE, None, 0, None) == 1
+    assert f(P(0x1004), 0, 64, 64, 64, 1, FAKE, FAKE, None, None, 0, None) == 3 and f(FAKE, 1, 64, 64, 68, 1, FAKE, FAKE, None, None, 0, None) == 3
+    assert f(None, 0, 0, 64, 64, 3, None, None, None, None, 0, None) == 0
+    g = lib.mxfp8_fp4_dequantize_ex
+    g.argtypes = [P, P, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, P]
+    assert g(FAKE, FAKE, 64, 64, FAKE, 2, 64, 0, None) == 4 and g(FAKE, FAKE, 64, 64, FAKE, 0, 64, 2, None) == 5
+    assert g(FAKE, FAKE, 64, 48, FAKE, 0, 64, 0, None) == 2 and g(FAKE, FAKE, 64, 64, FAKE, 0, 32, 0, None) == 2
+    assert g(None, FAKE, 64, 64, FAKE, 0, 64, 0, None) == 1 and g(FAKE, FAKE, 64, 64, P(0x1008), 0, 64, 0, None) == 3
+    assert g(None, None, 64, 0, None, 0, 64, 0, None) == 0
 
 
 def test_grouped_gemm_validation_needs_no_gpu(lib):

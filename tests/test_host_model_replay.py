@@ -72,3 +72,9 @@ def test_grouped_gpu_tests_pass_on_the_host_model(hostmodel_lib):
 def test_single_copy_gpu_tests_pass_on_the_host_model(hostmodel_lib):
     n = replay(hostmodel_lib, ["test_gpu_single_copy.py"], "not full_size")
     assert n >= 5
+
+
+def test_fp4_gpu_tests_pass_on_the_host_model(hostmodel_lib):
+    """MXFP4 conversion; the full-size case is left to the GPU."""
+    n = replay(hostmodel_lib, ["test_gpu_fp4.py"], "not full_size")
+    assert n >= 12

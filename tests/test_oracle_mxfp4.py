@@ -111,3 +111,34 @@ def test_product_of_decoded_operands_reduces_to_the_bf16_product():
     C, A = oracle.matmul_nt_bf16(ba, bb)
     ref = da @ db.T
     assert np.allclose(C, ref, rtol=0, atol=1e-13 * np.abs(ref).max()) and np.allclose(A, np.abs(da) @ np.abs(db).T, rtol=1e-13)
+
+
+def test_gemm_is_the_block_scaled_sum_written_out():
+    """Brute force on a tiny case: the double loop over blocks and elements of Section 2's definition, with the
+    scale applied per block pair, in exact rational arithmetic."""
+    from fractions import Fraction
+    rng = np.random.default_rng(9)
+    M, N, K = 3, 4, 64
+    a = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-6, 6, (M, 1)))).astype(np.float32)
+    b = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    (a_q, a_s), (b_q, b_s) = mxfp4.quantize_rowwise(a), mxfp4.quantize_rowwise(b)
+    C, A = mxfp4.gemm(a_q, a_s, b_q, b_s)
+    ca, cb = mxfp4.unpack(a_q), mxfp4.unpack(b_q)
+    val = [Fraction(x) for x in (0, 0.5, 1, 1.5, 2, 3, 4, 6)]
+    for m in range(M):
+        for n in range(N):
+            tot, tot_abs = Fraction(0), Fraction(0)
+            for blk in range(K // 32):
+                inner = inner_abs = Fraction(0)
+                for i in range(32):
+                    x, y = int(ca[m, 32 * blk + i]), int(cb[n, 32 * blk + i])
+                    p = val[x & 7] * val[y & 7]
+                    inner += -p if (x ^ y) & 8 else p
+                    inner_abs += p
+                sc = Fraction(2) ** (int(a_s[m, blk]) + int(b_s[n, blk]) - 254)
+                tot += sc * inner
+                tot_abs += sc * inner_abs
+            assert abs(Fraction(C[m, n]) - tot) <= Fraction(2) ** -45 * tot_abs and Fraction(A[m, n]) == tot_abs
+    a_s[1, 0] = 0xFF
+    C, _ = mxfp4.gemm(a_q, a_s, b_q, b_s)
+    assert np.isnan(C[1]).all() and not np.isnan(C[[0, 2]]).any()
