@@ -326,6 +326,19 @@ mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float
 mxfp8_status mxfp8_copy_rate_probe(const void *src, void *dst, int64_t bytes, int32_t workgroups, int32_t mode,
                                    void *hip_stream);
 
+/*
+ * Third measurement aid (no operation of the paper): runs ONE scaled 16x16x128 matrix instruction per experiment
+ * on registers taken straight from memory, so that tests can pin the operand layout the product kernels rely on.
+ * Experiment x, lane l (0..63): operand registers a_regs / b_regs[(64 x + l) * 8 .. + 7] (dwords; with 4-bit
+ * elements only the first four are used), scale registers a_scale_regs / b_scale_regs[64 x + l] (byte 0 is
+ * used), zero accumulator; the lane's four result registers go to out[(64 x + l) * 4 .. + 3].
+ * element_bits 8: both operands E4M3; 4: both E2M1; anything else MXFP8_ERR_MODE. experiments in [0, 65536].
+ * a_regs, b_regs and out 16-byte aligned, the scale arrays 4-byte aligned; all device memory.
+ */
+mxfp8_status mxfp8_mfma_layout_probe(const void *a_regs, const void *b_regs, const int32_t *a_scale_regs,
+                                     const int32_t *b_scale_regs, int32_t experiments, int32_t element_bits,
+                                     float *out, void *hip_stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp8_status_string(mxfp8_status status);
 

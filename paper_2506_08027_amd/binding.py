@@ -80,6 +80,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_fp4_dequantize_ex.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_copy_rate_probe.restype = ci
+    lib.mxfp8_mfma_layout_probe.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.mxfp8_mfma_layout_probe.restype = ci
     lib.mxfp8_copy_rate_probe.argtypes = [vp, vp, i64, ctypes.c_int32, ctypes.c_int32, vp]
     lib.mxfp8_status_string.restype = ctypes.c_char_p
     lib.mxfp8_status_string.argtypes = [ci]
@@ -326,6 +328,21 @@ def mxfp8_mfma_rate_probe(workgroups: int, iterations: int, sink, stream=None) -
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_mfma_rate_probe")
     return workgroups * 4.0 * iterations * 64 * 65536
+
+
+def mxfp8_mfma_layout_probe(a_regs, b_regs, a_scale_regs, b_scale_regs, element_bits, out, stream=None) -> None:
+    """One scaled 16x16x128 matrix instruction per experiment: a_regs / b_regs int32 [X x 64 x 8], scale registers
+    int32 [X x 64], out float32 [X x 64 x 4]."""
+    _need_cuda(a_regs, b_regs, a_scale_regs, b_scale_regs, out)
+    X = a_regs.shape[0]
+    for t, shape, dt in ((a_regs, (X, 64, 8), torch.int32), (b_regs, (X, 64, 8), torch.int32), (a_scale_regs, (X, 64), torch.int32),
+                         (b_scale_regs, (X, 64), torch.int32), (out, (X, 64, 4), torch.float32)):
+        if tuple(t.shape) != shape or t.dtype != dt or not t.is_contiguous():
+            raise ValueError("operand registers int32 [X x 64 x 8], scale registers int32 [X x 64], out float32 [X x 64 x 4], dense")
+    rc = load().mxfp8_mfma_layout_probe(_ptr(a_regs), _ptr(b_regs), _ptr(a_scale_regs), _ptr(b_scale_regs), X, element_bits,
+                                        _ptr(out), _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_mfma_layout_probe")
 
 
 def mxfp8_copy_rate_probe(src, dst, workgroups, mode=0, stream=None) -> int:

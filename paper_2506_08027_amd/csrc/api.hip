@@ -21,6 +21,8 @@ hipError_t launch_quantize_fp4(const void *src, bool bf16, int64_t rows, int64_t
                                uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
 hipError_t launch_dequantize_fp4(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, void *dst, bool bf16,
                                  bool tiled_scales, int64_t ld, hipStream_t stream);
+hipError_t launch_mfma_layout(const void *a, const void *b, const int *sa, const int *sb, int experiments, bool fp4, float *out,
+                              hipStream_t stream);
 hipError_t launch_requantize_colwise(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols, uint8_t *q_colT,
                                      uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
 hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
@@ -342,6 +344,26 @@ mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float
     if (reinterpret_cast<uintptr_t>(sink) % 4)
         return MXFP8_ERR_ALIGN;
     const hipError_t e = mxfp8::launch_mfma_rate(workgroups, iterations, sink, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_mfma_layout_probe(const void *a_regs, const void *b_regs, const int32_t *a_scale_regs,
+                                     const int32_t *b_scale_regs, int32_t experiments, int32_t element_bits, float *out,
+                                     void *hip_stream)
+{
+    if (element_bits != 8 && element_bits != 4)
+        return MXFP8_ERR_MODE;
+    if (experiments < 0 || experiments > (1 << 16))
+        return MXFP8_ERR_SHAPE;
+    if (experiments == 0)
+        return MXFP8_OK;
+    if (!a_regs || !b_regs || !a_scale_regs || !b_scale_regs || !out)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(a_regs) || !aligned16(b_regs) || !aligned16(out) ||
+        reinterpret_cast<uintptr_t>(a_scale_regs) % 4 || reinterpret_cast<uintptr_t>(b_scale_regs) % 4)
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_mfma_layout(a_regs, b_regs, a_scale_regs, b_scale_regs, experiments, element_bits == 4,
+                                                   out, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

@@ -105,6 +105,37 @@ hipError_t launch_copy_rate(const void *src, void *dst, int64_t bytes, int workg
     return hipGetLastError();
 }
 
+// Third aid: hands the scaled matrix instruction registers straight from memory, one wavefront per experiment,
+// so that a test can pin which operand register of which lane holds which (row, k) and which lane's scale
+// byte applies to which k, for the element formats the product kernels use. Lane l of experiment x takes its
+// eight A dwords from a[(64 x + l) * 8 ..], likewise B, its scale registers from sa / sb[64 x + l], starts
+// from a zero accumulator and stores its four result registers to out[(64 x + l) * 4 ..].
+template <int FMT>
+__global__ __launch_bounds__(64) void mfma_layout_kernel(const v4i *__restrict__ a, const v4i *__restrict__ b,
+                                                         const int *__restrict__ sa, const int *__restrict__ sb,
+                                                         v4f *__restrict__ out)
+{
+    const size_t i = (size_t)blockIdx.x * 64 + threadIdx.x;
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+    const v4i a0 = a[2 * i], a1 = a[2 * i + 1], b0 = b[2 * i], b1 = b[2 * i + 1];
+    const v8i av = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+    const v8i bv = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+    out[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, zero, FMT, FMT, 0, sa[i], 0, sb[i]);
+}
+
+hipError_t launch_mfma_layout(const void *a, const void *b, const int *sa, const int *sb, int experiments, bool fp4, float *out,
+                              hipStream_t stream)
+{
+    const v4i *pa = static_cast<const v4i *>(a), *pb = static_cast<const v4i *>(b);
+    if (fp4)
+        hipLaunchKernelGGL(mfma_layout_kernel<4>, dim3((unsigned)experiments), dim3(64), 0, stream, pa, pb, sa, sb,
+                           reinterpret_cast<v4f *>(out));
+    else
+        hipLaunchKernelGGL(mfma_layout_kernel<0>, dim3((unsigned)experiments), dim3(64), 0, stream, pa, pb, sa, sb,
+                           reinterpret_cast<v4f *>(out));
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream)
 {
     hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, iterations, sink);

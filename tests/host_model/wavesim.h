@@ -425,6 +425,16 @@ inline v2f cvt_pk_f32_fp8(int q, bool hi)
     return v2f{(float)e4m3_value(u & 0xFF), (float)e4m3_value((u >> 8) & 0xFF)};
 }
 
+// E2M1 (4-bit MX element): sign, 2 exponent bits (bias 1), 1 mantissa bit; no NaN, no Inf
+inline double e2m1_value(unsigned code)
+{
+    const unsigned e = (code >> 1) & 3u, m = code & 1u;
+    const double mag = e == 0 ? 0.5 * m : std::ldexp(1.0 + 0.5 * m, (int)e - 1);
+    return (code & 8u) ? -mag : mag;
+}
+
+// With both operands E2M1 (cbsz = blgp = 4) only dwords 0..3 are used: lane 16g+r holds K 32g..32g+31 of row r,
+// eight elements per dword, and its scale byte scales exactly those (K block g).
 // v_mfma_scale_f32_16x16x128_f8f6f4 with both operands E4M3: lane 16g+r holds row r of its operand,
 // dwords 0..3 = K 16g..16g+15, dwords 4..7 = K 64+16g..64+16g+15; scale byte op_sel of lane (r, g)
 // scales row r in K block g; result register v of lane (r, g) is D[4g+v][r] with
@@ -433,8 +443,9 @@ inline v2f cvt_pk_f32_fp8(int q, bool hi)
 inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp, int opsel_first, int scale_first,
                                 int opsel_second, int scale_second)
 {
-    if (cbsz != 0 || blgp != 0)
-        fail("only E4M3 x E4M3 operands are modelled");
+    if (cbsz != blgp || (cbsz != 0 && cbsz != 4))
+        fail("only E4M3 x E4M3 and E2M1 x E2M1 operands are modelled");
+    const bool fp4 = cbsz == 4;
     struct Pub {
         v8i first, second;
         uint8_t s_first, s_second;
@@ -452,8 +463,13 @@ inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp
         uint8_t bytes[32];
         memcpy(bytes, &p.second, 32);
         for (int t = 0; t < 16; ++t) {
-            yv[16 * kg + t] = e4m3_value(bytes[t]);
-            yv[64 + 16 * kg + t] = e4m3_value(bytes[16 + t]);
+            if (fp4) {
+                yv[32 * kg + 2 * t] = e2m1_value(bytes[t] & 0xF);
+                yv[32 * kg + 2 * t + 1] = e2m1_value(bytes[t] >> 4);
+            } else {
+                yv[16 * kg + t] = e4m3_value(bytes[t]);
+                yv[64 + 16 * kg + t] = e4m3_value(bytes[16 + t]);
+            }
         }
         ys[kg] = p.s_second == 0xFF ? NAN : std::ldexp(1.0, (int)p.s_second - 127);
     }
@@ -467,8 +483,13 @@ inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp
             uint8_t bytes[32];
             memcpy(bytes, &p.first, 32);
             for (int t = 0; t < 16; ++t) {
-                xv[16 * kg + t] = e4m3_value(bytes[t]);
-                xv[64 + 16 * kg + t] = e4m3_value(bytes[16 + t]);
+                if (fp4) {
+                    xv[32 * kg + 2 * t] = e2m1_value(bytes[t] & 0xF);
+                    xv[32 * kg + 2 * t + 1] = e2m1_value(bytes[t] >> 4);
+                } else {
+                    xv[16 * kg + t] = e4m3_value(bytes[t]);
+                    xv[64 + 16 * kg + t] = e4m3_value(bytes[16 + t]);
+                }
             }
             xs[kg] = p.s_first == 0xFF ? NAN : std::ldexp(1.0, (int)p.s_first - 127);
         }

@@ -32,7 +32,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == ["mxfp8_copy_rate_probe", "mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex",
-                                    "mxfp8_fp4_dequantize_ex", "mxfp8_fp4_quantize_ex", "mxfp8_gemm", "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
+                                    "mxfp8_fp4_dequantize_ex", "mxfp8_fp4_quantize_ex", "mxfp8_gemm", "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_layout_probe", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
                                     "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_requantize_colwise_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
 
@@ -168,6 +168,15 @@ def test_requantize_validation_needs_no_gpu(lib):
     assert f(None, FAKE, 64, 64, FAKE, FAKE, 0, None) == 1 and f(FAKE, FAKE, 64, 64, FAKE, None, 0, None) == 1
     assert f(P(0x1004), FAKE, 64, 64, FAKE, FAKE, 0, None) == 3
     assert f(None, None, 0, 64, None, None, 0, None) == 0
+
+
+def test_layout_probe_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_mfma_layout_probe
+    f.argtypes = [P, P, P, P, ctypes.c_int32, ctypes.c_int32, P, P]
+    assert f(FAKE, FAKE, FAKE, FAKE, 1, 6, FAKE, None) == 5 and f(FAKE, FAKE, FAKE, FAKE, -1, 8, FAKE, None) == 2
+    assert f(FAKE, FAKE, FAKE, FAKE, (1 << 16) + 1, 4, FAKE, None) == 2 and f(FAKE, None, FAKE, FAKE, 1, 4, FAKE, None) == 1
+    assert f(P(0x1008), FAKE, FAKE, FAKE, 1, 8, FAKE, None) == 3 and f(FAKE, FAKE, P(0x1002), FAKE, 1, 8, FAKE, None) == 3
+    assert f(None, None, None, None, 0, 8, None, None) == 0
 
 
 def test_fp4_validation_needs_no_gpu(lib):

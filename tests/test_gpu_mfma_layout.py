@@ -1,0 +1,127 @@
+"""What the scaled 16x16x128 matrix instruction does with the registers it is given, for the two element widths
+the product kernels use. The kernels' fragment reads, their scale-byte reads and the CPU execution model of the
+instruction all rest on these facts, so they are pinned on the hardware itself rather than taken from memory:
+  8-bit elements: lane 16g+r holds row r; dwords 0..3 are K 16g..16g+15, dwords 4..7 K 64+16g..64+16g+15; the scale
+                  byte of lane (r, g) scales K block g of row r (whose data sits in other lanes);
+  4-bit elements: only dwords 0..3 count; lane 16g+r holds K 32g..32g+31 of row r and its own scale byte scales them;
+  both:           byte 0 of the scale register is used, the upper bytes are ignored; result register v of lane
+                  (r, g) is D[4g+v][r]."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_08027_amd as mx
+
+pytestmark = pytest.mark.gpu
+
+G = np.arange(64) // 16          # lane group
+R = np.arange(64) % 16           # row held by the lane
+ONE = {8: 0x38383838, 4: 0x22222222}   # a dword full of 1.0 codes (E4M3 0x38, E2M1 0x2)
+
+
+def _run(a, b, sa, sb, bits):
+    out = torch.empty((a.shape[0], 64, 4), dtype=torch.float32, device="cuda")
+    mx.mxfp8_mfma_layout_probe(*(torch.from_numpy(np.ascontiguousarray(t, dtype=np.int32)).cuda() for t in (a, b, sa, sb)), bits, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_which_scale_byte_meets_which_operand_register(bits):
+    """Data only in dword d of lane group g, all lanes' scales distinct powers of two: the result tells whose
+    scale was applied. Done for the first and for the second operand."""
+    ndw, per_dword = (8, 4) if bits == 8 else (4, 8)
+    X = 4 * ndw
+    ones = np.zeros((X, 64, 8), np.int32)
+    ones[:, :, :ndw] = ONE[bits]
+    picked = np.zeros((X, 64, 8), np.int32)
+    for g in range(4):
+        for d in range(ndw):
+            picked[g * ndw + d, G == g, d] = ONE[bits]
+    graded = np.tile(127 + 4 * G, (X, 1))
+    flat = np.full((X, 64), 127)
+    want = np.array([[(g // 2 + 2 * (d // 4)) if bits == 8 else g for d in range(ndw)] for g in range(4)])
+    for out in (_run(picked, ones, graded, flat, bits), _run(ones, picked, flat, graded, bits)):
+        out = out.reshape(4, ndw, 256)
+        assert (out == out[:, :, :1]).all()
+        assert np.array_equal(np.log2(out[:, :, 0] / per_dword) / 4, want)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_operand_registers_pair_up_and_results_land_where_the_kernels_expect(bits):
+    ndw = 8 if bits == 8 else 4
+    n = 4 * ndw
+    a = np.zeros((n * n, 64, 8), np.int32)
+    b = np.zeros((n * n, 64, 8), np.int32)
+    for p in range(n):
+        for q in range(n):
+            a[p * n + q, G == p // ndw, p % ndw] = ONE[bits]
+            b[p * n + q, G == q // ndw, q % ndw] = ONE[bits]
+    s = np.full((n * n, 64), 127)
+    meet = (_run(a, b, s, s, bits).reshape(n, n, -1) != 0).all(-1)
+    assert np.array_equal(meet, np.eye(n, dtype=bool))       # register (g, d) of A multiplies register (g, d) of B only
+    # one row of each operand: exactly one result register is nonzero, D[x][y] in register x % 4 of lane 16 (x / 4) + y
+    pairs = [(3, 7), (12, 1), (0, 0), (15, 15)]
+    a = np.zeros((len(pairs), 64, 8), np.int32)
+    b = np.zeros((len(pairs), 64, 8), np.int32)
+    for i, (x, y) in enumerate(pairs):
+        a[i, R == x, :ndw] = ONE[bits]
+        b[i, R == y, :ndw] = ONE[bits]
+    s = np.full((len(pairs), 64), 127)
+    out = _run(a, b, s, s, bits)
+    for i, (x, y) in enumerate(pairs):
+        assert np.argwhere(out[i] != 0).tolist() == [[16 * (x // 4) + y, x % 4]] and out[i, 16 * (x // 4) + y, x % 4] == 128.0
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_upper_bytes_of_the_scale_register_are_ignored(bits):
+    ndw = 8 if bits == 8 else 4
+    a = np.zeros((1, 64, 8), np.int32)
+    a[:, :, :ndw] = ONE[bits]
+    junk = np.full((1, 64), 127 | (130 << 8) | (140 << 16) | (90 << 24))
+    out = _run(a, a, junk, np.full((1, 64), 127), bits)
+    assert (out == 128.0).all()
+
+
+def test_random_registers_against_the_layout_written_out():
+    """Random finite codes and scales, both widths: the result is the block-scaled dot product with the K
+    assignment stated at the top, to FP32 accumulation error."""
+    rng = np.random.default_rng(3)
+    X = 8
+    e4m3 = np.array([0.0 if (c & 0x7F) == 0 else ((c & 7) / 8 * 2.0 ** -6 if ((c >> 3) & 15) == 0 else (1 + (c & 7) / 8) * 2.0 ** (((c >> 3) & 15) - 7))
+                     for c in range(128)])
+    e2m1 = np.array([0, 0.5, 1, 1.5, 2, 3, 4, 6], np.float64)
+    for bits in (8, 4):
+        a = rng.integers(0, 1 << 32, (X, 64, 8), dtype=np.uint64).astype(np.uint32)
+        b = rng.integers(0, 1 << 32, (X, 64, 8), dtype=np.uint64).astype(np.uint32)
+        if bits == 8:
+            a &= 0xF7F7F7F7                                   # exponent field below 15: no NaN code
+            b &= 0xF7F7F7F7
+        sa = rng.integers(120, 135, (X, 64))
+        sb = rng.integers(120, 135, (X, 64))
+        out = _run(a.view(np.int32), b.view(np.int32), sa, sb, bits)
+
+        def decode(regs, scales):
+            """[X x 64 x 8] registers -> values [X x 16 rows x 128 k] and per-block scale factors [X x 16 x 4]."""
+            by = regs.view(np.uint8).reshape(X, 4, 16, 32)   # [x][g][r][byte]
+            val = np.zeros((X, 16, 128))
+            for g in range(4):
+                if bits == 8:
+                    v = np.where(by[:, g] & 0x80, -1.0, 1.0) * e4m3[by[:, g] & 0x7F]
+                    val[:, :, 16 * g:16 * g + 16] = v[:, :, :16]
+                    val[:, :, 64 + 16 * g:64 + 16 * g + 16] = v[:, :, 16:]
+                else:
+                    lo, hi = by[:, g, :, :16] & 0xF, by[:, g, :, :16] >> 4
+                    v = np.stack([np.where(c & 8, -1.0, 1.0) * e2m1[c & 7] for c in (lo, hi)], -1).reshape(X, 16, 32)
+                    val[:, :, 32 * g:32 * g + 32] = v
+            sc = np.exp2(scales.reshape(X, 4, 16).transpose(0, 2, 1) - 127.0)    # [x][r][block g]
+            return val, sc
+
+        va, fa = decode(a, sa)
+        vb, fb = decode(b, sb)
+        wa = (va.reshape(X, 16, 4, 32) * fa[..., None]).reshape(X, 16, 128)
+        wb = (vb.reshape(X, 16, 4, 32) * fb[..., None]).reshape(X, 16, 128)
+        D = np.einsum("xik,xjk->xij", wa, wb)
+        absum = np.einsum("xik,xjk->xij", np.abs(wa), np.abs(wb))
+        got = out.reshape(X, 4, 16, 4).transpose(0, 1, 3, 2).reshape(X, 16, 16)       # [x][g][r][v] -> D[4g+v][r]
+        assert (np.abs(got - D) <= 2.0 ** -21 * absum + 1e-30).all(), bits

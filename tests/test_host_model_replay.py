@@ -78,3 +78,10 @@ def test_fp4_gpu_tests_pass_on_the_host_model(hostmodel_lib):
     """MXFP4 conversion; the full-size case is left to the GPU."""
     n = replay(hostmodel_lib, ["test_gpu_fp4.py"], "not full_size")
     assert n >= 12
+
+
+def test_matrix_instruction_layout_tests_pass_on_the_host_model(hostmodel_lib):
+    """The facts about the scaled matrix instruction that the GPU test pins on the hardware hold for the CPU
+    model of the instruction as well: the two cannot drift apart."""
+    n = replay(hostmodel_lib, ["test_gpu_mfma_layout.py"], "layout or scale or operand")
+    assert n >= 7
