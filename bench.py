@@ -26,7 +26,8 @@ per compute unit) on the same tensor under the same rotation, `torch_copy_gbs` t
 `fused_output_quantization` times the forward product with the MXFP8 copies of Y emitted from its epilogue
 against the product followed by a stand-alone quantize of Y; `simulated_path` times the BF16 product of the
 round-tripped operands (Section 3.1) against the BF16 matrix peak; `grouped_moe` times the grouped forward
-product of a mixture-of-experts layer (Appendix A.4).
+product of a mixture-of-experts layer (Appendix A.4); `mxfp4_path` times the MXFP4 conversion of X and the forward
+product on MXFP4 operands (Table 1) against the 4-bit matrix peak.
 `layer_set_16384` times the three products of each linear layer of an 8B-class transformer block at
 16384 tokens. `cpu_baseline` times the CPU oracle on a bounded sample.
 """
@@ -49,6 +50,7 @@ T, H, O = 8192, 4096, 14336
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP8_PEAK_TFLOPS = 5000.0  # dense FP8 / MX-FP8 matrix peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense BF16 matrix peak
+MFMA_FP4_PEAK_TFLOPS = 10100.0  # dense FP4 / FP6 matrix peak
 
 
 def _ensure_built():
@@ -329,6 +331,18 @@ def main():
         return {"requantize_ms": ms, "requantize_gbs": T * H * 2 * (1 + 1 / 32) / (ms * 1e-3) / 1e9,
                 "colwise_quantize_from_bf16_ms": ms_src}
 
+    def mxfp4_path():
+        """Table 1's narrower format on the same layer: X and W converted to MXFP4 (row copies; X also timed with both
+        copies) and the forward product on the 4-bit form of the scaled matrix instruction (dense peak 10.1 PFLOP/s)."""
+        xq = mx.fp4_quantize(X, "both", lay)
+        wq = mx.fp4_quantize(W, "rowwise", lay)
+        ms = ms_avg(lambda: mx.mxfp8_fp4_gemm_ex(mx.FPROP, xq["q_row"], xq["s_row"], wq["q_row"], wq["s_row"], Y, lay))
+        q_ms = ms_avg(lambda: mx.mxfp8_fp4_quantize_ex(X, mx.BOTH, xq["q_row"], xq["s_row"], xq["q_colT"], xq["s_colT"], lay))
+        tf = gemm_flop / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": tf, "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_FP4_PEAK_TFLOPS,
+                "kernel": f"gemm_persistent_kernel, MXFP4 operands (fprop {T}x{O}x{H}, BF16 out)", "avg_ms": ms, "launches": 20,
+                "quantize_X_both_ms": q_ms, "quantize_X_both_gbs": T * H * (2 + 2 * (0.5 + 1 / 32)) / (q_ms * 1e-3) / 1e9}
+
     def sustained_mfma_tflops():
         """What the matrix pipes of this GPU sustain on the scaled FP8 instruction alone (operands in registers,
         pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling a GEMM
@@ -377,7 +391,8 @@ def main():
         extras["quant_bf16"] = (q_ms, q_fp, 160, rotating_copy_gbs(X, 8, 160))
         extras["quant_f32"] = (f_ms, f_fp, 100, rotating_copy_gbs(dY, 2, 100))
         for key, fn in (("fused_output_quantization", fused_output_quantization), ("simulated_path", simulated_path),
-                        ("grouped_moe", grouped_moe), ("single_copy", single_copy), ("layer_set", layer_set)):
+                        ("grouped_moe", grouped_moe), ("single_copy", single_copy), ("mxfp4_path", mxfp4_path),
+                        ("layer_set", layer_set)):
             try:
                 extras[key] = fn()
             except Exception as exc:   # the headline measurement must survive a problem in an extra one
@@ -433,7 +448,7 @@ def main():
                         "plain_copy_gbs": copy_gbs[0], "frac_of_plain_copy": gbs / copy_gbs[0], "torch_copy_gbs": copy_gbs[1]}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
-    for key in ("fused_output_quantization", "simulated_path", "grouped_moe", "single_copy"):
+    for key in ("fused_output_quantization", "simulated_path", "grouped_moe", "single_copy", "mxfp4_path"):
         if key in extras:
             out[key] = extras[key]
     if "layer_set" in extras:

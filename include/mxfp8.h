@@ -304,6 +304,20 @@ mxfp8_status mxfp8_fp4_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t
                                      void *hip_stream);
 
 /*
+ * mxfp8_gemm_ex for MXFP4 operands (Table 1; the sum of Section 2 and Appendix A.3 with E2M1 elements):
+ *   C[m, n] = sum over blocks b of 2^(a_s[m,b] + b_s[n,b] - 254) * sum_{i<32} A[m,32b+i] * B[n,32b+i]
+ * with a_q [M x K/2], b_q [N x K/2] packed as mxfp8_fp4_quantize_ex writes them, a_s [M x K/32], b_s [N x K/32] in
+ * `scale_layout`, FP32 accumulation on the 4-bit form of the scaled matrix instruction. `pass` only names the
+ * operands (same table as mxfp8_gemm). Requirements: K % 256 == 0 (one K step of the kernels is 128 operand
+ * bytes); everything else (alignment, ldc, zero sizes, limits, max_workgroups, NaN through a 0xFF scale) as in
+ * mxfp8_gemm_ex. E2M1 has no NaN or Inf code: only a scale byte can make an output NaN.
+ */
+mxfp8_status mxfp8_fp4_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q,
+                               const uint8_t *b_s, int64_t M, int64_t N, int64_t K, void *c, mxfp8_dtype c_dtype,
+                               int64_t ldc, mxfp8_scale_layout scale_layout, int32_t max_workgroups,
+                               void *hip_stream);
+
+/*
  * Measurement aid for benchmarks (no operation of the paper): `workgroups` workgroups of 4 wavefronts each
  * issue iterations * 64 independent scaled FP8 matrix instructions (16x16x128, 65536 flop each) on register
  * operands, without memory traffic, and then store one float per work-item to sink[workgroups * 256]

@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_fp4_quantize_ex.restype = ci
     lib.mxfp8_fp4_dequantize_ex.argtypes = [vp, vp, i64, i64, vp, ci, i64, ci, vp]
     lib.mxfp8_fp4_dequantize_ex.restype = ci
+    lib.mxfp8_fp4_gemm_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, ci, ctypes.c_int32, vp]
+    lib.mxfp8_fp4_gemm_ex.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_copy_rate_probe.restype = ci
     lib.mxfp8_mfma_layout_probe.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp]
@@ -400,6 +402,29 @@ def mxfp8_fp4_dequantize_ex(q, s, dst, scale_layout=SCALES_ROWMAJOR, stream=None
         raise MXFP8Error(rc, "mxfp8_fp4_dequantize_ex")
 
 
+def mxfp8_fp4_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, max_workgroups=0, stream=None) -> None:
+    """c [M x N] (float32/bfloat16) = A . B^T for MXFP4 operands a_q [M x K/2], b_q [N x K/2] (packed E2M1 codes) with
+    block scales [. x K/32] in `scale_layout`."""
+    _need_cuda(a_q, a_s, b_q, b_s, c)
+    M, Kh = a_q.shape
+    N, Kb = b_q.shape
+    if Kh != Kb:
+        raise ValueError("operand shapes disagree")
+    K = 2 * Kh
+    _check_scales(a_s, M, K, scale_layout, "a_s")
+    _check_scales(b_s, N, K, scale_layout, "b_s")
+    if tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
+        raise ValueError("c must be [M x N] with contiguous rows")
+    for t in (a_q, a_s, b_q, b_s):
+        if not t.is_contiguous() or t.dtype != torch.uint8:
+            raise ValueError("quantized operands must be dense uint8")
+    ldc = c.stride(0) if M > 1 else max(N, 1)
+    rc = load().mxfp8_fp4_gemm_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), M, N, K, _ptr(c),
+                                  _dtype_code(c.dtype), ldc, scale_layout, max_workgroups, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_fp4_gemm_ex")
+
+
 # ---- conveniences that only allocate the outputs ----------------------------------------------
 
 def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR, element=E4M3, rule=SCALE_ROUND_UP):
@@ -504,3 +529,9 @@ def fp4_dequantize(q, s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):
     dst = torch.empty((q.shape[0], q.shape[1] * 2), dtype=out_dtype, device=q.device)
     mxfp8_fp4_dequantize_ex(q, s, dst, scale_layout)
     return dst
+
+
+def fp4_gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
+    c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
+    mxfp8_fp4_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout, max_workgroups)
+    return c

@@ -28,24 +28,32 @@ namespace mxfp8 {
 constexpr int BK = 128;  // K bytes per step = 4 scale blocks = one MFMA
 constexpr int kStageBytes = 4608;  // per-wavefront LDS area of the persistent kernel's epilogue (16 rows x (256 + 32) bytes)
 
-// SCALED: MXFP8 operands with their scale bytes (the method itself); otherwise plain BF16 operands, 64 per
-// 128-byte K step, no scales (the product of the simulated path of Section 3.1). Everything about tiles,
-// buffers, requests and the schedule is counted in BYTES of a K-contiguous operand row and is the same.
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool SCALED_ = true> struct GemmCfg {
+// Operand formats. kFmtFp8: MXFP8 operands with their scale bytes (the method itself), 128 elements and 4 scale
+// blocks per 128-byte K step. kFmtBf16: plain BF16 operands, 64 per K step, no scales (the product of the
+// simulated path of Section 3.1). kFmtFp4: MXFP4 operands (Table 1), two E2M1 codes per byte: 256 elements and
+// 8 scale blocks (two scale dwords per row) per K step. Everything about tiles, buffers, data requests and the
+// schedule is counted in BYTES of a K-contiguous operand row and is the same for all three.
+constexpr int kFmtFp8 = 0, kFmtBf16 = 1, kFmtFp4 = 2;
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int FMT_ = kFmtFp8> struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-    static constexpr bool SCALED = SCALED_;
+    static constexpr int FMT = FMT_;
+    static constexpr bool SCALED = FMT_ != kFmtBf16;
+    static constexpr int SDW = FMT_ == kFmtFp4 ? 2 : 1;     // scale dwords per operand row and K step
+    static constexpr int SBLK = FMT_ == kFmtFp4 ? 16 : 32;  // operand bytes per scale block
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile
     static constexpr int TM = WM / 16, TN = WN / 16;            // MFMA tiles per wavefront
     static constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
-    // LDS map: A[2] | B[2] | A scales[2] (one dword = 4 scale bytes per row) | B scales[2]
-    static constexpr int A_OFF = 0, B_OFF = 2 * A_BYTES, SA_OFF = B_OFF + 2 * B_BYTES, SB_OFF = SA_OFF + 2 * BM * 4;
-    static constexpr int LDS_BYTES = SB_OFF + 2 * BN * 4;
+    // LDS map: A[2] | B[2] | A scales[2] | B scales[2]; a scale buffer holds, for each of the SDW scale dwords of
+    // a K step, one dword (4 scale bytes) per tile row: [dword][row][4]
+    static constexpr int SA_BYTES = BM * 4 * SDW, SB_BYTES = BN * 4 * SDW;
+    static constexpr int A_OFF = 0, B_OFF = 2 * A_BYTES, SA_OFF = B_OFF + 2 * B_BYTES, SB_OFF = SA_OFF + 2 * SA_BYTES;
+    static constexpr int LDS_BYTES = SB_OFF + 2 * SB_BYTES;
     static constexpr int LDS_BYTES_PERSISTENT = LDS_BYTES + WAVES * kStageBytes;  // + the epilogue's staging areas
     // one direct-to-LDS instruction moves 8 rows x 128 bytes (or 64 scale dwords) per wavefront
     static constexpr int A_LOADS = BM / 8 / WAVES, B_LOADS = BN / 8 / WAVES;
-    static constexpr int SA_LOADS = SCALED ? (BM / 64 + WAVES - 1) / WAVES : 0, SB_LOADS = SCALED ? (BN / 64 + WAVES - 1) / WAVES : 0;
+    static constexpr int SA_LOADS = SCALED ? SDW * ((BM / 64 + WAVES - 1) / WAVES) : 0, SB_LOADS = SCALED ? SDW * ((BN / 64 + WAVES - 1) / WAVES) : 0;
     static constexpr int NA = A_LOADS + SA_LOADS, NB = B_LOADS + SB_LOADS;  // DMA slots per step
     static_assert(BM % (8 * WAVES) == 0 && BN % (8 * WAVES) == 0, "tile rows per wavefront");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "scale rows per instruction");
@@ -85,13 +93,22 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
 
 // One K step of one 16x16 output tile. MXFP8: one scaled matrix instruction over 128 k (4 blocks per
 // operand row, scale byte 0 of each lane's scale register). BF16: the lane's two 16-byte pieces are k
-// 8g..8g+7 and 32+8g..32+8g+7 of the row's 64 values: two 16x16x32 instructions.
+// 8g..8g+7 and 32+8g..32+8g+7 of the row's 64 values: two 16x16x32 instructions. MXFP4: the lane's two
+// 16-byte pieces are scale blocks g and 4+g of the row's 8 (with 4-bit elements a lane holds one whole block
+// and its own scale byte applies to it): two scaled instructions over 128 k each; the scale registers carry
+// the byte of block g in bits 7:0 and that of block 4+g in bits 15:8.
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-template <bool SCALED>
+template <int FMT>
 __device__ __forceinline__ v4f mma_step(const v8i &first, const v8i &second, v4f acc, int s_first, int s_second)
 {
-    if constexpr (SCALED) {
+    if constexpr (FMT == kFmtFp8) {
         return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(first, second, acc, 0, 0, 0, s_first, 0, s_second);
+    } else if constexpr (FMT == kFmtFp4) {
+        const v8i f0 = {first[0], first[1], first[2], first[3], 0, 0, 0, 0}, f1 = {first[4], first[5], first[6], first[7], 0, 0, 0, 0};
+        const v8i s0 = {second[0], second[1], second[2], second[3], 0, 0, 0, 0}, s1 = {second[4], second[5], second[6], second[7], 0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(f0, s0, acc, 4, 4, 0, s_first & 0xFF, 0, s_second & 0xFF);
+        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(f1, s1, acc, 4, 4, 0, (int)((uint32_t)s_first >> 8), 0,
+                                                                (int)((uint32_t)s_second >> 8));
     } else {
         const v4i f0 = {first[0], first[1], first[2], first[3]}, f1 = {first[4], first[5], first[6], first[7]};
         const v4i s0 = {second[0], second[1], second[2], second[3]}, s1 = {second[4], second[5], second[6], second[7]};
@@ -107,6 +124,18 @@ struct GemmGroups {
     int count;
     int64_t b_group_bytes, bs_group_bytes;
 };
+
+// Scale register of one fragment from a scale buffer in LDS ([dword][row][4], `rows` tile rows): MXFP8 takes the
+// byte of the lane's K block, MXFP4 the bytes of blocks g and 4+g (same position in the two dwords of the row).
+template <class Cfg> __device__ __forceinline__ int read_scale(const uint8_t *sbuf, int off, int rows)
+{
+    if constexpr (Cfg::FMT == kFmtFp4)
+        return (int)sbuf[off] | ((int)sbuf[rows * 4 + off] << 8);
+    else if constexpr (Cfg::FMT == kFmtFp8)
+        return sbuf[off];
+    else
+        return 0;
+}
 
 // The kernel. LDS holds two A buffers, two B buffers and their scale dwords; the software pipeline
 // is described at the step lambda below.
@@ -149,8 +178,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     }
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     // K is the length of an operand row in BYTES (= elements for MXFP8, 2 x elements for BF16 operands)
-    const int nkb = K / kBlock;  // scale bytes per row
-    const int KT = k_len / BK;   // steps of this workgroup
+    static_assert(!KGROUPED || Cfg::FMT == kFmtFp8, "grouped products take MXFP8 operands");
+    const int nkb = K / Cfg::SBLK;  // scale bytes per row
+    const int KT = k_len / BK;      // steps of this workgroup
     const int KT_row = K / BK;   // steps in a whole operand row (the pitch of the tiled scale layout)
 
     // ---- global -> LDS addressing: wavefront w owns 8-row groups w*LOADS.. of each tile; one
@@ -171,14 +201,18 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         const int chunk = ld_c ^ ((row >> 1) & 7);
         b_goff[i] = (uint32_t)min(row, N - 1 - n0) * (uint32_t)K + chunk * 16;
     }
+    // scale request i of a wavefront: scale dword i % SDW of the K step, for 64-row group a_grp(i) / b_grp(i)
+    constexpr int SDW = Cfg::SDW;
+    auto a_grp = [&](int i) __attribute__((always_inline)) { return (wave + (i / SDW) * Cfg::WAVES) % (Cfg::BM / 64); };
+    auto b_grp = [&](int i) __attribute__((always_inline)) { return (wave + (i / SDW) * Cfg::WAVES) % (Cfg::BN / 64); };
 #pragma unroll
     for (int i = 0; i < Cfg::SA_LOADS; ++i)
-        as_goff[i] = (uint32_t)min(((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 64 + lane, M - 1 - m0) * (uint32_t)nkb;
+        as_goff[i] = (uint32_t)min(a_grp(i) * 64 + lane, M - 1 - m0) * (uint32_t)nkb;
 #pragma unroll
     for (int i = 0; i < Cfg::SB_LOADS; ++i)
-        bs_goff[i] = (uint32_t)min(((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 64 + lane, N - 1 - n0) * (uint32_t)nkb;
+        bs_goff[i] = (uint32_t)min(b_grp(i) * 64 + lane, N - 1 - n0) * (uint32_t)nkb;
     const uint8_t *a_tile = a_q + (int64_t)m0 * K + k0, *b_tile = b_q + (int64_t)n0 * K + k0;
-    const uint8_t *as_tile = a_s + (int64_t)m0 * nkb + k0 / kBlock, *bs_tile = b_s + (int64_t)n0 * nkb + k0 / kBlock;
+    const uint8_t *as_tile = a_s + (int64_t)m0 * nkb + k0 / Cfg::SBLK, *bs_tile = b_s + (int64_t)n0 * nkb + k0 / Cfg::SBLK;
     // Tiled scales: the 64 dwords of a (64-row group, K step) are contiguous, so the instruction that
     // reads one cache line per lane from row-major scales reads 256 consecutive bytes here. A ragged
     // last tile re-reads the last valid group: its rows are never stored.
@@ -186,10 +220,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     if constexpr (TILED) {
 #pragma unroll
         for (int i = 0; i < Cfg::SA_LOADS; ++i)
-            as_grp[i] = a_s + ((int64_t)min(m0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BM / 64), (M + 63) / 64 - 1) * KT_row + k0 / BK) * 256;
+            as_grp[i] = a_s + ((int64_t)min(m0 / 64 + a_grp(i), (M + 63) / 64 - 1) * KT_row + k0 / BK) * (256 * SDW);
 #pragma unroll
         for (int i = 0; i < Cfg::SB_LOADS; ++i)
-            bs_grp[i] = b_s + ((int64_t)min(n0 / 64 + (wave + i * Cfg::WAVES) % (Cfg::BN / 64), (N + 63) / 64 - 1) * KT_row + k0 / BK) * 256;
+            bs_grp[i] = b_s + ((int64_t)min(n0 / 64 + b_grp(i), (N + 63) / 64 - 1) * KT_row + k0 / BK) * (256 * SDW);
     }
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
 
@@ -202,12 +236,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
             const int i = t - Cfg::A_LOADS;
             // every wavefront issues the same number of requests (the wait counts rely on it):
             // with fewer 64-row groups than wavefronts some groups are simply fetched twice
+            const int dw = i % SDW;
             if constexpr (TILED)
-                dma_load<4>(as_grp[i] + (int64_t)kt * 256, lane * 4,
-                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);
+                dma_load<4>(as_grp[i] + ((int64_t)kt * SDW + dw) * 256, lane * 4,
+                            lds_base + Cfg::SA_OFF + buf * Cfg::SA_BYTES + dw * Cfg::BM * 4 + a_grp(i) * 256);
             else
-                dma_load<4>(as_tile + kt * 4, as_goff[i],
-                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);
+                dma_load<4>(as_tile + (kt * SDW + dw) * 4, as_goff[i],
+                            lds_base + Cfg::SA_OFF + buf * Cfg::SA_BYTES + dw * Cfg::BM * 4 + a_grp(i) * 256);
         }
     };
     auto issue_b = [&](int t, int kt, int buf) __attribute__((always_inline)) {
@@ -216,12 +251,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
                          lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
         } else if (t < Cfg::NB) {
             const int i = t - Cfg::B_LOADS;
+            const int dw = i % SDW;
             if constexpr (TILED)
-                dma_load<4>(bs_grp[i] + (int64_t)kt * 256, lane * 4,
-                            lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 256);
+                dma_load<4>(bs_grp[i] + ((int64_t)kt * SDW + dw) * 256, lane * 4,
+                            lds_base + Cfg::SB_OFF + buf * Cfg::SB_BYTES + dw * Cfg::BN * 4 + b_grp(i) * 256);
             else
-                dma_load<4>(bs_tile + kt * 4, bs_goff[i],
-                            lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BN / 64)) * 256);
+                dma_load<4>(bs_tile + (kt * SDW + dw) * 4, bs_goff[i],
+                            lds_base + Cfg::SB_OFF + buf * Cfg::SB_BYTES + dw * Cfg::BN * 4 + b_grp(i) * 256);
         }
     };
 
@@ -271,8 +307,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         // past the end of K the prefetches fetch the last step again into buffers nobody reads any
         // more: every step runs the same branch-free code and the wait counts stay valid
         const int kt1 = min(kt + 1, KT - 1), kt2 = min(kt + 2, KT - 1);
-        const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
-        const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::BM * 4;
+        const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::SB_BYTES;
+        const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::SA_BYTES;
         // B fragments stream through NFB register sets, fetched NFB-1 columns ahead of their use
         constexpr int NFB = 3;
         v8i fb[NFB];
@@ -280,7 +316,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 #pragma unroll
         for (int j = 0; j < NFB - 1 && j < TN; ++j) {
             fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
-            sb[j] = Cfg::SCALED ? sbbuf[b_soff + j * 64] : 0;
+            sb[j] = read_scale<Cfg>(sbbuf, b_soff + j * 64, Cfg::BN);
         }
         MXFP8_PIN();
         int a_slot = 0;  // compile-time after unrolling
@@ -288,7 +324,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
         for (int j = 0; j < TN; ++j) {
             if (j + NFB - 1 < TN) {
                 fb[(j + NFB - 1) % NFB] = read_frag(bbuf, b_off0 + (j + NFB - 1) * 2048, b_off1 + (j + NFB - 1) * 2048);
-                sb[(j + NFB - 1) % NFB] = Cfg::SCALED ? sbbuf[b_soff + (j + NFB - 1) * 64] : 0;
+                sb[(j + NFB - 1) % NFB] = read_scale<Cfg>(sbbuf, b_soff + (j + NFB - 1) * 64, Cfg::BN);
             }
             if (j == TN - 1) {
                 MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);  // all but this step's requests: A(kt+1) is in LDS
@@ -297,7 +333,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
             MXFP8_PIN();
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                acc[i][j] = mma_step<Cfg::SCALED>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
+                acc[i][j] = mma_step<Cfg::FMT>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
                 MXFP8_PIN();
                 if (j == 0) {
                     issue_b(i, kt1, nxt);
@@ -310,7 +346,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
                 }
                 if (j == TN - 1) {
                     fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
-                    sa[i] = Cfg::SCALED ? sanext[a_soff + i * 64] : 0;
+                    sa[i] = read_scale<Cfg>(sanext, a_soff + i * 64, Cfg::BM);
                 }
                 MXFP8_PIN();
             }
@@ -334,7 +370,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
-            sa[i] = Cfg::SCALED ? (lds + Cfg::SA_OFF)[a_soff + i * 64] : 0;
+            sa[i] = read_scale<Cfg>(lds + Cfg::SA_OFF, a_soff + i * 64, Cfg::BM);
         }
         __syncthreads();  // A buffer 0 is refilled by the requests of step 0 from here on
     }
@@ -425,12 +461,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     int tiles_m, int tiles_n, uint8_t *__restrict__ cq, uint8_t *__restrict__ cs, uint8_t *__restrict__ cqT,
     uint8_t *__restrict__ csT, GemmGroups groups)
 {
-    static_assert(!GROUPED || (FUSE_Q == 0 && Cfg::SCALED), "grouped products: MXFP8 operands, plain epilogue");
+    static_assert(!GROUPED || (FUSE_Q == 0 && Cfg::FMT == kFmtFp8), "grouped products: MXFP8 operands, plain epilogue");
     static_assert(!FUSE_Q || (OUT_BF16 && (Cfg::TN == 8 || Cfg::TN == 4) && Cfg::TM == Cfg::TN), "fused output quantization");
     constexpr bool Q_ROW = (FUSE_Q & 1) != 0, Q_COL = (FUSE_Q & 2) != 0;
     static_assert(!Q_COL || Cfg::BM * Cfg::BN <= 2 * Cfg::B_BYTES, "transposed tile fits the two idle buffers");
-    static_assert(!Cfg::SCALED || (Cfg::SA_LOADS == 1 && Cfg::SB_LOADS == 1), "one scale request per wavefront and operand");
-    static_assert(Cfg::SCALED || FUSE_Q == 0, "output quantization belongs to the MXFP8 product");
+    static_assert(!Cfg::SCALED || (Cfg::SA_LOADS == Cfg::SDW && Cfg::SB_LOADS == Cfg::SDW), "one scale request per wavefront, operand and scale dword");
+    static_assert(Cfg::FMT == kFmtFp8 || FUSE_Q == 0, "output quantization belongs to the MXFP8 product");
     MXFP8_DYNAMIC_LDS(lds);
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     const int tid = threadIdx.x;
@@ -438,7 +474,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
     const int r16 = lane & 15, g = lane >> 4;
-    const int nkb = K / kBlock;
+    constexpr int SDW = Cfg::SDW;
+    const int nkb = K / Cfg::SBLK;
     const int KT = K / BK;
     int ntiles = tiles_m * tiles_n;
     if constexpr (GROUPED) {
@@ -467,7 +504,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     }
     const int grp = wave % (Cfg::BM / 64);  // 64-row group of each tile whose scale dwords this wavefront fetches
     const uint32_t sgoff = TILED ? lane * 4 : (uint32_t)(grp * 64 + lane) * (uint32_t)nkb;
-    const int s_step = TILED ? 256 : 4;  // bytes from the scale dwords of one K step to the next
+    const int s_step = (TILED ? 256 : 4) * SDW;  // bytes from the scale dwords of one K step to the next
+    constexpr int s_dword = TILED ? 256 : 4;     // ... and from one scale dword of a K step to its next one
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
 
     // operand pointers of a tile at K step 0 (wavefront-uniform)
@@ -512,8 +550,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         if constexpr (TILED) {
             // (grouped: group starts are multiples of 64 rows; 64-row groups past the end of A re-read the last one)
             const int ag = GROUPED ? min(t.m0 / 64 + grp, (M + 63) / 64 - 1) : t.m0 / 64 + grp;
-            t.as = a_s + (int64_t)ag * KT * 256;
-            t.bs = bsc + (int64_t)(t.n0 / 64 + grp) * KT * 256;
+            t.as = a_s + (int64_t)ag * KT * (256 * SDW);
+            t.bs = bsc + (int64_t)(t.n0 / 64 + grp) * KT * (256 * SDW);
         } else {
             t.as = a_s + (int64_t)t.m0 * nkb;
             t.bs = bsc + (int64_t)t.n0 * nkb;
@@ -534,14 +572,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             uint32_t off = sgoff;
             if constexpr (GROUPED && !TILED)
                 off -= (uint32_t)max(grp * 64 + lane - lim, 0) * (uint32_t)nkb;
-            dma_load<4>(ssrc, off, lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + grp * 256);
+            const int dw = t - Cfg::A_LOADS;
+            dma_load<4>(ssrc + dw * s_dword, off, lds_base + Cfg::SA_OFF + buf * Cfg::SA_BYTES + dw * Cfg::BM * 4 + grp * 256);
         }
     };
     auto issue_b = [&](int t, const uint8_t *src, const uint8_t *ssrc, int buf) __attribute__((always_inline)) {
         if (t < Cfg::B_LOADS)
             dma_load<16>(src, goff[t], lds_base + Cfg::B_OFF + buf * Cfg::B_BYTES + (wave * Cfg::B_LOADS + t) * 1024);
         else if (t < Cfg::NB)
-            dma_load<4>(ssrc, sgoff, lds_base + Cfg::SB_OFF + buf * Cfg::BN * 4 + grp * 256);
+            dma_load<4>(ssrc + (t - Cfg::B_LOADS) * s_dword, sgoff,
+                        lds_base + Cfg::SB_OFF + buf * Cfg::SB_BYTES + (t - Cfg::B_LOADS) * Cfg::BN * 4 + grp * 256);
     };
 
     const int a_row = wm * Cfg::WM + r16, b_row = wn * Cfg::WN + r16;
@@ -571,15 +611,15 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     auto step = [&](int cur, const uint8_t *b_src, const uint8_t *bs_src, const uint8_t *a_src,
                     const uint8_t *as_src, int a_lim) __attribute__((always_inline)) {
         const int nxt = cur ^ 1;
-        const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::BN * 4;
-        const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::BM * 4;
+        const uint8_t *bbuf = lds + Cfg::B_OFF + cur * Cfg::B_BYTES, *sbbuf = lds + Cfg::SB_OFF + cur * Cfg::SB_BYTES;
+        const uint8_t *anext = lds + Cfg::A_OFF + nxt * Cfg::A_BYTES, *sanext = lds + Cfg::SA_OFF + nxt * Cfg::SA_BYTES;
         constexpr int NFB = 3;  // B fragment register sets, read NFB-1 columns ahead
         v8i fb[NFB];
         int sb[NFB];
 #pragma unroll
         for (int j = 0; j < NFB - 1 && j < TN; ++j) {
             fb[j] = read_frag(bbuf, b_off0 + j * 2048, b_off1 + j * 2048);
-            sb[j] = Cfg::SCALED ? sbbuf[b_soff + j * 64] : 0;
+            sb[j] = read_scale<Cfg>(sbbuf, b_soff + j * 64, Cfg::BN);
         }
         MXFP8_PIN();
         int a_slot = 0;
@@ -587,7 +627,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
         for (int j = 0; j < TN; ++j) {
             if (j + NFB - 1 < TN) {
                 fb[(j + NFB - 1) % NFB] = read_frag(bbuf, b_off0 + (j + NFB - 1) * 2048, b_off1 + (j + NFB - 1) * 2048);
-                sb[(j + NFB - 1) % NFB] = Cfg::SCALED ? sbbuf[b_soff + (j + NFB - 1) * 64] : 0;
+                sb[(j + NFB - 1) % NFB] = read_scale<Cfg>(sbbuf, b_soff + (j + NFB - 1) * 64, Cfg::BN);
             }
             if (j == TN - 1) {
                 MXFP8_WAIT_VMCNT(Cfg::NA + Cfg::NB);
@@ -596,7 +636,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             MXFP8_PIN();
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                acc[i][j] = mma_step<Cfg::SCALED>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
+                acc[i][j] = mma_step<Cfg::FMT>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
                 MXFP8_PIN();
                 if constexpr (SPREAD) {
                     // SCHED = 100 * gap + 10 * A spacing + B spacing (in MFMAs)
@@ -619,7 +659,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
                 }
                 if (j == TN - 1) {
                     fa[i] = read_frag(anext, a_off0 + i * 2048, a_off1 + i * 2048);
-                    sa[i] = Cfg::SCALED ? sanext[a_soff + i * 64] : 0;
+                    sa[i] = read_scale<Cfg>(sanext, a_soff + i * 64, Cfg::BM);
                 }
                 MXFP8_PIN();
             }
@@ -646,7 +686,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         fa[i] = read_frag(lds + Cfg::A_OFF, a_off0 + i * 2048, a_off1 + i * 2048);
-        sa[i] = Cfg::SCALED ? (lds + Cfg::SA_OFF)[a_soff + i * 64] : 0;
+        sa[i] = read_scale<Cfg>(lds + Cfg::SA_OFF, a_soff + i * 64, Cfg::BM);
     }
     __syncthreads();
 
@@ -934,6 +974,14 @@ template <class Cfg> constexpr bool spread_fits()
 {
     return 2 * Cfg::NB + 2 + 4 * (Cfg::NA - 1) < (Cfg::TN - 1) * Cfg::TM;
 }
+// The schedule of a configuration: the default spacing where it fits, else (two more requests per operand
+// with MXFP4's second scale dword) A requests behind every 3rd MFMA pair, else bursts (0).
+template <class Cfg> constexpr int sched_for()
+{
+    if (spread_fits<Cfg>())
+        return MXFP8_GEMM_SCHED;
+    return 2 * Cfg::NB + 2 + 3 * (Cfg::NA - 1) < (Cfg::TN - 1) * Cfg::TM ? 232 : 0;
+}
 
 template <class Cfg, bool OUT_BF16, bool TILED>
 static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
@@ -950,7 +998,8 @@ static hipError_t launch_cfg(const uint8_t *a_q, const uint8_t *a_s, const uint8
         hipError_t e = persistent_grid(tiles_m * tiles_n, max_workgroups, grid);
         if (e != hipSuccess)
             return e;
-        auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED, spread_fits<Cfg>()>;
+        constexpr int sched = sched_for<Cfg>();
+        auto kern = gemm_persistent_kernel<Cfg, OUT_BF16, TILED, sched != 0, 0, sched != 0 ? sched : MXFP8_GEMM_SCHED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 Cfg::LDS_BYTES_PERSISTENT);
         if (e != hipSuccess)
@@ -1086,14 +1135,31 @@ hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uin
 #undef MXFP8_GROUPED
 }
 
+// Product of two MXFP4 operands (Table 1: E2M1 elements, two per byte), [M x K/2] and [N x K/2] bytes with K/32
+// scale bytes per row: the same block-scaled sum (Section 2, Appendix A.3) on the 4-bit form of the scaled matrix
+// instruction. K is counted in elements here and in bytes inside the kernels.
+hipError_t launch_gemm_fp4(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
+                           int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc, int max_workgroups,
+                           hipStream_t stream)
+{
+    using Big = GemmCfg<256, 256, 2, 2, kFmtFp4>;
+    using Small = GemmCfg<128, 128, 2, 2, kFmtFp4>;
+    const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
+    if (big)
+        return launch_any<Big>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)(K / 2), c, c_bf16, tiled_scales, ldc, max_workgroups,
+                               stream);
+    return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)(K / 2), c, c_bf16, tiled_scales, ldc, max_workgroups,
+                             stream);
+}
+
 // Product of two BF16 operands, [M x K] and [N x K], both K-contiguous, FP32 accumulation: the GEMM of the
 // simulated path (Section 3.1). Same kernels as the MXFP8 product with the BF16 matrix instruction and no
 // scales; K is counted in elements here and in bytes inside the kernels.
 hipError_t launch_gemm_bf16(const uint8_t *a, const uint8_t *b, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
                             int64_t ldc, int max_workgroups, hipStream_t stream)
 {
-    using Big = GemmCfg<256, 256, 2, 2, false>;
-    using Small = GemmCfg<128, 128, 2, 2, false>;
+    using Big = GemmCfg<256, 256, 2, 2, kFmtBf16>;
+    using Small = GemmCfg<128, 128, 2, 2, kFmtBf16>;
     const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
     const uint8_t *none = nullptr;
     const int m = (int)M, n = (int)N, kbytes = (int)(2 * K);

@@ -319,6 +319,24 @@ int main(int argc, char **argv)
             unchanged(sb, "s");
             report(st);
             save(out, o);
+        } else if (op == "gemmfp4") {
+            int pass;
+            long M, N, K, ldc;
+            std::string dt, aq, as, bq, bs, cout;
+            ls >> pass >> M >> N >> K >> dt >> ldc >> aq >> as >> bq >> bs >> cout;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf a = load(aq, (size_t)M * K / 2), sa = load(as, (size_t)mxfp8_scale_bytes(M, K, lay));
+            Buf b = load(bq, (size_t)N * K / 2), sb = load(bs, (size_t)mxfp8_scale_bytes(N, K, lay));
+            Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * es : 0);
+            const int st = mxfp8_fp4_gemm_ex((mxfp8_pass)pass, a.p, sa.p, b.p, sb.p, M, N, K, c.p, dtype_of(dt), ldc, lay,
+                                             g_max_workgroups, nullptr);
+            unchanged(a, "a_q");
+            unchanged(sa, "a_s");
+            unchanged(b, "b_q");
+            unchanged(sb, "b_s");
+            report(st);
+            save(cout, c);
         } else if (op == "quantfp4") {
             std::string dt, src, prefix;
             long rows, cols, ld;
