@@ -45,6 +45,13 @@ def test_fp4_quantize_single_axis_padded_source(hostmodel, tmp_path, axis):
     _check_quantize(hostmodel, tmp_path, x, True, axis, True, ld=104)
 
 
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+def test_fp4_quantize_resident_grid_walks_over_several_tiles(hostmodel, tmp_path, bf16):
+    """One compute unit: two workgroups, three tiles each, the next tile's loads in registers while a tile is converted."""
+    x = si.fp4_hard_cases(288, 160, seed=13)
+    _check_quantize(hostmodel, tmp_path, x, bf16, 3, bf16, WAVESIM_CUS=1)
+
+
 def test_fp4_quantize_tiny_with_specials(hostmodel, tmp_path):
     x = si.tiny_with_specials(256, seed=0)
     _check_quantize(hostmodel, tmp_path, x, False, 3, False)
