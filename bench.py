@@ -339,22 +339,24 @@ def main():
         ms = ms_avg(lambda: mx.mxfp8_fp4_gemm_ex(mx.FPROP, xq["q_row"], xq["s_row"], wq["q_row"], wq["s_row"], Y, lay))
         q_ms = ms_avg(lambda: mx.mxfp8_fp4_quantize_ex(X, mx.BOTH, xq["q_row"], xq["s_row"], xq["q_colT"], xq["s_colT"], lay))
         tf = gemm_flop / (ms * 1e-3) / 1e12
+        sustained = sustained_mfma_tflops(4)
         return {"bound": "mfma", "achieved": tf, "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_FP4_PEAK_TFLOPS,
+                "peak_sustained": sustained, "frac_sustained": tf / sustained,
                 "kernel": f"gemm_persistent_kernel, MXFP4 operands (fprop {T}x{O}x{H}, BF16 out)", "avg_ms": ms, "launches": 20,
                 "quantize_X_both_ms": q_ms, "quantize_X_both_gbs": T * H * (2 + 2 * (0.5 + 1 / 32)) / (q_ms * 1e-3) / 1e9}
 
-    def sustained_mfma_tflops():
-        """What the matrix pipes of this GPU sustain on the scaled FP8 instruction alone (operands in registers,
-        pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling a GEMM
-        could reach on this machine if moving data were free. About 0.3 s of launches, the last two thirds timed."""
+    def sustained_mfma_tflops(element_bits=8):
+        """What the matrix pipes of this GPU sustain on the scaled matrix instruction alone (E4M3 or E2M1 operands in
+        registers, pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling
+        a GEMM could reach on this machine if moving data were free. About 0.3 s of launches, the last two thirds timed."""
         sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
         for _ in range(40):
-            mx.mxfp8_mfma_rate_probe(512, 1000, sink)
+            mx.mxfp8_mfma_rate_probe_ex(512, 1000, element_bits, sink)
         a, b = ev(), ev()
         a.record()
         flop = 0.0
         for _ in range(80):
-            flop += mx.mxfp8_mfma_rate_probe(512, 1000, sink)
+            flop += mx.mxfp8_mfma_rate_probe_ex(512, 1000, element_bits, sink)
         b.record()
         torch.cuda.synchronize()
         return flop / (a.elapsed_time(b) * 1e-3) / 1e12

@@ -327,6 +327,11 @@ mxfp8_status mxfp8_fp4_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_
  */
 mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float *sink, void *hip_stream);
 
+/* mxfp8_mfma_rate_probe with the element width of the operands: 8 (E4M3, what the call above does) or 4 (E2M1, the
+ * instruction form of the MXFP4 product; same flop count per instruction); anything else MXFP8_ERR_MODE. */
+mxfp8_status mxfp8_mfma_rate_probe_ex(int32_t workgroups, int32_t iterations, int32_t element_bits, float *sink,
+                                      void *hip_stream);
+
 /*
  * Second measurement aid (no operation of the paper): copies `bytes` bytes from src to dst (device memory, both
  * 16-byte aligned, not overlapping, bytes a multiple of 16) with 128-bit streaming loads and stores on

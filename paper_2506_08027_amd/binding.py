@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_fp4_gemm_ex.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_copy_rate_probe.restype = ci
+    lib.mxfp8_mfma_rate_probe_ex.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.mxfp8_mfma_rate_probe_ex.restype = ci
     lib.mxfp8_mfma_layout_probe.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_mfma_layout_probe.restype = ci
     lib.mxfp8_copy_rate_probe.argtypes = [vp, vp, i64, ctypes.c_int32, ctypes.c_int32, vp]
@@ -329,6 +331,17 @@ def mxfp8_mfma_rate_probe(workgroups: int, iterations: int, sink, stream=None) -
     rc = load().mxfp8_mfma_rate_probe(workgroups, iterations, _ptr(sink), _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_mfma_rate_probe")
+    return workgroups * 4.0 * iterations * 64 * 65536
+
+
+def mxfp8_mfma_rate_probe_ex(workgroups: int, iterations: int, element_bits: int, sink, stream=None) -> float:
+    """mxfp8_mfma_rate_probe on 8-bit (E4M3) or 4-bit (E2M1) operands; returns the flop it performs."""
+    _need_cuda(sink)
+    if sink.dtype != torch.float32 or sink.numel() < workgroups * 256 or not sink.is_contiguous():
+        raise ValueError("sink must be a dense float32 tensor of workgroups * 256 elements")
+    rc = load().mxfp8_mfma_rate_probe_ex(workgroups, iterations, element_bits, _ptr(sink), _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_mfma_rate_probe_ex")
     return workgroups * 4.0 * iterations * 64 * 65536
 
 

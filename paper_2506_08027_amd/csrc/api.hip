@@ -37,7 +37,7 @@ hipError_t launch_gemm_kgrouped(const uint8_t *a_q, const uint8_t *a_s, const ui
                                 bool tiled_scales, int64_t ldc, hipStream_t stream);
 hipError_t launch_gemm_bf16(const uint8_t *a, const uint8_t *b, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16,
                             int64_t ldc, int max_workgroups, hipStream_t stream);
-hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream);
+hipError_t launch_mfma_rate(int workgroups, int iterations, bool fp4, float *sink, hipStream_t stream);
 hipError_t launch_copy_rate(const void *src, void *dst, int64_t bytes, int workgroups, int mode, hipStream_t stream);
 }  // namespace mxfp8
 
@@ -364,6 +364,14 @@ mxfp8_status mxfp8_fp4_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_
 
 mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float *sink, void *hip_stream)
 {
+    return mxfp8_mfma_rate_probe_ex(workgroups, iterations, 8, sink, hip_stream);
+}
+
+mxfp8_status mxfp8_mfma_rate_probe_ex(int32_t workgroups, int32_t iterations, int32_t element_bits, float *sink,
+                                      void *hip_stream)
+{
+    if (element_bits != 8 && element_bits != 4)
+        return MXFP8_ERR_MODE;
     if (workgroups < 0 || iterations < 0 || workgroups > (1 << 20) || iterations > (1 << 24))
         return MXFP8_ERR_SHAPE;
     if (workgroups == 0)
@@ -372,7 +380,8 @@ mxfp8_status mxfp8_mfma_rate_probe(int32_t workgroups, int32_t iterations, float
         return MXFP8_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(sink) % 4)
         return MXFP8_ERR_ALIGN;
-    const hipError_t e = mxfp8::launch_mfma_rate(workgroups, iterations, sink, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = mxfp8::launch_mfma_rate(workgroups, iterations, element_bits == 4, sink,
+                                                 static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

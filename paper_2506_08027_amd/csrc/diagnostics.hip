@@ -11,6 +11,7 @@ namespace mxfp8 {
 // The operands are four A and four B fragments of pseudo-random finite E4M3 codes (different in every
 // lane, |value| < 2), used in rotation: the power drawn by the matrix pipes depends on how many operand
 // bits change from one instruction to the next, and constant operands would flatter the result.
+template <int FMT>  // cbsz = blgp: 0 = E4M3 operands, 4 = E2M1 operands (the first four dwords of each fragment)
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int iterations, float *__restrict__ sink)
 {
     v8i a[4], b[4];
@@ -31,7 +32,7 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iterations, float *_
     for (int it = 0; it < iterations; ++it) {
 #pragma unroll
         for (int t = 0; t < 64; ++t)   // scale bytes 100: products around 2^-54, sums stay finite
-            acc[t & 15] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[t & 3], b[(t >> 2) & 3], acc[t & 15], 0, 0, 0,
+            acc[t & 15] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[t & 3], b[(t >> 2) & 3], acc[t & 15], FMT, FMT, 0,
                                                                            100, 0, 100);
     }
     float s = 0.f;
@@ -136,9 +137,12 @@ hipError_t launch_mfma_layout(const void *a, const void *b, const int *sa, const
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_rate(int workgroups, int iterations, float *sink, hipStream_t stream)
+hipError_t launch_mfma_rate(int workgroups, int iterations, bool fp4, float *sink, hipStream_t stream)
 {
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, iterations, sink);
+    if (fp4)
+        hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3((unsigned)workgroups), dim3(256), 0, stream, iterations, sink);
+    else
+        hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3((unsigned)workgroups), dim3(256), 0, stream, iterations, sink);
     return hipGetLastError();
 }
 

@@ -32,7 +32,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == ["mxfp8_copy_rate_probe", "mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex",
-                                    "mxfp8_fp4_dequantize_ex", "mxfp8_fp4_gemm_ex", "mxfp8_fp4_quantize_ex", "mxfp8_gemm", "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_layout_probe", "mxfp8_mfma_rate_probe", "mxfp8_quantize",
+                                    "mxfp8_fp4_dequantize_ex", "mxfp8_fp4_gemm_ex", "mxfp8_fp4_quantize_ex", "mxfp8_gemm", "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_layout_probe", "mxfp8_mfma_rate_probe", "mxfp8_mfma_rate_probe_ex", "mxfp8_quantize",
                                     "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_requantize_colwise_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
 
@@ -114,6 +114,9 @@ def test_mode_entry_points_and_rate_probe_validate(lib):
     r.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P]
     assert r(-1, 10, FAKE, None) == 2 and r(10, -1, FAKE, None) == 2 and r((1 << 20) + 1, 1, FAKE, None) == 2
     assert r(4, 10, None, None) == 1 and r(4, 10, P(0x1002), None) == 3 and r(0, 10, None, None) == 0
+    rx = lib.mxfp8_mfma_rate_probe_ex
+    rx.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, P, P]
+    assert rx(4, 10, 6, FAKE, None) == 5 and rx(-1, 10, 4, FAKE, None) == 2 and rx(4, 10, 4, None, None) == 1 and rx(0, 10, 4, None, None) == 0
 
 
 def test_status_strings(lib):
