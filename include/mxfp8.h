@@ -318,6 +318,45 @@ mxfp8_status mxfp8_fp4_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_
                                void *hip_stream);
 
 /*
+ * MXFP6 (Table 1: E2M3 elements, largest magnitude 7.5, or E3M2 elements, largest magnitude 28; 32-element blocks
+ * with a UE8M0 scale): the conversion of Section 3.3 / Algorithm 1 / Appendix A.1 and A.2 with those constants.
+ * X = 2^n for the smallest n with amax <= destmax * 2^n (clamped to [-127, 127]), Q_i = V_i / X rounded to the
+ * nearest representable value (ties to the code with an even mantissa), saturating at +-destmax, sign kept.
+ * E3M2's smallest subnormal is 2^-4 (bias 3, two mantissa bits: the value Table 1's binade count implies).
+ * Storage: the 32 six-bit codes of a block (sign << 5 | exponent << M | mantissa) form one little-endian 192-bit
+ * string, code i in bits 6i .. 6i+5 = 24 bytes per block:
+ *   MXFP8_ROWWISE   q_row  [rows x cols*3/4] bytes, s_row  [rows x cols/32] bytes
+ *   MXFP8_COLWISE   q_colT [cols x rows*3/4] bytes, s_colT [cols x rows/32] bytes  (stored transposed)
+ * Scale bytes in `scale_layout`, sized by mxfp8_scale_bytes. Requirements as for mxfp8_quantize_ex. Neither
+ * format has a NaN or an Inf code: a block with a NaN gets scale 0xFF and all codes 0, a block with +-Inf and no
+ * NaN gets scale 254, its infinities become +-destmax and its finite values are divided by 2^127.
+ */
+typedef enum { MXFP8_E2M3 = 0, MXFP8_E3M2 = 1 } mxfp8_fp6_element;
+
+mxfp8_status mxfp8_fp6_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                                   int64_t ld_src, mxfp8_axis axis, mxfp8_fp6_element element, uint8_t *q_row,
+                                   uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                                   mxfp8_scale_layout scale_layout, void *hip_stream);
+
+/* dst[r, c] = value(code(r, c)) * 2^(s[r, c/32] - 127) for an MXFP6 operand q [rows x cols*3/4], s (Section 2:
+ * value = X * P_i); dst FP32 or BF16 (every decoded value has at most 4 significant bits), leading dimension
+ * ld_dst >= cols. A 0xFF scale decodes to NaN. cols % 32 == 0; q and dst 16-byte aligned, ld_dst a multiple of
+ * 16 bytes. */
+mxfp8_status mxfp8_fp6_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
+                                     mxfp8_fp6_element element, void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst,
+                                     mxfp8_scale_layout scale_layout, void *hip_stream);
+
+/*
+ * The product of MXFP6 operands: every E2M3 and every E3M2 value is also an E4M3 value, so q [rows x cols*3/4]
+ * is expanded, exactly, to E4M3 bytes q_e4m3 [rows x cols]; together with the operand's UNCHANGED scale bytes
+ * that is an MXFP8 operand, and mxfp8_gemm_ex of two such operands computes the MXFP6 sum of Section 2 /
+ * Appendix A.3 (the two operands may use different 6-bit formats, or one may be a genuine MXFP8 operand).
+ * cols % 32 == 0; q and q_e4m3 16-byte aligned, not overlapping.
+ */
+mxfp8_status mxfp8_fp6_expand_ex(const uint8_t *q, int64_t rows, int64_t cols, mxfp8_fp6_element element,
+                                 uint8_t *q_e4m3, void *hip_stream);
+
+/*
  * Measurement aid for benchmarks (no operation of the paper): `workgroups` workgroups of 4 wavefronts each
  * issue iterations * 64 independent scaled FP8 matrix instructions (16x16x128, 65536 flop each) on register
  * operands, without memory traffic, and then store one float per work-item to sink[workgroups * 256]

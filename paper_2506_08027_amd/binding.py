@@ -80,6 +80,12 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_fp4_dequantize_ex.restype = ci
     lib.mxfp8_fp4_gemm_ex.argtypes = [ci, vp, vp, vp, vp, i64, i64, i64, vp, ci, i64, ci, ctypes.c_int32, vp]
     lib.mxfp8_fp4_gemm_ex.restype = ci
+    lib.mxfp8_fp6_quantize_ex.argtypes = [vp, ci, i64, i64, i64, ci, ci, vp, vp, vp, vp, ci, vp]
+    lib.mxfp8_fp6_quantize_ex.restype = ci
+    lib.mxfp8_fp6_dequantize_ex.argtypes = [vp, vp, i64, i64, ci, vp, ci, i64, ci, vp]
+    lib.mxfp8_fp6_dequantize_ex.restype = ci
+    lib.mxfp8_fp6_expand_ex.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.mxfp8_fp6_expand_ex.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_copy_rate_probe.restype = ci
     lib.mxfp8_mfma_rate_probe_ex.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
@@ -438,6 +444,58 @@ def mxfp8_fp4_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR
         raise MXFP8Error(rc, "mxfp8_fp4_gemm_ex")
 
 
+E2M3, E3M2 = 0, 1   # mxfp8_fp6_element
+
+
+def mxfp8_fp6_quantize_ex(src, axis, element, q_row=None, s_row=None, q_colT=None, s_colT=None,
+                          scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """src [rows x cols] float32/bfloat16 -> MXFP6 copies: q_row [rows x cols*3/4], q_colT [cols x rows*3/4] (32 six-bit
+    codes per 24 bytes), scales as for MXFP8. element: E2M3 or E3M2."""
+    _need_cuda(src, q_row, s_row, q_colT, s_colT)
+    if src.dim() != 2 or (src.numel() and src.stride(1) != 1):
+        raise ValueError("src must be 2-D with contiguous rows")
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else max(cols, 1)
+    ax = _AXIS[axis]
+    for want, q, s, r, c, what in ((ax & ROWWISE, q_row, s_row, rows, cols, "row"), (ax & COLWISE, q_colT, s_colT, cols, rows, "colT")):
+        if want and q is not None and s is not None:   # the library cannot see buffer sizes: check them here
+            if q.dtype != torch.uint8 or not q.is_contiguous() or q.numel() != r * c // 4 * 3:
+                raise ValueError(f"q_{what} must be dense uint8 with {r * c // 4 * 3} bytes")
+            _check_scales(s, r, c, scale_layout, f"s_{what}")
+    rc = load().mxfp8_fp6_quantize_ex(_ptr(src), _dtype_code(src.dtype), rows, cols, ld, ax, element, _ptr(q_row), _ptr(s_row),
+                                      _ptr(q_colT), _ptr(s_colT), scale_layout, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_fp6_quantize_ex")
+
+
+def mxfp8_fp6_dequantize_ex(q, s, element, dst, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
+    """q [rows x cols*3/4] packed 6-bit codes, s its scales -> dst [rows x cols] float32/bfloat16."""
+    _need_cuda(q, s, dst)
+    rows, cols = dst.shape
+    if q.dtype != torch.uint8 or not q.is_contiguous() or tuple(q.shape) != (rows, cols // 4 * 3):
+        raise ValueError(f"q must be dense uint8 [{rows} x {cols // 4 * 3}]")
+    _check_scales(s, rows, cols, scale_layout, "s")
+    if dst.numel() and dst.stride(1) != 1:
+        raise ValueError("dst rows must be contiguous")
+    ld = dst.stride(0) if rows > 1 else max(cols, 1)
+    rc = load().mxfp8_fp6_dequantize_ex(_ptr(q), _ptr(s), rows, cols, element, _ptr(dst), _dtype_code(dst.dtype), ld,
+                                        scale_layout, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_fp6_dequantize_ex")
+
+
+def mxfp8_fp6_expand_ex(q, element, q_e4m3, stream=None) -> None:
+    """q [rows x cols*3/4] packed 6-bit codes -> q_e4m3 [rows x cols] E4M3 bytes of the same values."""
+    _need_cuda(q, q_e4m3)
+    rows, cols = q_e4m3.shape
+    for t, shape in ((q, (rows, cols // 4 * 3)), (q_e4m3, (rows, cols))):
+        if t.dtype != torch.uint8 or not t.is_contiguous() or tuple(t.shape) != shape:
+            raise ValueError("q must be dense uint8 [rows x cols*3/4], q_e4m3 dense uint8 [rows x cols]")
+    rc = load().mxfp8_fp6_expand_ex(_ptr(q), rows, cols, element, _ptr(q_e4m3), _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_fp6_expand_ex")
+
+
 # ---- conveniences that only allocate the outputs ----------------------------------------------
 
 def quantize(src, axis="both", scale_layout=SCALES_ROWMAJOR, element=E4M3, rule=SCALE_ROUND_UP):
@@ -548,3 +606,37 @@ def fp4_gemm(pass_, a_q, a_s, b_q, b_s, out_dtype=torch.float32, scale_layout=SC
     c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
     mxfp8_fp4_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout, max_workgroups)
     return c
+
+
+def fp6_quantize(src, element, axis="both", scale_layout=SCALES_ROWMAJOR):
+    """Allocate outputs and call mxfp8_fp6_quantize_ex; keys as for quantize(), element buffers 3/4 as wide."""
+    rows, cols = src.shape
+    ax = _AXIS[axis]
+    out = {}
+    u8 = dict(dtype=torch.uint8, device=src.device)
+    tiled = scale_layout != SCALES_ROWMAJOR
+    if ax & ROWWISE:
+        out["q_row"] = torch.empty((rows, cols // 4 * 3), **u8)
+        out["s_row"] = torch.empty((mxfp8_scale_bytes(rows, cols, scale_layout),) if tiled else (rows, cols // K_BLOCK), **u8)
+    if ax & COLWISE:
+        out["q_colT"] = torch.empty((cols, rows // 4 * 3), **u8)
+        out["s_colT"] = torch.empty((mxfp8_scale_bytes(cols, rows, scale_layout),) if tiled else (cols, rows // K_BLOCK), **u8)
+    mxfp8_fp6_quantize_ex(src, ax, element, out.get("q_row"), out.get("s_row"), out.get("q_colT"), out.get("s_colT"), scale_layout)
+    return out
+
+
+def fp6_dequantize(q, s, element, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR):
+    dst = torch.empty((q.shape[0], q.shape[1] // 3 * 4), dtype=out_dtype, device=q.device)
+    mxfp8_fp6_dequantize_ex(q, s, element, dst, scale_layout)
+    return dst
+
+
+def fp6_expand(q, element):
+    q8 = torch.empty((q.shape[0], q.shape[1] // 3 * 4), dtype=torch.uint8, device=q.device)
+    mxfp8_fp6_expand_ex(q, element, q8)
+    return q8
+
+
+def fp6_gemm(pass_, a_q, a_s, a_element, b_q, b_s, b_element, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
+    """Product of two MXFP6 operands: both expanded to E4M3 bytes, then the MXFP8 product with the operands' own scales."""
+    return gemm(pass_, fp6_expand(a_q, a_element), a_s, fp6_expand(b_q, b_element), b_s, out_dtype, scale_layout, max_workgroups)

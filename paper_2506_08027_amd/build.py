@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libmxfp8.so")
-SOURCES = ["api.hip", "quantize.hip", "dequantize.hip", "gemm.hip", "diagnostics.hip", "mxfp4.hip"]
+SOURCES = ["api.hip", "quantize.hip", "dequantize.hip", "gemm.hip", "diagnostics.hip", "mxfp4.hip", "mxfp6.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed-FP32 code generation is switched off on purpose (the compiler would otherwise form
 # v_pk_*_f32 from ordinary float code).

@@ -26,6 +26,11 @@ hipError_t launch_mfma_layout(const void *a, const void *b, const int *sa, const
 hipError_t launch_gemm_fp4(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
                            int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc, int max_workgroups,
                            hipStream_t stream);
+hipError_t launch_quantize_fp6(const void *src, bool bf16, int64_t rows, int64_t cols, int64_t ld, int axis, bool e3m2, uint8_t *q_row,
+                               uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
+hipError_t launch_dequantize_fp6(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, bool e3m2, void *dst, bool bf16,
+                                 bool tiled, int64_t ld, hipStream_t stream);
+hipError_t launch_expand_fp6(const uint8_t *q, int64_t rows, int64_t cols, bool e3m2, uint8_t *q8, hipStream_t stream);
 hipError_t launch_requantize_colwise(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols, uint8_t *q_colT,
                                      uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
 hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
@@ -359,6 +364,72 @@ mxfp8_status mxfp8_fp4_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_
     const hipError_t e = mxfp8::launch_gemm_fp4(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16,
                                                 scale_layout == MXFP8_SCALES_TILED, ldc, max_workgroups,
                                                 static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_fp6_quantize_ex(const void *src, mxfp8_dtype src_dtype, int64_t rows, int64_t cols,
+                                   int64_t ld_src, mxfp8_axis axis, mxfp8_fp6_element element, uint8_t *q_row,
+                                   uint8_t *s_row, uint8_t *q_colT, uint8_t *s_colT,
+                                   mxfp8_scale_layout scale_layout, void *hip_stream)
+{
+    if (!valid_dtype(src_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout) || (axis != MXFP8_ROWWISE && axis != MXFP8_COLWISE && axis != MXFP8_BOTH) ||
+        (element != MXFP8_E2M3 && element != MXFP8_E3M2))
+        return MXFP8_ERR_MODE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || rows % 32 || cols % 32 || ld_src < cols)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    const bool want_row = axis & MXFP8_ROWWISE, want_col = axis & MXFP8_COLWISE;
+    if (!src || (want_row && (!q_row || !s_row)) || (want_col && (!q_colT || !s_colT)))
+        return MXFP8_ERR_NULL;
+    if (!aligned16(src) || (ld_src * esize(src_dtype)) % 16 || (want_row && !aligned16(q_row)) ||
+        (want_col && !aligned16(q_colT)))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_quantize_fp6(src, src_dtype == MXFP8_BF16, rows, cols, ld_src, (int)axis,
+                                                    element == MXFP8_E3M2, q_row, s_row, q_colT, s_colT,
+                                                    scale_layout == MXFP8_SCALES_TILED, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_fp6_dequantize_ex(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols,
+                                     mxfp8_fp6_element element, void *dst, mxfp8_dtype dst_dtype, int64_t ld_dst,
+                                     mxfp8_scale_layout scale_layout, void *hip_stream)
+{
+    if (!valid_dtype(dst_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout) || (element != MXFP8_E2M3 && element != MXFP8_E3M2))
+        return MXFP8_ERR_MODE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || cols % 32 || ld_dst < cols)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    if (!q || !s || !dst)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(q) || !aligned16(dst) || (ld_dst * esize(dst_dtype)) % 16)
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_dequantize_fp6(q, s, rows, cols, element == MXFP8_E3M2, dst, dst_dtype == MXFP8_BF16,
+                                                      scale_layout == MXFP8_SCALES_TILED, ld_dst,
+                                                      static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_fp6_expand_ex(const uint8_t *q, int64_t rows, int64_t cols, mxfp8_fp6_element element,
+                                 uint8_t *q_e4m3, void *hip_stream)
+{
+    if (element != MXFP8_E2M3 && element != MXFP8_E3M2)
+        return MXFP8_ERR_MODE;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim || cols % 32)
+        return MXFP8_ERR_SHAPE;
+    if (rows == 0 || cols == 0)
+        return MXFP8_OK;
+    if (!q || !q_e4m3)
+        return MXFP8_ERR_NULL;
+    if (!aligned16(q) || !aligned16(q_e4m3))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_expand_fp6(q, rows, cols, element == MXFP8_E3M2, q_e4m3,
+                                                  static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

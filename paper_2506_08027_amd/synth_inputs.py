@@ -151,3 +151,38 @@ def fp4_hard_cases(rows: int, cols: int, seed: int) -> np.ndarray:
     x[5, 64:96] = 0.0
     x[5, 65] = -0.0
     return x
+
+
+def fp6_hard_cases(rows: int, cols: int, seed: int, top: float) -> np.ndarray:
+    """N(0,1) with outliers, plus blocks drawn from the grid k * 2^-6 (it holds every magnitude of both 6-bit formats
+    and every midpoint between two of them) and from its neighbours one FP32 step away, with the block maximum on,
+    just above and just below `top` * 2^k (the scale boundary of the format whose largest magnitude is `top`), for k
+    over the whole exponent range; NaN / Inf blocks; signed zeros."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, cols), dtype=np.float32)
+    x[rng.random((rows, cols)) < 0.01] *= np.float32(100.0)
+    ks = [-149, -140, -131, -130, -129, -128, -127, -126, -60, -1, 0, 1, 50, 120, 122]
+    slot = 0
+    t32 = np.float32(top)
+    for k in ks:
+        for peak in (t32, np.nextafter(t32, np.float32(2 * top)), np.nextafter(t32, np.float32(0.0)), np.float32(top / 2),
+                     np.nextafter(np.float32(top / 2), np.float32(top))):
+            grid = (rng.integers(0, int(top * 64) + 1, 32).astype(np.float32) / np.float32(64.0)).astype(np.float32)
+            nudge = rng.integers(-1, 2, 32)
+            blk = np.where(nudge > 0, np.nextafter(grid, np.float32(1e9)), np.where(nudge < 0, np.nextafter(grid, np.float32(-1.0)), grid))
+            blk = np.minimum(np.abs(blk), float(peak)) * rng.choice([-1.0, 1.0], 32)
+            blk[rng.integers(32)] = float(peak)
+            with np.errstate(over="ignore", under="ignore"):
+                v = np.ldexp(blk.astype(np.float64), k).astype(np.float32)
+            r, b = (slot * 7) % rows, (slot * 3) % (cols // 32)
+            x[r, 32 * b:32 * b + 32] = v
+            c, rb = (slot * 5 + 1) % cols, (slot * 2 + 1) % (rows // 32)
+            x[32 * rb:32 * rb + 32, c] = v
+            slot += 1
+    x[1, 0] = np.nan
+    x[3, 40] = np.inf
+    x[rows - 1, cols - 1] = -np.inf
+    x[rows - 2, cols - 2] = np.nan
+    x[5, 64:96] = 0.0
+    x[5, 65] = -0.0
+    return x

@@ -8,7 +8,7 @@ here="$(cd "$(dirname "$0")" && pwd)"
 csrc="$here/../../paper_2506_08027_amd/csrc"
 CXX="${HOST_CLANG:-/opt/rocm/llvm/bin/clang++}"
 common=(-std=c++17 -x c++ -I "$here/shim" -Wall -Wno-unknown-pragmas -Wno-unused-function -Wno-psabi)
-kernels=("$csrc/api.hip" "$csrc/quantize.hip" "$csrc/dequantize.hip" "$csrc/gemm.hip" "$csrc/diagnostics.hip" "$csrc/mxfp4.hip")
+kernels=("$csrc/api.hip" "$csrc/quantize.hip" "$csrc/dequantize.hip" "$csrc/gemm.hip" "$csrc/diagnostics.hip" "$csrc/mxfp4.hip" "$csrc/mxfp6.hip")
 if [ "$1" = "--shared" ]; then
     out="${2:-$here/_build/libmxfp8_hostmodel.so}"
     mkdir -p "$(dirname "$out")"

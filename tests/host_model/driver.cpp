@@ -337,6 +337,54 @@ int main(int argc, char **argv)
             unchanged(sb, "b_s");
             report(st);
             save(cout, c);
+        } else if (op == "quantfp6") {
+            std::string dt, src, prefix;
+            long rows, cols, ld;
+            int axis, element;
+            ls >> dt >> rows >> cols >> ld >> axis >> element >> src >> prefix;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf s = load(src, rows > 0 ? ((size_t)(rows - 1) * ld + cols) * es : 0);
+            const bool r = axis & 1, c = axis & 2;
+            Buf qr = output(r ? (size_t)rows * cols / 4 * 3 : 0), sr = output(r ? (size_t)mxfp8_scale_bytes(rows, cols, lay) : 0);
+            Buf qc = output(c ? (size_t)rows * cols / 4 * 3 : 0), sc = output(c ? (size_t)mxfp8_scale_bytes(cols, rows, lay) : 0);
+            const int st = mxfp8_fp6_quantize_ex(s.p, dtype_of(dt), rows, cols, ld, (mxfp8_axis)axis, (mxfp8_fp6_element)element,
+                                                 qr.p, sr.p, qc.p, sc.p, lay, nullptr);
+            unchanged(s, "src");
+            report(st);
+            if (r) {
+                save(prefix + ".q_row", qr);
+                save(prefix + ".s_row", sr);
+            }
+            if (c) {
+                save(prefix + ".q_colT", qc);
+                save(prefix + ".s_colT", sc);
+            }
+        } else if (op == "dequantfp6") {
+            long rows, cols, ld;
+            int element;
+            std::string dt, q, s, out;
+            ls >> rows >> cols >> element >> dt >> ld >> q >> s >> out;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf qb = load(q, (size_t)rows * cols / 4 * 3), sb = load(s, (size_t)mxfp8_scale_bytes(rows, cols, lay));
+            Buf o = output(rows > 0 ? ((size_t)(rows - 1) * ld + cols) * es : 0);
+            const int st = mxfp8_fp6_dequantize_ex(qb.p, sb.p, rows, cols, (mxfp8_fp6_element)element, o.p, dtype_of(dt), ld, lay, nullptr);
+            unchanged(qb, "q");
+            unchanged(sb, "s");
+            report(st);
+            save(out, o);
+        } else if (op == "expandfp6") {
+            long rows, cols;
+            int element;
+            std::string q, out;
+            ls >> rows >> cols >> element >> q >> out;
+            Buf qb = load(q, (size_t)rows * cols / 4 * 3);
+            Buf o = output((size_t)rows * cols);
+            const int st = mxfp8_fp6_expand_ex(qb.p, rows, cols, (mxfp8_fp6_element)element, o.p, nullptr);
+            unchanged(qb, "q");
+            report(st);
+            save(out, o);
         } else if (op == "quantfp4") {
             std::string dt, src, prefix;
             long rows, cols, ld;

@@ -1,0 +1,104 @@
+"""The MXFP6 quantizer, decoder and E4M3 expansion (Table 1: E2M3 and E3M2 elements) on the CPU execution model of
+the kernels: byte-exact against the oracle for ragged multi-tile shapes, both axes, both scale layouts, padded
+sources, every rounding tie and every scale boundary, with AddressSanitizer watching the accesses."""
+import numpy as np
+import pytest
+import torch
+
+import scale_layout as sl
+from oracle import mxfp6
+from paper_2506_08027_amd import synth_inputs as si
+from test_host_model import SENTINEL, _compare_scales, get, hostmodel, put, run_case  # noqa: F401  (hostmodel is a fixture)
+
+FMTS = [("e2m3", 0), ("e3m2", 1)]
+
+
+def _check_quantize(hostmodel, tmp_path, x, fmt, element, bf16, axis, tiled, ld=None, **env):
+    rows, cols = x.shape
+    src = si.to_bf16_bits(x) if bf16 else x
+    ld = ld or cols
+    padded = np.full((rows, ld), 0x7FC0 if bf16 else np.nan, src.dtype)
+    padded[:, :cols] = src
+    flat = padded.ravel()[:(rows - 1) * ld + cols]
+    line = (f"quantfp6 {'bf16' if bf16 else 'f32'} {rows} {cols} {ld} {axis} {element} {put(tmp_path, 'src.bin', flat)} {tmp_path / 'o'}"
+            + (" tiled" if tiled else ""))
+    _, calls = run_case(hostmodel, tmp_path, [line], **env)
+    assert calls[0][0] == 0
+    if axis & 1:
+        q, s = mxfp6.quantize_rowwise(src, fmt)
+        assert np.array_equal(get(str(tmp_path / "o.q_row"), np.uint8, q.shape), q)
+        _compare_scales(str(tmp_path / "o.s_row"), s, tiled)
+    if axis & 2:
+        q, s = mxfp6.quantize_colwise(src, fmt)
+        assert np.array_equal(get(str(tmp_path / "o.q_colT"), np.uint8, q.shape), q)
+        _compare_scales(str(tmp_path / "o.s_colT"), s, tiled)
+
+
+@pytest.mark.parametrize("fmt,element", FMTS)
+@pytest.mark.parametrize("bf16,tiled", [(False, False), (True, True)], ids=["f32-rowmajor", "bf16-tiled"])
+def test_fp6_quantize_ties_boundaries_and_specials(hostmodel, tmp_path, fmt, element, bf16, tiled):
+    x = si.fp6_hard_cases(288, 160, seed=11, top=mxfp6.dest_max(fmt))             # 3 x 2 tiles, ragged in both directions
+    _check_quantize(hostmodel, tmp_path, x, fmt, element, bf16, 3, tiled, WAVESIM_CUS=1)   # two workgroups, three tiles each
+
+
+@pytest.mark.parametrize("fmt,element", FMTS)
+@pytest.mark.parametrize("axis", [1, 2])
+def test_fp6_quantize_single_axis_padded_source(hostmodel, tmp_path, fmt, element, axis):
+    x = si.fp6_hard_cases(160, 96, seed=12, top=mxfp6.dest_max(fmt))
+    _check_quantize(hostmodel, tmp_path, x, fmt, element, False, axis, True, ld=100)
+    _check_quantize(hostmodel, tmp_path, x, fmt, element, True, axis, False, ld=104)
+
+
+@pytest.mark.parametrize("fmt,element", FMTS)
+def test_fp6_quantize_tiny_with_specials(hostmodel, tmp_path, fmt, element):
+    _check_quantize(hostmodel, tmp_path, si.tiny_with_specials(256, seed=0), fmt, element, False, 3, False)
+
+
+def _all_codes_operand(rows, cols, seed):
+    rng = np.random.default_rng(seed)
+    codes = rng.integers(0, 64, (rows, cols)).astype(np.uint8)
+    codes[:256, :64] = np.arange(64, dtype=np.uint8)[None, :]
+    s = rng.integers(0, 256, (rows, cols // 32)).astype(np.uint8)
+    s[:256, 0] = np.arange(256, dtype=np.uint8)
+    return mxfp6.pack(codes), s
+
+
+@pytest.mark.parametrize("fmt,element", FMTS)
+@pytest.mark.parametrize("bf16,tiled", [(False, False), (True, True), (True, False)], ids=["f32-rowmajor", "bf16-tiled", "bf16-rowmajor"])
+def test_fp6_dequantize_every_code_and_scale(hostmodel, tmp_path, fmt, element, bf16, tiled):
+    rows, cols, ld = 256 + 40, 96, 104
+    q, s = _all_codes_operand(rows, cols, 5)
+    out = str(tmp_path / "d.bin")
+    line = (f"dequantfp6 {rows} {cols} {element} {'bf16' if bf16 else 'f32'} {ld} {put(tmp_path, 'q.bin', q)} "
+            f"{put(tmp_path, 's.bin', sl.tile(s, filler=0xFF) if tiled else s)} {out}" + (" tiled" if tiled else ""))
+    _, calls = run_case(hostmodel, tmp_path, [line])
+    assert calls[0][0] == 0
+    want = mxfp6.dequantize(q, s, fmt)
+    n = (rows - 1) * ld + cols
+    dt, fill = (np.uint16, SENTINEL * 0x0101) if bf16 else (np.uint32, SENTINEL * 0x01010101)
+    raw = np.full(rows * ld, fill, dt)
+    raw[:n] = np.fromfile(out, dt)
+    raw = raw.reshape(rows, ld)
+    assert (raw[:, cols:] == fill).all()
+    with np.errstate(over="ignore", under="ignore"):
+        w32 = want.astype(np.float32)
+    ref = si.to_bf16_bits(w32) if bf16 else w32.view(np.uint32)
+    nan = np.isnan(want)
+    got = raw[:, :cols]
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.isnan(si.bf16_bits_to_f32(got[nan]) if bf16 else got[nan].view(np.float32)).all()
+
+
+@pytest.mark.parametrize("fmt,element", FMTS)
+def test_fp6_expansion_to_e4m3_is_exact(hostmodel, tmp_path, fmt, element):
+    """Every code of the format, in every position of a block: the E4M3 byte decodes (library table) to the code's value."""
+    rows, cols = 256 + 8, 96
+    q, _ = _all_codes_operand(rows, cols, 6)
+    out = str(tmp_path / "e.bin")
+    _, calls = run_case(hostmodel, tmp_path, [f"expandfp6 {rows} {cols} {element} {put(tmp_path, 'q.bin', q)} {out}"])
+    assert calls[0][0] == 0
+    by = np.fromfile(out, np.uint8).reshape(rows, cols)
+    e4 = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy().astype(np.float64)
+    want = mxfp6.decode(mxfp6.unpack(q), fmt)
+    got = e4[by]
+    assert np.array_equal(got, want) and np.array_equal(np.signbit(got), np.signbit(want))

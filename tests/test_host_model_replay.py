@@ -85,3 +85,9 @@ def test_matrix_instruction_layout_tests_pass_on_the_host_model(hostmodel_lib):
     model of the instruction as well: the two cannot drift apart."""
     n = replay(hostmodel_lib, ["test_gpu_mfma_layout.py"], "layout or scale or operand")
     assert n >= 7
+
+
+def test_fp6_gpu_tests_pass_on_the_host_model(hostmodel_lib):
+    """MXFP6 conversion, expansion and product; the full-size case is left to the GPU."""
+    n = replay(hostmodel_lib, ["test_gpu_fp6.py"], "not full_size")
+    assert n >= 31
