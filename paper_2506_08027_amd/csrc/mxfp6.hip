@@ -58,7 +58,12 @@ template <class F> __device__ __forceinline__ uint32_t fp6_code(float v, int n)
     return (uint32_t)(((e - F::EMIN) << F::M) + (int)q) | ((__float_as_uint(v) >> 26) & 32u);
 }
 
-// 32 values -> six dwords (one little-endian 192-bit string, code i in bits 6i..6i+5) and the block's scale byte
+// 32 values -> six dwords (one little-endian 192-bit string, code i in bits 6i..6i+5) and the block's scale byte.
+// Finite blocks go through the hardware converter (v_cvt_scalef32_2xpk16_{fp6,bf6}_f32: 2 x 16 values divided by
+// the scale, rounded to nearest even, saturated, packed; element 2i of the result comes from the first source,
+// 2i+1 from the second); blocks with an infinity take the software encoder, blocks with a NaN are not converted.
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v6u __attribute__((ext_vector_type(6)));
 template <class F> __device__ __forceinline__ void fp6_block(const float (&v)[kBlock], uint32_t (&w)[6], uint32_t &scale)
 {
     uint32_t amax = 0;
@@ -70,11 +75,25 @@ template <class F> __device__ __forceinline__ void fp6_block(const float (&v)[kB
 #pragma unroll
     for (int j = 0; j < 6; ++j)
         w[j] = 0;
-    if (sb != 0xFFu) {
-        const int n = (int)sb - 127;
+    if (amax < 0x7F800000u) {
+        v16f even, odd;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            even[i] = v[2 * i];
+            odd[i] = v[2 * i + 1];
+        }
+        v6u r;
+        if constexpr (F::E == 2)
+            r = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(even, odd, scale_operand(sb));
+        else
+            r = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(even, odd, scale_operand(sb));
+#pragma unroll
+        for (int j = 0; j < 6; ++j)
+            w[j] = r[j];
+    } else if (sb != 0xFFu) {  // a block with an infinity: +-Inf -> +-destmax, finite values / 2^127
 #pragma unroll
         for (int i = 0; i < kBlock; ++i) {
-            const uint32_t c = fp6_code<F>(v[i], n);
+            const uint32_t c = fp6_code<F>(v[i], 127);
             const int pos = 6 * i;  // compile-time after unrolling
             w[pos / 32] |= c << (pos % 32);
             if (pos % 32 > 26)

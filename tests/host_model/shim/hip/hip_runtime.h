@@ -63,6 +63,8 @@ inline uint32_t __float_as_uint(float f)
 #define __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(old, p, scale, hi) \
     ::wavesim::cvt_scalef32_pk_fp8_bf16((old), (p), (scale), (hi))
 #define __builtin_amdgcn_cvt_pk_f32_fp8(q, hi) ::wavesim::cvt_pk_f32_fp8((q), (hi))
+#define __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(a, b, scale) ::wavesim::cvt_scalef32_2xpk16_6bit((a), (b), (scale), 2, 3)
+#define __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(a, b, scale) ::wavesim::cvt_scalef32_2xpk16_6bit((a), (b), (scale), 3, 2)
 #define __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(old, a, b, scale, sel) \
     ::wavesim::cvt_scalef32_pk_fp4_f32((old), (a), (b), (scale), (sel))
 #define __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(old, a, b, scale, hi) \

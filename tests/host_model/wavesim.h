@@ -384,6 +384,48 @@ inline uint32_t cvt_scalef32_pk_fp4_f32(uint32_t old, float a, float b, float sc
     const uint32_t byte = (uint32_t)(cvt_scaled_e2m1(a, scale) | (cvt_scaled_e2m1(b, scale) << 4));
     return (old & ~(0xFFu << (8 * sel))) | (byte << (8 * sel));
 }
+// v_cvt_scalef32_2xpk16_{fp6,bf6}_f32: 2 x 16 FP32 values divided by the scale (same reading of the scale operand
+// as the FP8 forms), rounded to E2M3 (fp6) or E3M2 (bf6), nearest with ties to even, saturating, sign kept; the
+// 32 six-bit codes are packed little-endian, element 2i from the first source and 2i+1 from the second. What the
+// instruction makes of a NaN is not modelled (the kernels never convert a block that holds one).
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v6u __attribute__((ext_vector_type(6)));
+inline uint32_t cvt_scaled_fp6(float x, float scale, int ebits, int mbits)
+{
+    uint32_t sbits;
+    memcpy(&sbits, &scale, 4);
+    const int field = (sbits >> 23) & 0xFF;
+    if (std::isnan(x) || field == 0xFF)
+        fail("6-bit conversion of a NaN (or with a NaN scale) is not modelled");
+    const int bias = (1 << (ebits - 1)) - 1, emin = 1 - bias, emax = (1 << ebits) - 1 - bias;
+    const double top = std::ldexp((double)((1 << (mbits + 1)) - 1), emax - mbits);
+    double t = std::ldexp(std::fabs((double)x), -(field == 0 ? -127 : field - 127));
+    if (t > top)
+        t = top;
+    int e = emin;
+    if (t > 0) {
+        int ex;
+        std::frexp(t, &ex);
+        e = std::min(std::max(ex - 1, emin), emax);
+    }
+    const int q = (int)std::nearbyint(std::ldexp(t, mbits - e));  // default rounding mode: nearest even
+    return (uint32_t)(((e - emin) << mbits) + q) | (std::signbit(x) ? 32u : 0u);
+}
+inline v6u cvt_scalef32_2xpk16_6bit(v16f a, v16f b, float scale, int ebits, int mbits)
+{
+    uint64_t bits[3] = {0, 0, 0};
+    for (int i = 0; i < 32; ++i) {
+        const uint64_t c = cvt_scaled_fp6(i % 2 ? b[i / 2] : a[i / 2], scale, ebits, mbits);
+        const int pos = 6 * i;
+        bits[pos / 64] |= c << (pos % 64);
+        if (pos % 64 > 58)
+            bits[pos / 64 + 1] |= c >> (64 - pos % 64);
+    }
+    v6u r;
+    for (int j = 0; j < 6; ++j)
+        r[j] = (uint32_t)(bits[j / 2] >> (32 * (j % 2)));
+    return r;
+}
 // ---- FP8 (OCP E5M2: 1-5-2, bias 15, subnormals, exponent field 31 = Inf / NaN) ------------------------
 inline double e5m2_value(uint8_t code)
 {
