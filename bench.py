@@ -27,7 +27,8 @@ per compute unit) on the same tensor under the same rotation, `torch_copy_gbs` t
 against the product followed by a stand-alone quantize of Y; `simulated_path` times the BF16 product of the
 round-tripped operands (Section 3.1) against the BF16 matrix peak; `grouped_moe` times the grouped forward
 product of a mixture-of-experts layer (Appendix A.4); `mxfp4_path` times the MXFP4 conversion of X and the forward
-product on MXFP4 operands (Table 1) against the 4-bit matrix peak.
+product on MXFP4 operands (Table 1) against the 4-bit matrix peak; `mxfp6_path` the MXFP6 conversion, the exact
+expansion to E4M3 bytes and the product of the expanded operands.
 `layer_set_16384` times the three products of each linear layer of an 8B-class transformer block at
 16384 tokens. `cpu_baseline` times the CPU oracle on a bounded sample.
 """
@@ -345,6 +346,21 @@ def main():
                 "kernel": f"gemm_persistent_kernel, MXFP4 operands (fprop {T}x{O}x{H}, BF16 out)", "avg_ms": ms, "launches": 20,
                 "quantize_X_both_ms": q_ms, "quantize_X_both_gbs": T * H * (2 + 2 * (0.5 + 1 / 32)) / (q_ms * 1e-3) / 1e9}
 
+    def mxfp6_path():
+        """Table 1's 6-bit formats on the same layer: X and W converted to MXFP6-E2M3, expanded exactly to E4M3 bytes
+        and multiplied by the MXFP8 product kernel; the rate counts expansion of both operands plus the product."""
+        xq = mx.fp6_quantize(X, mx.E2M3, "both", lay)
+        wq = mx.fp6_quantize(W, mx.E2M3, "rowwise", lay)
+        x8, w8 = torch.empty((T, H), dtype=torch.uint8, device=dev), torch.empty((O, H), dtype=torch.uint8, device=dev)
+        q_ms = ms_avg(lambda: mx.mxfp8_fp6_quantize_ex(X, mx.BOTH, mx.E2M3, xq["q_row"], xq["s_row"], xq["q_colT"], xq["s_colT"], lay))
+        e_ms = ms_avg(lambda: (mx.mxfp8_fp6_expand_ex(xq["q_row"], mx.E2M3, x8), mx.mxfp8_fp6_expand_ex(wq["q_row"], mx.E2M3, w8)))
+        g_ms = ms_avg(lambda: mx.mxfp8_gemm_ex(mx.FPROP, x8, xq["s_row"], w8, wq["s_row"], Y, lay))
+        tf = gemm_flop / ((e_ms + g_ms) * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": tf, "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_FP8_PEAK_TFLOPS,
+                "kernel": f"expand_fp6_kernel x2 + gemm_persistent_kernel (fprop {T}x{O}x{H}, BF16 out, E2M3 operands as E4M3)",
+                "expand_ms": e_ms, "gemm_ms": g_ms, "quantize_X_both_ms": q_ms,
+                "quantize_X_both_gbs": T * H * (2 + 2 * (0.75 + 1 / 32)) / (q_ms * 1e-3) / 1e9}
+
     def sustained_mfma_tflops(element_bits=8):
         """What the matrix pipes of this GPU sustain on the scaled matrix instruction alone (E4M3 or E2M1 operands in
         registers, pseudo-random bits, no memory traffic), at the clock the power management settles on: the ceiling
@@ -393,7 +409,7 @@ def main():
         extras["quant_bf16"] = (q_ms, q_fp, 160, rotating_copy_gbs(X, 8, 160))
         extras["quant_f32"] = (f_ms, f_fp, 100, rotating_copy_gbs(dY, 2, 100))
         for key, fn in (("fused_output_quantization", fused_output_quantization), ("simulated_path", simulated_path),
-                        ("grouped_moe", grouped_moe), ("single_copy", single_copy), ("mxfp4_path", mxfp4_path),
+                        ("grouped_moe", grouped_moe), ("single_copy", single_copy), ("mxfp4_path", mxfp4_path), ("mxfp6_path", mxfp6_path),
                         ("layer_set", layer_set)):
             try:
                 extras[key] = fn()
@@ -450,7 +466,7 @@ def main():
                         "plain_copy_gbs": copy_gbs[0], "frac_of_plain_copy": gbs / copy_gbs[0], "torch_copy_gbs": copy_gbs[1]}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
-    for key in ("fused_output_quantization", "simulated_path", "grouped_moe", "single_copy", "mxfp4_path"):
+    for key in ("fused_output_quantization", "simulated_path", "grouped_moe", "single_copy", "mxfp4_path", "mxfp6_path"):
         if key in extras:
             out[key] = extras[key]
     if "layer_set" in extras:
