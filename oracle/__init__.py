@@ -333,3 +333,14 @@ def dequantize_mode(q: np.ndarray, s: np.ndarray, fmt: str = "e4m3") -> np.ndarr
     out = np.empty((rows, cols), np.float64)
     _load().mxo_dequantize_mode_f64(_u8(q), _u8(s), rows, cols, out.ctypes.data, _FMT[fmt])
     return out
+
+
+def gemm_mode(a_q, a_s, a_fmt, b_q, b_s, b_fmt):
+    """C = A * B^T with each operand's elements in its own FP8 format ('e4m3' or 'e5m2'; Section 3.2.2 compares
+    them per tensor type): the block-scaled sum of Section 2 / Appendix A.3 written as the product of the decoded
+    operands in double (every decoded value and every product of two is exact there). Returns (C, sum|a*b|)."""
+    da, db = dequantize_mode(a_q, a_s, a_fmt), dequantize_mode(b_q, b_s, b_fmt)
+    if da.shape[1] != db.shape[1]:
+        raise ValueError("operands disagree on K")
+    with np.errstate(invalid="ignore", over="ignore"):
+        return da @ db.T, np.abs(da) @ np.abs(db).T

@@ -21,6 +21,13 @@
 // the 16 lanes of a fragment read hit 16 different bank groups. A direct-to-LDS load writes lane l
 // of a wavefront to LDS offset 16*l, so the swizzle is applied on the global side: each lane
 // fetches the chunk that belongs at its slot.
+//
+// Other operand formats on the same kernels (GemmCfg's FMT): plain BF16 operands for the product of the
+// simulated path (two 16x16x32 BF16 instructions per K step and tile pair, no scales), and MXFP4 operands
+// (two E2M1 codes per byte: a 128-byte K step is 256 elements, i.e. two 4-bit scaled instructions and two scale
+// dwords per row). With 4-bit elements the instruction takes dwords 0..3 only, lane (r, g) holds K =
+// 32g..32g+31 of row r and its own scale byte applies to them (pinned on the hardware by a test that runs
+// single instructions on registers taken from memory).
 #include "mxfp8_device.h"
 
 namespace mxfp8 {

@@ -121,3 +121,33 @@ def test_e5m2_row_quantization_end_to_end_against_the_library_cast():
     want = t.to(torch.float8_e5m2).view(torch.uint8).numpy()
     assert np.array_equal(q, want)
     assert int(s[5, 0]) + 1 == int(s[6, 0])
+
+
+def test_mixed_format_product_against_the_recipe_product_and_brute_force():
+    """gemm_mode with E4M3 x E4M3 is the recipe's product (the C triple loop); with an E5M2 operand it is the
+    block-scaled double sum written out in exact rationals on a tiny case."""
+    from fractions import Fraction
+    rng = np.random.default_rng(21)
+    a = (rng.standard_normal((5, 96)) * np.exp2(rng.integers(-5, 6, (5, 1)))).astype(np.float32)
+    b = (rng.standard_normal((4, 96)) * 0.03).astype(np.float32)
+    a4, b4 = oracle.quantize_rowwise(a), oracle.quantize_rowwise(b)
+    C0, A0 = oracle.gemm(*a4, *b4)
+    C1, A1 = oracle.gemm_mode(a4[0], a4[1], "e4m3", b4[0], b4[1], "e4m3")
+    assert np.allclose(C0, C1, rtol=0, atol=1e-14 * A0.max()) and np.allclose(A0, A1, rtol=1e-14)
+    a5 = oracle.quantize_rowwise_mode(a, "e5m2")
+    for fa, qa, fb, qb in (("e5m2", a5, "e4m3", b4), ("e4m3", a4, "e5m2", oracle.quantize_rowwise_mode(b, "e5m2")), ("e5m2", a5, "e5m2", oracle.quantize_rowwise_mode(b, "e5m2"))):
+        C, A = oracle.gemm_mode(qa[0], qa[1], fa, qb[0], qb[1], fb)
+        dec = {"e4m3": oracle.e4m3_decode, "e5m2": oracle.e5m2_decode}
+        for m in range(5):
+            for n in range(4):
+                tot = tot_abs = Fraction(0)
+                for blk in range(3):
+                    inner = inner_abs = Fraction(0)
+                    for i in range(32):
+                        p = Fraction(dec[fa](int(qa[0][m, 32 * blk + i]))) * Fraction(dec[fb](int(qb[0][n, 32 * blk + i])))
+                        inner += p
+                        inner_abs += abs(p)
+                    sc = Fraction(2) ** (int(qa[1][m, blk]) + int(qb[1][n, blk]) - 254)
+                    tot += sc * inner
+                    tot_abs += sc * inner_abs
+                assert abs(Fraction(C[m, n]) - tot) <= Fraction(2) ** -45 * tot_abs and Fraction(A[m, n]) == tot_abs
