@@ -168,6 +168,15 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
                            void *c, mxfp8_dtype c_dtype, int64_t ldc, mxfp8_scale_layout scale_layout,
                            int32_t max_workgroups, void *hip_stream);
 
+/* mxfp8_gemm_ex with the element format of each operand chosen by the caller (Table 1; Section 3.2.2 compares E4M3
+ * and E5M2 for weights, activations and gradients): a_q holds a_element codes, b_q b_element codes, as
+ * mxfp8_quantize_mode_ex writes them; the same sum with the other decode table. E5M2 has Inf and NaN codes (the
+ * quantizer never writes them): they propagate as in IEEE arithmetic. Unknown element: MXFP8_ERR_MODE. */
+mxfp8_status mxfp8_gemm_mode_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, mxfp8_element a_element,
+                                const uint8_t *b_q, const uint8_t *b_s, mxfp8_element b_element, int64_t M,
+                                int64_t N, int64_t K, void *c, mxfp8_dtype c_dtype, int64_t ldc,
+                                mxfp8_scale_layout scale_layout, int32_t max_workgroups, void *hip_stream);
+
 /*
  * Single-copy storage (Section 5 names the two stored copies per tensor as the overhead to remove): keep
  * only the row copy of a tensor and derive the column copy from it when the backward pass needs it. Every

@@ -86,6 +86,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp8_fp6_dequantize_ex.restype = ci
     lib.mxfp8_fp6_expand_ex.argtypes = [vp, i64, i64, ci, vp, vp]
     lib.mxfp8_fp6_expand_ex.restype = ci
+    lib.mxfp8_gemm_mode_ex.argtypes = [ci, vp, vp, ci, vp, vp, ci, i64, i64, i64, vp, ci, i64, ci, ctypes.c_int32, vp]
+    lib.mxfp8_gemm_mode_ex.restype = ci
     lib.mxfp8_mfma_rate_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.mxfp8_copy_rate_probe.restype = ci
     lib.mxfp8_mfma_rate_probe_ex.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
@@ -206,6 +208,28 @@ def mxfp8_gemm_ex(pass_, a_q, a_s, b_q, b_s, c, scale_layout=SCALES_ROWMAJOR, ma
                               _dtype_code(c.dtype), ldc, scale_layout, max_workgroups, _stream(stream))
     if rc != OK:
         raise MXFP8Error(rc, "mxfp8_gemm")
+
+
+def mxfp8_gemm_mode_ex(pass_, a_q, a_s, a_element, b_q, b_s, b_element, c, scale_layout=SCALES_ROWMAJOR, max_workgroups=0,
+                       stream=None) -> None:
+    """mxfp8_gemm_ex with the element format (E4M3 / E5M2) of each operand chosen by the caller."""
+    _need_cuda(a_q, a_s, b_q, b_s, c)
+    M, K = a_q.shape
+    N, Kb = b_q.shape
+    if K != Kb:
+        raise ValueError("operand shapes disagree")
+    _check_scales(a_s, M, K, scale_layout, "a_s")
+    _check_scales(b_s, N, K, scale_layout, "b_s")
+    if tuple(c.shape) != (M, N) or (c.numel() and c.stride(1) != 1):
+        raise ValueError("c must be [M x N] with contiguous rows")
+    for t in (a_q, a_s, b_q, b_s):
+        if not t.is_contiguous() or t.dtype != torch.uint8:
+            raise ValueError("quantized operands must be dense uint8")
+    ldc = c.stride(0) if M > 1 else max(N, 1)
+    rc = load().mxfp8_gemm_mode_ex(_PASS[pass_], _ptr(a_q), _ptr(a_s), a_element, _ptr(b_q), _ptr(b_s), b_element, M, N, K,
+                                   _ptr(c), _dtype_code(c.dtype), ldc, scale_layout, max_workgroups, _stream(stream))
+    if rc != OK:
+        raise MXFP8Error(rc, "mxfp8_gemm_mode_ex")
 
 
 def mxfp8_requantize_colwise_ex(q_row, s_row, q_colT, s_colT, scale_layout=SCALES_ROWMAJOR, stream=None) -> None:
@@ -640,3 +664,9 @@ def fp6_expand(q, element):
 def fp6_gemm(pass_, a_q, a_s, a_element, b_q, b_s, b_element, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
     """Product of two MXFP6 operands: both expanded to E4M3 bytes, then the MXFP8 product with the operands' own scales."""
     return gemm(pass_, fp6_expand(a_q, a_element), a_s, fp6_expand(b_q, b_element), b_s, out_dtype, scale_layout, max_workgroups)
+
+
+def gemm_mode(pass_, a_q, a_s, a_element, b_q, b_s, b_element, out_dtype=torch.float32, scale_layout=SCALES_ROWMAJOR, max_workgroups=0):
+    c = torch.empty((a_q.shape[0], b_q.shape[0]), dtype=out_dtype, device=a_q.device)
+    mxfp8_gemm_mode_ex(pass_, a_q, a_s, a_element, b_q, b_s, b_element, c, scale_layout, max_workgroups)
+    return c

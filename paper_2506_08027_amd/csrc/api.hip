@@ -31,6 +31,9 @@ hipError_t launch_quantize_fp6(const void *src, bool bf16, int64_t rows, int64_t
 hipError_t launch_dequantize_fp6(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, bool e3m2, void *dst, bool bf16,
                                  bool tiled, int64_t ld, hipStream_t stream);
 hipError_t launch_expand_fp6(const uint8_t *q, int64_t rows, int64_t cols, bool e3m2, uint8_t *q8, hipStream_t stream);
+hipError_t launch_gemm_elements(const uint8_t *a_q, const uint8_t *a_s, bool a_e5m2, const uint8_t *b_q, const uint8_t *b_s,
+                                bool b_e5m2, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                                int max_workgroups, hipStream_t stream);
 hipError_t launch_requantize_colwise(const uint8_t *q_row, const uint8_t *s_row, int64_t rows, int64_t cols, uint8_t *q_colT,
                                      uint8_t *s_colT, bool tiled_scales, hipStream_t stream);
 hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s,
@@ -166,6 +169,34 @@ mxfp8_status mxfp8_gemm_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a
     const hipError_t e = mxfp8::launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_dtype == MXFP8_BF16,
                                             scale_layout == MXFP8_SCALES_TILED, ldc, max_workgroups,
                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
+}
+
+mxfp8_status mxfp8_gemm_mode_ex(mxfp8_pass pass, const uint8_t *a_q, const uint8_t *a_s, mxfp8_element a_element,
+                                const uint8_t *b_q, const uint8_t *b_s, mxfp8_element b_element, int64_t M, int64_t N,
+                                int64_t K, void *c, mxfp8_dtype c_dtype, int64_t ldc, mxfp8_scale_layout scale_layout,
+                                int32_t max_workgroups, void *hip_stream)
+{
+    if (!valid_dtype(c_dtype))
+        return MXFP8_ERR_DTYPE;
+    if (!valid_layout(scale_layout) || max_workgroups < 0 || (a_element != MXFP8_E4M3 && a_element != MXFP8_E5M2) ||
+        (b_element != MXFP8_E4M3 && b_element != MXFP8_E5M2))
+        return MXFP8_ERR_MODE;
+    if (pass != MXFP8_FPROP && pass != MXFP8_DGRAD && pass != MXFP8_WGRAD)
+        return MXFP8_ERR_MODE;
+    if (M < 0 || N < 0 || K < 0 || M > kMaxGemmMN || N > kMaxGemmMN || K > kMaxGemmK || K % 128 || ldc < N ||
+        ((M + 127) / 128) * ((N + 127) / 128) > kMaxDim)
+        return MXFP8_ERR_SHAPE;
+    if (M == 0 || N == 0)
+        return MXFP8_OK;
+    if (!c || (K > 0 && (!a_q || !a_s || !b_q || !b_s)))
+        return MXFP8_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(c) % esize(c_dtype) ||
+        (K > 0 && (!aligned16(a_q) || !aligned16(a_s) || !aligned16(b_q) || !aligned16(b_s))))
+        return MXFP8_ERR_ALIGN;
+    const hipError_t e = mxfp8::launch_gemm_elements(a_q, a_s, a_element == MXFP8_E5M2, b_q, b_s, b_element == MXFP8_E5M2, M, N, K, c,
+                                                     c_dtype == MXFP8_BF16, scale_layout == MXFP8_SCALES_TILED, ldc,
+                                                     max_workgroups, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP8_OK : MXFP8_ERR_HIP;
 }
 

@@ -41,9 +41,13 @@ constexpr int kStageBytes = 4608;  // per-wavefront LDS area of the persistent k
 // 8 scale blocks (two scale dwords per row) per K step. Everything about tiles, buffers, data requests and the
 // schedule is counted in BYTES of a K-contiguous operand row and is the same for all three.
 constexpr int kFmtFp8 = 0, kFmtBf16 = 1, kFmtFp4 = 2;
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int FMT_ = kFmtFp8> struct GemmCfg {
+// A_E5M2 / B_E5M2 (kFmtFp8 only): the elements of that operand are E5M2 instead of E4M3 (Section 3.2.2 compares the
+// two per tensor type); nothing but the format fields of the matrix instruction changes.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int FMT_ = kFmtFp8, bool A_E5M2_ = false, bool B_E5M2_ = false> struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
     static constexpr int FMT = FMT_;
+    static constexpr bool A_E5M2 = A_E5M2_, B_E5M2 = B_E5M2_, ALL_E4M3 = FMT_ == kFmtFp8 && !A_E5M2_ && !B_E5M2_;
+    static_assert(FMT_ == kFmtFp8 || (!A_E5M2_ && !B_E5M2_), "element formats belong to the MXFP8 product");
     static constexpr bool SCALED = FMT_ != kFmtBf16;
     static constexpr int SDW = FMT_ == kFmtFp4 ? 2 : 1;     // scale dwords per operand row and K step
     static constexpr int SBLK = FMT_ == kFmtFp4 ? 16 : 32;  // operand bytes per scale block
@@ -105,11 +109,14 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
 // and its own scale byte applies to it): two scaled instructions over 128 k each; the scale registers carry
 // the byte of block g in bits 7:0 and that of block 4+g in bits 15:8.
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-template <int FMT>
+template <class Cfg>
 __device__ __forceinline__ v4f mma_step(const v8i &first, const v8i &second, v4f acc, int s_first, int s_second)
 {
+    constexpr int FMT = Cfg::FMT;
     if constexpr (FMT == kFmtFp8) {
-        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(first, second, acc, 0, 0, 0, s_first, 0, s_second);
+        // format fields: 0 = E4M3, 1 = E5M2; the kernels feed B fragments as the first operand, A as the second
+        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(first, second, acc, Cfg::B_E5M2 ? 1 : 0, Cfg::A_E5M2 ? 1 : 0, 0,
+                                                                s_first, 0, s_second);
     } else if constexpr (FMT == kFmtFp4) {
         const v8i f0 = {first[0], first[1], first[2], first[3], 0, 0, 0, 0}, f1 = {first[4], first[5], first[6], first[7], 0, 0, 0, 0};
         const v8i s0 = {second[0], second[1], second[2], second[3], 0, 0, 0, 0}, s1 = {second[4], second[5], second[6], second[7], 0, 0, 0, 0};
@@ -185,7 +192,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
     }
     const int m0 = tile_m * Cfg::BM, n0 = tile_n * Cfg::BN;
     // K is the length of an operand row in BYTES (= elements for MXFP8, 2 x elements for BF16 operands)
-    static_assert(!KGROUPED || Cfg::FMT == kFmtFp8, "grouped products take MXFP8 operands");
+    static_assert(!KGROUPED || Cfg::ALL_E4M3, "grouped products take MXFP8-E4M3 operands");
     const int nkb = K / Cfg::SBLK;  // scale bytes per row
     const int KT = k_len / BK;      // steps of this workgroup
     const int KT_row = K / BK;   // steps in a whole operand row (the pitch of the tiled scale layout)
@@ -340,7 +347,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(
             MXFP8_PIN();
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                acc[i][j] = mma_step<Cfg::FMT>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
+                acc[i][j] = mma_step<Cfg>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
                 MXFP8_PIN();
                 if (j == 0) {
                     issue_b(i, kt1, nxt);
@@ -468,12 +475,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
     int tiles_m, int tiles_n, uint8_t *__restrict__ cq, uint8_t *__restrict__ cs, uint8_t *__restrict__ cqT,
     uint8_t *__restrict__ csT, GemmGroups groups)
 {
-    static_assert(!GROUPED || (FUSE_Q == 0 && Cfg::FMT == kFmtFp8), "grouped products: MXFP8 operands, plain epilogue");
+    static_assert(!GROUPED || (FUSE_Q == 0 && Cfg::ALL_E4M3), "grouped products: MXFP8-E4M3 operands, plain epilogue");
     static_assert(!FUSE_Q || (OUT_BF16 && (Cfg::TN == 8 || Cfg::TN == 4) && Cfg::TM == Cfg::TN), "fused output quantization");
     constexpr bool Q_ROW = (FUSE_Q & 1) != 0, Q_COL = (FUSE_Q & 2) != 0;
     static_assert(!Q_COL || Cfg::BM * Cfg::BN <= 2 * Cfg::B_BYTES, "transposed tile fits the two idle buffers");
     static_assert(!Cfg::SCALED || (Cfg::SA_LOADS == Cfg::SDW && Cfg::SB_LOADS == Cfg::SDW), "one scale request per wavefront, operand and scale dword");
-    static_assert(Cfg::FMT == kFmtFp8 || FUSE_Q == 0, "output quantization belongs to the MXFP8 product");
+    static_assert(Cfg::ALL_E4M3 || FUSE_Q == 0, "output quantization belongs to the MXFP8-E4M3 product");
     MXFP8_DYNAMIC_LDS(lds);
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     const int tid = threadIdx.x;
@@ -643,7 +650,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_persistent_kernel(
             MXFP8_PIN();
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                acc[i][j] = mma_step<Cfg::FMT>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
+                acc[i][j] = mma_step<Cfg>(fb[j % NFB], fa[i], acc[i][j], sb[j % NFB], sa[i]);
                 MXFP8_PIN();
                 if constexpr (SPREAD) {
                     // SCHED = 100 * gap + 10 * A spacing + B spacing (in MFMAs)
@@ -1140,6 +1147,32 @@ hipError_t launch_gemm_grouped(const uint8_t *a_q, const uint8_t *a_s, const uin
                             : launch_grouped_cfg<CFG, false, false>(a_q, a_s, b_q, b_s, g, m, n, k, c, ldc, max_workgroups, stream)))
     return big ? MXFP8_GROUPED(Big) : MXFP8_GROUPED(Small);
 #undef MXFP8_GROUPED
+}
+
+// MXFP8 product with the element format of each operand chosen by the caller (E4M3 or E5M2: Section 3.2.2).
+template <bool A5, bool B5>
+static hipError_t launch_gemm_elements_t(const uint8_t *a_q, const uint8_t *a_s, const uint8_t *b_q, const uint8_t *b_s, int64_t M,
+                                         int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                                         int max_workgroups, hipStream_t stream)
+{
+    using Big = GemmCfg<256, 256, 2, 2, kFmtFp8, A5, B5>;
+    using Small = GemmCfg<128, 128, 2, 2, kFmtFp8, A5, B5>;
+    const bool big = ((M + 255) / 256) * ((N + 255) / 256) >= 128;
+    if (big)
+        return launch_any<Big>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, max_workgroups, stream);
+    return launch_any<Small>(a_q, a_s, b_q, b_s, (int)M, (int)N, (int)K, c, c_bf16, tiled_scales, ldc, max_workgroups, stream);
+}
+
+hipError_t launch_gemm_elements(const uint8_t *a_q, const uint8_t *a_s, bool a_e5m2, const uint8_t *b_q, const uint8_t *b_s,
+                                bool b_e5m2, int64_t M, int64_t N, int64_t K, void *c, bool c_bf16, bool tiled_scales, int64_t ldc,
+                                int max_workgroups, hipStream_t stream)
+{
+    if (a_e5m2)
+        return b_e5m2 ? launch_gemm_elements_t<true, true>(a_q, a_s, b_q, b_s, M, N, K, c, c_bf16, tiled_scales, ldc, max_workgroups, stream)
+                      : launch_gemm_elements_t<true, false>(a_q, a_s, b_q, b_s, M, N, K, c, c_bf16, tiled_scales, ldc, max_workgroups, stream);
+    if (b_e5m2)
+        return launch_gemm_elements_t<false, true>(a_q, a_s, b_q, b_s, M, N, K, c, c_bf16, tiled_scales, ldc, max_workgroups, stream);
+    return launch_gemm(a_q, a_s, b_q, b_s, M, N, K, c, c_bf16, tiled_scales, ldc, max_workgroups, stream);
 }
 
 // Product of two MXFP4 operands (Table 1: E2M1 elements, two per byte), [M x K/2] and [N x K/2] bytes with K/32

@@ -319,6 +319,24 @@ int main(int argc, char **argv)
             unchanged(sb, "s");
             report(st);
             save(out, o);
+        } else if (op == "gemmmode") {
+            int pass, ea, eb;
+            long M, N, K, ldc;
+            std::string dt, aq, as, bq, bs, cout;
+            ls >> pass >> M >> N >> K >> ea >> eb >> dt >> ldc >> aq >> as >> bq >> bs >> cout;
+            const mxfp8_scale_layout lay = layout_of(ls);
+            const size_t es = dt == "bf16" ? 2 : 4;
+            Buf a = load(aq, (size_t)M * K), sa = load(as, (size_t)mxfp8_scale_bytes(M, K, lay));
+            Buf b = load(bq, (size_t)N * K), sb = load(bs, (size_t)mxfp8_scale_bytes(N, K, lay));
+            Buf c = output(M > 0 ? ((size_t)(M - 1) * ldc + N) * es : 0);
+            const int st = mxfp8_gemm_mode_ex((mxfp8_pass)pass, a.p, sa.p, (mxfp8_element)ea, b.p, sb.p, (mxfp8_element)eb, M, N, K, c.p,
+                                              dtype_of(dt), ldc, lay, g_max_workgroups, nullptr);
+            unchanged(a, "a_q");
+            unchanged(sa, "a_s");
+            unchanged(b, "b_q");
+            unchanged(sb, "b_s");
+            report(st);
+            save(cout, c);
         } else if (op == "gemmfp4") {
             int pass;
             long M, N, K, ldc;

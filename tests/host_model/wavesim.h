@@ -509,9 +509,10 @@ inline double e2m1_value(unsigned code)
 inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp, int opsel_first, int scale_first,
                                 int opsel_second, int scale_second)
 {
-    if (cbsz != blgp || (cbsz != 0 && cbsz != 4))
-        fail("only E4M3 x E4M3 and E2M1 x E2M1 operands are modelled");
+    if (!((cbsz == 4 && blgp == 4) || (cbsz <= 1 && blgp <= 1)))
+        fail("only FP8 x FP8 (E4M3 / E5M2 per operand) and E2M1 x E2M1 operands are modelled");
     const bool fp4 = cbsz == 4;
+    const bool first_e5m2 = cbsz == 1, second_e5m2 = blgp == 1;  // format field of the first / second operand
     struct Pub {
         v8i first, second;
         uint8_t s_first, s_second;
@@ -533,8 +534,8 @@ inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp
                 yv[32 * kg + 2 * t] = e2m1_value(bytes[t] & 0xF);
                 yv[32 * kg + 2 * t + 1] = e2m1_value(bytes[t] >> 4);
             } else {
-                yv[16 * kg + t] = e4m3_value(bytes[t]);
-                yv[64 + 16 * kg + t] = e4m3_value(bytes[16 + t]);
+                yv[16 * kg + t] = second_e5m2 ? e5m2_value(bytes[t]) : e4m3_value(bytes[t]);
+                yv[64 + 16 * kg + t] = second_e5m2 ? e5m2_value(bytes[16 + t]) : e4m3_value(bytes[16 + t]);
             }
         }
         ys[kg] = p.s_second == 0xFF ? NAN : std::ldexp(1.0, (int)p.s_second - 127);
@@ -553,8 +554,8 @@ inline v4f mfma_scale_16x16x128(v8i first, v8i second, v4f c, int cbsz, int blgp
                     xv[32 * kg + 2 * t] = e2m1_value(bytes[t] & 0xF);
                     xv[32 * kg + 2 * t + 1] = e2m1_value(bytes[t] >> 4);
                 } else {
-                    xv[16 * kg + t] = e4m3_value(bytes[t]);
-                    xv[64 + 16 * kg + t] = e4m3_value(bytes[16 + t]);
+                    xv[16 * kg + t] = first_e5m2 ? e5m2_value(bytes[t]) : e4m3_value(bytes[t]);
+                    xv[64 + 16 * kg + t] = first_e5m2 ? e5m2_value(bytes[16 + t]) : e4m3_value(bytes[16 + t]);
                 }
             }
             xs[kg] = p.s_first == 0xFF ? NAN : std::ldexp(1.0, (int)p.s_first - 127);

@@ -32,7 +32,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == ["mxfp8_copy_rate_probe", "mxfp8_dequantize", "mxfp8_dequantize_ex", "mxfp8_dequantize_mode_ex",
-                                    "mxfp8_fp4_dequantize_ex", "mxfp8_fp4_gemm_ex", "mxfp8_fp4_quantize_ex", "mxfp8_fp6_dequantize_ex", "mxfp8_fp6_expand_ex", "mxfp8_fp6_quantize_ex", "mxfp8_gemm", "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_layout_probe", "mxfp8_mfma_rate_probe", "mxfp8_mfma_rate_probe_ex", "mxfp8_quantize",
+                                    "mxfp8_fp4_dequantize_ex", "mxfp8_fp4_gemm_ex", "mxfp8_fp4_quantize_ex", "mxfp8_fp6_dequantize_ex", "mxfp8_fp6_expand_ex", "mxfp8_fp6_quantize_ex", "mxfp8_gemm", "mxfp8_gemm_bf16", "mxfp8_gemm_ex", "mxfp8_gemm_grouped_ex", "mxfp8_gemm_mode_ex", "mxfp8_gemm_quantize_ex", "mxfp8_mfma_layout_probe", "mxfp8_mfma_rate_probe", "mxfp8_mfma_rate_probe_ex", "mxfp8_quantize",
                                     "mxfp8_quantize_ex", "mxfp8_quantize_mode_ex", "mxfp8_requantize_colwise_ex", "mxfp8_scale_bytes",
                                     "mxfp8_status_string"]
 
@@ -197,6 +197,15 @@ def test_fp4_validation_needs_no_gpu(lib):
     assert g(FAKE, FAKE, 64, 48, FAKE, 0, 64, 0, None) == 2 and g(FAKE, FAKE, 64, 64, FAKE, 0, 32, 0, None) == 2
     assert g(None, FAKE, 64, 64, FAKE, 0, 64, 0, None) == 1 and g(FAKE, FAKE, 64, 64, P(0x1008), 0, 64, 0, None) == 3
     assert g(None, None, 64, 0, None, 0, 64, 0, None) == 0
+
+
+def test_gemm_mode_validation_needs_no_gpu(lib):
+    f = lib.mxfp8_gemm_mode_ex
+    f.argtypes = [ctypes.c_int, P, P, ctypes.c_int, P, P, ctypes.c_int, I64, I64, I64, P, ctypes.c_int, I64, ctypes.c_int, ctypes.c_int32, P]
+    assert f(0, FAKE, FAKE, 2, FAKE, FAKE, 0, 64, 64, 128, FAKE, 0, 64, 0, 0, None) == 5 and f(0, FAKE, FAKE, 1, FAKE, FAKE, 3, 64, 64, 128, FAKE, 0, 64, 0, 0, None) == 5
+    assert f(0, FAKE, FAKE, 1, FAKE, FAKE, 0, 64, 64, 128, FAKE, 2, 64, 0, 0, None) == 4 and f(0, FAKE, FAKE, 1, FAKE, FAKE, 0, 64, 64, 96, FAKE, 0, 64, 0, 0, None) == 2
+    assert f(0, None, FAKE, 1, FAKE, FAKE, 1, 64, 64, 128, FAKE, 0, 64, 0, 0, None) == 1 and f(0, FAKE, FAKE, 1, P(0x1004), FAKE, 1, 64, 64, 128, FAKE, 0, 64, 0, 0, None) == 3
+    assert f(0, None, None, 1, None, None, 0, 0, 64, 128, None, 0, 64, 0, 0, None) == 0
 
 
 def test_fp6_validation_needs_no_gpu(lib):

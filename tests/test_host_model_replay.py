@@ -91,3 +91,8 @@ def test_fp6_gpu_tests_pass_on_the_host_model(hostmodel_lib):
     """MXFP6 conversion, expansion and product; the full-size case is left to the GPU."""
     n = replay(hostmodel_lib, ["test_gpu_fp6.py"], "not full_size")
     assert n >= 31
+
+
+def test_gemm_mode_gpu_tests_pass_on_the_host_model(hostmodel_lib):
+    n = replay(hostmodel_lib, ["test_gpu_gemm_modes.py"], "not nothing")
+    assert n >= 12
