@@ -31,10 +31,15 @@ BINARY = os.path.join(MODEL_DIR, "_build", "hostmodel")
 SENTINEL = 0xA5
 
 
+_BUILT = []   # the other host-model test modules import this fixture: one build per session, not one per module
+
+
 @pytest.fixture(scope="session")
 def hostmodel():
-    res = subprocess.run([os.path.join(MODEL_DIR, "build.sh"), BINARY], capture_output=True, text=True)
-    assert res.returncode == 0, res.stderr[-4000:]
+    if not _BUILT:
+        res = subprocess.run([os.path.join(MODEL_DIR, "build.sh"), BINARY], capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr[-4000:]
+        _BUILT.append(BINARY)
     return BINARY
 
 

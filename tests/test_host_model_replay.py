@@ -3,7 +3,9 @@ test files of the `gpu` marker run unchanged, in a child pytest process whose bi
 host-model build of the library. Everything that fits the model's speed is selected: the exactness,
 special-value, ragged-shape, all-BF16-pattern, error-code and tolerance tests; the full-size cases are
 left to the GPU. A failure here means the GPU run would fail
-for a reason that has nothing to do with the hardware (a bug in a test or in a kernel's logic)."""
+for a reason that has nothing to do with the hardware (a bug in a test or in a kernel's logic).
+The child processes are independent of one another, so all of them are started when the first replay test runs
+and each test then waits for its own: the module takes as long as its longest replay, not the sum."""
 import os
 import re
 import subprocess
@@ -24,75 +26,67 @@ def hostmodel_lib():
     return LIB
 
 
-def replay(lib, files, select, extra_env=None):
+# name -> (test files, -k selection, least number of tests that must have run)
+PLAN = {
+    "core": (("test_gpu_quantize.py", "test_gpu_quantize_modes.py", "test_gpu_gemm.py"),
+             "not full_size and not transformer_layer", 50),
+    # everything but the cases whose size the model cannot run in minutes (the full-size layer and the
+    # 2048 x 4096 / 4352 x 4096 problems, which were replayed once by hand)
+    "layouts": (("test_gpu_scale_layouts_persistent_fused.py",),
+                "not full_size and not (quantize_tiled_matches and shape4) and not (gemm_tiled_matches and shape3) "
+                "and not (persistent_gemm_matches and (shape2 or shape3 or shape4)) "
+                "and not (fused_output and (shape2 or shape3))", 34),
+    # the long-K, 2048 x 4096 and full-size cases are left to the GPU
+    "simulated": (("test_gpu_simulated.py",),
+                  "not full_size and not (matches_oracle and (shape3 or shape4 or shape5)) and not (small_integers and shape7)", 18),
+    "grouped": (("test_gpu_grouped.py",), "not full_size and not equals_the_plain_product", 6),
+    "single_copy": (("test_gpu_single_copy.py",), "not full_size", 5),
+    "fp4": (("test_gpu_fp4.py",), "not full_size and not large_tiles", 28),
+    "mfma_layout": (("test_gpu_mfma_layout.py",), "layout or scale or operand", 7),
+    "fp6": (("test_gpu_fp6.py",), "not full_size", 31),
+    "gemm_modes": (("test_gpu_gemm_modes.py",), "not nothing", 12),
+}
+_RUNNING = {}   # name -> child process; all of them are started by the first call of replay()
+
+
+def _start(lib, files, select):
     env = dict(os.environ, MXFP8_HOSTMODEL_LIB=lib,
                PYTHONPATH=os.pathsep.join([MODEL_DIR, ROOT, os.environ.get("PYTHONPATH", "")]))
-    env.update(extra_env or {})
-    res = subprocess.run([sys.executable, "-m", "pytest", "-p", "no:cacheprovider", "-p", "replay_plugin", "-q", "-x",
-                          "-m", "gpu", "-k", select] + [os.path.join(HERE, f) for f in files],
-                         capture_output=True, text=True, cwd=ROOT, env=env, timeout=1500)
-    tail = (res.stdout + res.stderr)[-3000:]
-    assert res.returncode == 0, tail
-    m = re.search(r"(\d+) passed", res.stdout)
+    return subprocess.Popen([sys.executable, "-m", "pytest", "-p", "no:cacheprovider", "-p", "replay_plugin", "-q", "-x",
+                             "-m", "gpu", "-k", select] + [os.path.join(HERE, f) for f in files],
+                            stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, cwd=ROOT, env=env)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _reap_children():
+    yield
+    for proc in _RUNNING.values():   # a failure with -x leaves the other replays running
+        if proc.poll() is None:
+            proc.kill()
+
+
+def replay(lib, name):
+    if not _RUNNING:
+        for key, (files, select, _) in PLAN.items():
+            _RUNNING[key] = _start(lib, files, select)
+    proc = _RUNNING[name]
+    try:
+        out, _ = proc.communicate(timeout=2400)
+    except subprocess.TimeoutExpired:
+        proc.kill()
+        raise
+    tail = out[-3000:]
+    assert proc.returncode == 0, tail
+    m = re.search(r"(\d+) passed", out)
     assert m, tail
-    return int(m.group(1))
+    assert int(m.group(1)) >= PLAN[name][2], tail
 
 
-def test_gpu_parity_tests_pass_on_the_host_model(hostmodel_lib):
-    n = replay(hostmodel_lib, ["test_gpu_quantize.py", "test_gpu_quantize_modes.py", "test_gpu_gemm.py"],
-               "not full_size and not transformer_layer")
-    assert n >= 50
-
-
-def test_layout_persistent_and_fused_gpu_tests_pass_on_the_host_model(hostmodel_lib):
-    """The parity tests of the tiled scale layout, the persistent kernel and the fused output quantization:
-    everything but the cases whose size the model cannot run in minutes (the full-size layer and the
-    2048 x 4096 / 4352 x 4096 problems, which were replayed once by hand)."""
-    n = replay(hostmodel_lib, ["test_gpu_scale_layouts_persistent_fused.py"],
-               "not full_size and not (quantize_tiled_matches and shape4) and not (gemm_tiled_matches and shape3) "
-               "and not (persistent_gemm_matches and (shape2 or shape3 or shape4)) "
-               "and not (fused_output and (shape2 or shape3))")
-    assert n >= 34
-
-
-def test_simulated_path_gpu_tests_pass_on_the_host_model(hostmodel_lib):
-    """The BF16 product and the round trip of the simulated path; the long-K, 2048 x 4096 and full-size cases
-    are left to the GPU."""
-    n = replay(hostmodel_lib, ["test_gpu_simulated.py"],
-               "not full_size and not (matches_oracle and (shape3 or shape4 or shape5)) and not (small_integers and shape7)")
-    assert n >= 18
-
-
-def test_grouped_gpu_tests_pass_on_the_host_model(hostmodel_lib):
-    """The grouped (mixture-of-experts) product; the 4096-token and full-size cases are left to the GPU."""
-    n = replay(hostmodel_lib, ["test_gpu_grouped.py"], "not full_size and not equals_the_plain_product")
-    assert n >= 6
-
-
-def test_single_copy_gpu_tests_pass_on_the_host_model(hostmodel_lib):
-    n = replay(hostmodel_lib, ["test_gpu_single_copy.py"], "not full_size")
-    assert n >= 5
-
-
-def test_fp4_gpu_tests_pass_on_the_host_model(hostmodel_lib):
-    """MXFP4 conversion and product; the full-size and 2048 x 4096 cases are left to the GPU."""
-    n = replay(hostmodel_lib, ["test_gpu_fp4.py"], "not full_size and not large_tiles")
-    assert n >= 28
-
-
-def test_matrix_instruction_layout_tests_pass_on_the_host_model(hostmodel_lib):
-    """The facts about the scaled matrix instruction that the GPU test pins on the hardware hold for the CPU
-    model of the instruction as well: the two cannot drift apart."""
-    n = replay(hostmodel_lib, ["test_gpu_mfma_layout.py"], "layout or scale or operand")
-    assert n >= 7
-
-
-def test_fp6_gpu_tests_pass_on_the_host_model(hostmodel_lib):
-    """MXFP6 conversion, expansion and product; the full-size case is left to the GPU."""
-    n = replay(hostmodel_lib, ["test_gpu_fp6.py"], "not full_size")
-    assert n >= 31
-
-
-def test_gemm_mode_gpu_tests_pass_on_the_host_model(hostmodel_lib):
-    n = replay(hostmodel_lib, ["test_gpu_gemm_modes.py"], "not nothing")
-    assert n >= 12
+@pytest.mark.parametrize("name", list(PLAN))
+def test_gpu_parity_tests_pass_on_the_host_model(hostmodel_lib, name):
+    """core: quantize / dequantize / GEMM parity; layouts: tiled scales, resident kernel, fused output quantization;
+    simulated: the BF16 product and round trip of the simulated path; grouped: mixture-of-experts products;
+    single_copy: the derived column copy; fp4 / fp6: the narrow formats; mfma_layout: the facts about the scaled matrix
+    instruction that the GPU test pins on the hardware hold for the CPU model of the instruction as well (the two
+    cannot drift apart); gemm_modes: per-operand element formats."""
+    replay(hostmodel_lib, name)
