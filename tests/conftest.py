@@ -10,15 +10,39 @@ if ROOT not in sys.path:
 
 def pytest_addoption(parser):
     parser.addoption("--runslow", action="store_true", default=False,
-                     help="also run the tests marked slow (the full mutation checks: tens of minutes)")
+                     help="also run the tests marked slow (the full mutation checks, the long cases of the kernels' CPU execution model)")
 
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
-    config.addinivalue_line("markers", "slow: takes tens of minutes; runs only with --runslow")
+    config.addinivalue_line("markers", "slow: long-running (minutes); runs only with --runslow")
+
+
+# Cases of the CPU execution model of the kernels (tests/test_host_model*.py) that run only with --runslow: the
+# second execution-order / scale-layout variant of a case whose first variant stays in the default run, and the
+# sampled-workgroup cases of the 256 x 256 configuration but one. They take 5 .. 20 s each (seven minutes together);
+# the default run keeps one case per kernel family, and the GPU parity tests replayed on the model
+# (tests/test_host_model_replay.py) walk the same kernels again. Before a changed kernel goes to a GPU: --runslow.
+SLOW_HOST_MODEL_CASES = (
+    "test_fp4_gemm_persistent_small_tiles", "test_fp4_gemm_persistent_large_tiles", "test_fp4_gemm_large_tiles_ragged",
+    "test_fp4_gemm_small_tiles_ragged[lazy-up-rowmajor]", "test_fp4_gemm_small_tiles_ragged[lazy-down-rowmajor]",
+    "test_fp4_gemm_small_tiles_ragged[eager-up-tiled]",
+    "test_fused_output_quantization_large_tiles", "test_gemm_large_tiles_sampled_workgroups",
+    "test_gemm_persistent_large_tiles_sampled_workgroups[False-down]", "test_gemm_tiled_scales_large_tiles",
+    "test_gemm_persistent_small_tiles[eager-down-tiled]", "test_gemm_small_tiles_ragged[eager-down]",
+    "test_fused_output_quantization_small_tiles[3-", "test_gemm_tiled_scales_small_tiles[eager-down]",
+    "test_grouped_wgrad_small_tiles", "test_grouped_large_tiles",
+    "test_grouped_small_tiles_partial_and_empty_experts[eager-down]", "test_grouped_small_tiles_partial_and_empty_experts[lazy-up]",
+    "test_bf16_gemm_persistent_small_tiles", "test_bf16_gemm_persistent_large_tiles", "test_bf16_gemm_large_tiles_ragged",
+    "test_bf16_gemm_small_tiles_ragged[eager-down]",
+    "test_gemm_modes_large_tiles", "test_gemm_modes_small_tiles[e5m2xe5m2]", "test_gemm_modes_small_tiles[e4m3xe5m2]",
+)
 
 
 def pytest_collection_modifyitems(config, items):
+    for item in items:
+        if "test_host_model" in item.nodeid and any(case in item.nodeid for case in SLOW_HOST_MODEL_CASES):
+            item.add_marker(pytest.mark.slow)
     if config.getoption("--runslow"):
         return
     skip = pytest.mark.skip(reason="slow: run with --runslow")
