@@ -14,6 +14,12 @@
  *               Section 3.2 / Figure 2, Appendix A.3), on the scaled MX MFMA instructions;
  *   dequantize  the decode Q_i * X (Section 2).
  *
+ * Around these three, each declared below with the passage it serves: the same calls with the scale bytes in a
+ * tiled layout and a bound on the workgroups (_ex); the product that also emits the MXFP8 copies of its output;
+ * E5M2 elements and the OCP v1 scale rule of the paper's ablations (_mode_ex, for quantize, dequantize and the
+ * product); the BF16 product of the simulated path; grouped products for mixture-of-experts layers; the column
+ * copy derived from a kept row copy; the MXFP4 and MXFP6 members of Table 1; and measurement aids.
+ *
  * Conventions common to every entry point
  *   - All data pointers are DEVICE pointers (HIP global memory of the current device). The
  *     caller owns every buffer; the library allocates nothing, keeps no state between calls and

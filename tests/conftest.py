@@ -1,4 +1,5 @@
 import os
+import subprocess
 import sys
 
 import pytest
@@ -54,3 +55,20 @@ def pytest_collection_modifyitems(config, items):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_collection_finish(session):
+    """The replayed GPU tests need the optimised shared build of the kernels' CPU model (a minute of compilation):
+    started here, in the background, as soon as it is known that they will run; their fixture waits for it."""
+    if session.config.option.collectonly or not any("test_host_model_replay" in item.nodeid for item in session.items):
+        return
+    model = os.path.join(ROOT, "tests", "host_model")
+    session.config._hostmodel_shared_build = subprocess.Popen(
+        [os.path.join(model, "build.sh"), "--shared", os.path.join(model, "_build", "libmxfp8_hostmodel.so")],
+        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    proc = getattr(session.config, "_hostmodel_shared_build", None)
+    if proc is not None and proc.poll() is None:   # the session ended before the replay tests asked for it
+        proc.kill()

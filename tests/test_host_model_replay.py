@@ -20,9 +20,14 @@ LIB = os.path.join(MODEL_DIR, "_build", "libmxfp8_hostmodel.so")
 
 
 @pytest.fixture(scope="module")
-def hostmodel_lib():
-    res = subprocess.run([os.path.join(MODEL_DIR, "build.sh"), "--shared", LIB], capture_output=True, text=True)
-    assert res.returncode == 0, res.stderr[-4000:]
+def hostmodel_lib(request):
+    proc = getattr(request.config, "_hostmodel_shared_build", None)   # started by conftest.py when collection ended
+    if proc is not None:
+        out, _ = proc.communicate()
+        assert proc.returncode == 0, out[-4000:]
+    else:
+        res = subprocess.run([os.path.join(MODEL_DIR, "build.sh"), "--shared", LIB], capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr[-4000:]
     return LIB
 
 
