@@ -40,8 +40,8 @@ MUTANTS = [  # (description, old text, new text): first occurrence, i.e. in the 
     ("ragged tile reads past the last row", "a_goff[i] = (uint32_t)min(row, M - 1 - m0) * (uint32_t)K + chunk * 16;",
      "a_goff[i] = (uint32_t)row * (uint32_t)K + chunk * 16;"),
     ("row-major scale dwords land in the wrong 64-row group",
-     "                dma_load<4>(as_tile + kt * 4, as_goff[i],\n                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);",
-     "                dma_load<4>(as_tile + kt * 4, as_goff[i],\n                            lds_base + Cfg::SA_OFF + buf * Cfg::BM * 4 + ((wave + 1 + i * Cfg::WAVES) % (Cfg::BM / 64)) * 256);"),
+     "                dma_load<4>(as_tile + (kt * SDW + dw) * 4, as_goff[i],\n                            lds_base + Cfg::SA_OFF + buf * Cfg::SA_BYTES + dw * Cfg::BM * 4 + a_grp(i) * 256);",
+     "                dma_load<4>(as_tile + (kt * SDW + dw) * 4, as_goff[i],\n                            lds_base + Cfg::SA_OFF + buf * Cfg::SA_BYTES + dw * Cfg::BM * 4 + ((a_grp(i) + 1) % (Cfg::BM / 64)) * 256);"),
     ("epilogue stores to the rows of another wavefront", "const int m = m0 + wm * Cfg::WM + i * 16 + r16;",
      "const int m = m0 + wn * Cfg::WM + i * 16 + r16;"),
 ]
@@ -119,6 +119,8 @@ def main():
     todo = [("(unmutated source: must pass)", "", "", 0), ("(unmutated source, persistent kernel: must pass)", "", "", 1)]
     todo += [m + (0,) for m in MUTANTS] + [m + (1,) for m in PERSISTENT_MUTANTS]
     only = sys.argv[1:]
+    for desc, old, new, persistent in todo:   # every pattern must still be in the source: a stale one would test nothing
+        assert old == "" or old in source, desc
     for desc, old, new, persistent in todo:
         if only and not any(o in desc for o in only):
             continue
