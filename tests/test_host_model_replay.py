@@ -57,6 +57,8 @@ _RUNNING = {}   # name -> child process; all of them are started by the first ca
 def _start(lib, files, select):
     env = dict(os.environ, MXFP8_HOSTMODEL_LIB=lib,
                PYTHONPATH=os.pathsep.join([MODEL_DIR, ROOT, os.environ.get("PYTHONPATH", "")]))
+    for var in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+        env[var] = "2"   # nine children side by side: the oracle's and numpy's thread pools must not each take every core
     return subprocess.Popen([sys.executable, "-m", "pytest", "-p", "no:cacheprovider", "-p", "replay_plugin", "-q", "-x",
                              "-m", "gpu", "-k", select] + [os.path.join(HERE, f) for f in files],
                             stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, cwd=ROOT, env=env)
