@@ -21,20 +21,20 @@ def pytest_configure(config):
 
 # Cases of the CPU execution model of the kernels (tests/test_host_model*.py) that run only with --runslow: the
 # second execution-order / scale-layout variant of a case whose first variant stays in the default run, and the
-# sampled-workgroup cases of the 256 x 256 configuration but one. They take 5 .. 20 s each (seven minutes together);
+# sampled-workgroup cases of the 256 x 256 configuration but one. They take 5 .. 20 s each (six minutes together);
 # the default run keeps one case per kernel family, and the GPU parity tests replayed on the model
 # (tests/test_host_model_replay.py) walk the same kernels again. Before a changed kernel goes to a GPU: --runslow.
 SLOW_HOST_MODEL_CASES = (
-    "test_fp4_gemm_persistent_small_tiles", "test_fp4_gemm_persistent_large_tiles", "test_fp4_gemm_large_tiles_ragged",
+    "test_fp4_gemm_persistent_small_tiles[eager-down-tiled]", "test_fp4_gemm_persistent_large_tiles", "test_fp4_gemm_large_tiles_ragged",
     "test_fp4_gemm_small_tiles_ragged[lazy-up-rowmajor]", "test_fp4_gemm_small_tiles_ragged[lazy-down-rowmajor]",
     "test_fp4_gemm_small_tiles_ragged[eager-up-tiled]",
     "test_fused_output_quantization_large_tiles", "test_gemm_large_tiles_sampled_workgroups",
     "test_gemm_persistent_large_tiles_sampled_workgroups[False-down]", "test_gemm_tiled_scales_large_tiles",
     "test_gemm_persistent_small_tiles[eager-down-tiled]", "test_gemm_small_tiles_ragged[eager-down]",
     "test_fused_output_quantization_small_tiles[3-", "test_gemm_tiled_scales_small_tiles[eager-down]",
-    "test_grouped_wgrad_small_tiles", "test_grouped_large_tiles",
+    "test_grouped_wgrad_small_tiles[eager-down-tiled]", "test_grouped_large_tiles",
     "test_grouped_small_tiles_partial_and_empty_experts[eager-down]", "test_grouped_small_tiles_partial_and_empty_experts[lazy-up]",
-    "test_bf16_gemm_persistent_small_tiles", "test_bf16_gemm_persistent_large_tiles", "test_bf16_gemm_large_tiles_ragged",
+    "test_bf16_gemm_persistent_small_tiles[eager-down]", "test_bf16_gemm_persistent_large_tiles", "test_bf16_gemm_large_tiles_ragged",
     "test_bf16_gemm_small_tiles_ragged[eager-down]",
     "test_gemm_modes_large_tiles", "test_gemm_modes_small_tiles[e5m2xe5m2]", "test_gemm_modes_small_tiles[e4m3xe5m2]",
 )
