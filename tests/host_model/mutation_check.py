@@ -4,8 +4,10 @@ copy of the GEMM kernel source -- a removed barrier, a wait count that is one to
 a swizzle mismatch, a prefetch into the wrong buffer or of the wrong K step, a missing ragged-tile clamp,
 a wrong output row -- builds the host model from it and runs a few products against the oracle in all
 four scheduling modes (lazy / eager DMA completion, either wavefront running ahead). Every mutant must
-be caught, by a wrong or NaN result or by the model's range check. Arguments, if any, select the mutants
-whose description contains one of them."""
+be caught, by a wrong or NaN result or by the model's range check. A second group plants mistakes into the
+converters (scale-rule constants, the staging swizzle of the transposed copy, a removed barrier, the infinity patch,
+the narrow formats' scale rules) and compares the quantized bytes with the oracle's. Arguments, if any, select the
+mutants whose description contains one of them."""
 import os
 import shutil
 import subprocess
@@ -65,10 +67,10 @@ PERSISTENT_MUTANTS = [
 MODES = [{}, {"WAVESIM_ORDER": "down"}, {"WAVESIM_DMA": "eager"}, {"WAVESIM_DMA": "eager", "WAVESIM_ORDER": "down"}]
 
 
-def build(work, gemm_text):
+def build(work, text, name="gemm.hip"):
     csrc = os.path.join(work, "csrc")
     shutil.copytree(os.path.join(ROOT, "paper_2506_08027_amd", "csrc"), csrc)
-    open(os.path.join(csrc, "gemm.hip"), "w").write(gemm_text)
+    open(os.path.join(csrc, name), "w").write(text)
     inc = os.path.join(ROOT, "include", "mxfp8.h")
     for name, path in (("api.hip", csrc), ("driver.cpp", work)):
         src = os.path.join(csrc if name == "api.hip" else HERE, name)
@@ -113,6 +115,56 @@ def caught(binary, work, persistent=0):
     return None
 
 
+# mistakes in the converters: (description, source file, old text, new text), first occurrence
+QUANT_MUTANTS = [
+    ("quantizer: FP32 scale rule carries at 1.875 instead of 1.75", "mxfp8_device.h",
+     "(abs_bits + 0x1FFFFFu) >> 23) - 8", "(abs_bits + 0x0FFFFFu) >> 23) - 8"),
+    ("quantizer: BF16 scale rule carries at 1.875 instead of 1.75", "mxfp8_device.h",
+     "(abs_bits16 + 0x1Fu) >> 7) - 8", "(abs_bits16 + 0x0Fu) >> 7) - 8"),
+    ("quantizer: staging swizzle of the transposed copy differs from the write-out's", "quantize.hip",
+     "const int slot16 = (lrow0 >> 4) ^ (cc & 7);", "const int slot16 = (lrow0 >> 4) ^ ((cc + 1) & 7);"),
+    ("quantizer: barrier between staging and write-out removed", "quantize.hip",
+     "        __syncthreads();\n\n        // ---- write-out of the staged pieces", "\n        // ---- write-out of the staged pieces"),
+    ("quantizer: infinities keep the converter's NaN code in the row copy", "quantize.hip",
+     "f0 |= inf_byte<BF16, MODE>(elem_at<BF16>(x[i], j), (q0 >> (8 * j)) & 0xFFu) << (8 * j);",
+     "f0 |= ((q0 >> (8 * j)) & 0xFFu) << (8 * j);"),
+    ("quantizer: MXFP4 scale rule carries at 1.75 instead of 1.5", "mxfp4.hip",
+     "(abs_bits + 0x3FFFFFu) >> 23) - 2", "(abs_bits + 0x1FFFFFu) >> 23) - 2"),
+    ("quantizer: MXFP6 scale exponent one too large", "mxfp6.hip",
+     "(0x7FFFFFu - F::TOP_FRAC)) >> 23) - F::EMAX;", "(0x7FFFFFu - F::TOP_FRAC)) >> 23) - F::EMAX + 1;"),
+]
+
+
+def caught_quant(binary, work):
+    """Quantizes the tiny configuration (every special block) as FP32 and as BF16 along both axes, and hard cases of
+    the narrow formats, and compares every output byte with the oracle."""
+    from oracle import mxfp4, mxfp6
+    from paper_2506_08027_amd import synth_inputs as si
+    x = si.tiny_with_specials(256, seed=0)
+    cases = []
+    for bf16 in (False, True):
+        src = si.to_bf16_bits(x) if bf16 else x
+        cases.append((f"quantize {'bf16' if bf16 else 'f32'} 256 256 256 3", src,
+                      (oracle.quantize_rowwise(src), oracle.quantize_colwise(src))))
+    h4 = si.fp4_hard_cases(160, 96, seed=12)
+    cases.append(("quantfp4 f32 160 96 96 3", h4, (mxfp4.quantize_rowwise(h4), mxfp4.quantize_colwise(h4))))
+    h6 = si.fp6_hard_cases(160, 96, seed=12, top=7.5)
+    cases.append(("quantfp6 f32 160 96 96 3 0", h6, (mxfp6.quantize_rowwise(h6, "e2m3"), mxfp6.quantize_colwise(h6, "e2m3"))))
+    for head, src, ((q, s), (qT, sT)) in cases:
+        path = os.path.join(work, "src.bin")
+        np.ascontiguousarray(src).tofile(path)
+        prefix = os.path.join(work, "o")
+        case = os.path.join(work, "case.txt")
+        open(case, "w").write(f"{head} {path} {prefix}\n")
+        r = subprocess.run([binary, case], capture_output=True, text=True)
+        if r.returncode != 0:
+            return f"model stopped: {r.stderr.strip().splitlines()[-1][:100]}"
+        for suffix, want in ((".q_row", q), (".s_row", s), (".q_colT", qT), (".s_colT", sT)):
+            if not np.array_equal(np.fromfile(prefix + suffix, np.uint8), want.ravel()):
+                return f"wrong bytes in {suffix[1:]} of '{head}'"
+    return None
+
+
 def main():
     source = open(os.path.join(ROOT, "paper_2506_08027_amd", "csrc", "gemm.hip")).read()
     survivors = 0
@@ -135,6 +187,22 @@ def main():
             else:
                 text = source.replace(old, new, 1)
             how = caught(build(work, text), work, persistent)
+        finally:
+            shutil.rmtree(work, ignore_errors=True)
+        ok = (how is None) if old == "" else (how is not None)
+        survivors += not ok
+        print(("ok      " if ok else "PROBLEM ") + desc + (f" -> {how}" if how else ""), flush=True)
+    csrc = os.path.join(ROOT, "paper_2506_08027_amd", "csrc")
+    quant = [("(unmutated converters: must pass)", "gemm.hip", "", "")] + QUANT_MUTANTS
+    for desc, name, old, new in quant:
+        assert old == "" or old in open(os.path.join(csrc, name)).read(), desc
+    for desc, name, old, new in quant:
+        if only and not any(o in desc for o in only):
+            continue
+        text = open(os.path.join(csrc, name)).read()
+        work = tempfile.mkdtemp(prefix="kmut_")
+        try:
+            how = caught_quant(build(work, text.replace(old, new, 1) if old else text, name), work)
         finally:
             shutil.rmtree(work, ignore_errors=True)
         ok = (how is None) if old == "" else (how is not None)
