@@ -161,6 +161,28 @@ def test_fp6_full_size_samples_and_properties(fmt, element):
     assert bool((err <= amax * 2.0 ** -M).all())        # half a step of the top binade <= X * 2^(emax - M - 1) < amax * 2^-M
 
 
+@pytest.mark.skipif(not ON_HARDWARE, reason="full-size problem: hardware only")
+def test_fp6_gemm_full_size_end_to_end():
+    """The forward product of the benchmark's layer at full size and in its launch configuration (tiled scales): X in
+    E2M3 and W in E3M2 from the GPU's own quantizer, expanded on the GPU, multiplied by the MXFP8 kernel; sampled rows
+    against the oracle's MXFP6 product of the oracle's quantization of the same tensors."""
+    M, N, K = 8192, 14336, 4096
+    xb, wb = si.activations(M, K, seed=2), si.weights(N, K, seed=4)
+    lay = mx.SCALES_TILED
+    xq = mx.fp6_quantize(_dev(xb, True), mx.E2M3, "rowwise", lay)
+    wq = mx.fp6_quantize(_dev(wb, True), mx.E3M2, "rowwise", lay)
+    c = mx.fp6_gemm("fprop", xq["q_row"], xq["s_row"], mx.E2M3, wq["q_row"], wq["s_row"], mx.E3M2, torch.float32, lay)
+    torch.cuda.synchronize()
+    rows = np.array([0, 77, 4095, 4096, 8191])
+    a_q, a_s = mxfp6.quantize_rowwise(xb[rows], "e2m3")
+    b_q, b_s = mxfp6.quantize_rowwise(wb, "e3m2")
+    assert np.array_equal(xq["q_row"].cpu().numpy()[rows], a_q)
+    ref, absum = mxfp6.gemm(a_q, a_s, b_q, b_s, "e2m3", "e3m2")
+    got = c[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    assert (err <= 2.0 ** -10 * absum + 1e-300).all() and np.linalg.norm(err) / np.linalg.norm(ref) <= 1e-4
+
+
 def test_fp6_error_codes():
     x = torch.zeros((64, 64), device="cuda")
     with pytest.raises(mx.MXFP8Error):
