@@ -28,5 +28,20 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+EXAMPLE_SRC = os.path.join(_HERE, "examples", "linear_layer_step.cpp")
+EXAMPLE_BIN = os.path.join(_HERE, "examples", "linear_layer_step")
+
+
+def build_example() -> str:
+    """The stand-alone C++ program that drives one linear-layer step through the C ABI (needs the library built)."""
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", EXAMPLE_SRC, "-I", os.path.join(os.path.dirname(_HERE), "include"),
+           "-L", _HERE, "-lmxfp8", "-Wl,-rpath,$ORIGIN/..", "-o", EXAMPLE_BIN]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stderr)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_example())
