@@ -170,7 +170,14 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
 
     // a workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ... (one tile each when the grid has one per tile)
     for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const uint32_t tile_y = tile / tiles_x, tile_x = tile - tile_y * tiles_x;
+        // Order of the tiles over the workgroup ids: along the rows of the source, except that a wide tensor (more
+        // columns than rows) whose column copy is wanted is walked down its columns, so that the workgroups running
+        // side by side append to the same rows of the transposed copy. Measured on an MI355X over six shapes, both
+        // source types: 6 % (both copies) to 17 % (column copy only) less time where the rule switches, 5 .. 30 %
+        // more wherever it does not.
+        const bool walk_down = COL && cols > rows;
+        const uint32_t tiles_y = ntiles / tiles_x;
+        const uint32_t tile_y = walk_down ? tile % tiles_y : tile / tiles_x, tile_x = walk_down ? tile / tiles_y : tile % tiles_x;
         const int64_t wg_col0 = (int64_t)tile_x * kTile, wg_row0 = (int64_t)tile_y * kTile;
         const int64_t col0 = wg_col0 + lcol0, row0 = wg_row0 + lrow0;
         // rows % 32 == 0 and cols % 32 == 0: a wavefront's 32 rows are wholly inside or outside a

@@ -155,6 +155,17 @@ def test_quantize_resident_grid_walks_over_several_tiles(hostmodel, tmp_path, ti
     _quantize_and_compare(hostmodel, tmp_path, x, True, 3, tiled=tiled, groups=4, WAVESIM_CUS=1)
 
 
+@pytest.mark.parametrize("bf16,axis", [(False, 3), (True, 3), (False, 2), (True, 1)])
+def test_quantize_wide_tensors_walk_down_their_columns(hostmodel, tmp_path, bf16, axis):
+    """More columns than rows with the column copy wanted: the tiles are handed out down the columns (3 x 5 tiles, ragged
+    in both directions; BF16 with both copies on the resident grid of a one-unit device, 4 workgroups over 15 tiles).
+    The row-only case keeps the row order."""
+    x = (np.random.default_rng(6).standard_normal((288, 608)) * 3).astype(np.float32)
+    x[7, 300], x[200, 5] = np.inf, np.nan
+    env = dict(groups=4, WAVESIM_CUS=1) if bf16 and axis == 3 else {}
+    _quantize_and_compare(hostmodel, tmp_path, si.to_bf16_bits(x) if bf16 else x, bf16, axis, tiled=bf16, **env)
+
+
 @pytest.mark.parametrize("tiled", [False, True])
 def test_requantize_column_copy_from_row_copy(hostmodel, tmp_path, tiled):
     """Single-copy storage: ragged tiles, every special block of the tiny configuration in the row copy."""
