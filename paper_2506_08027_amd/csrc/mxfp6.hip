@@ -319,13 +319,45 @@ __global__ __launch_bounds__(256) void dequantize_fp6_kernel(const uint8_t *__re
     }
 }
 
-// E4M3 byte of a 6-bit code: the magnitude is zero or a normal E4M3 number with at most 3 mantissa bits, so its FP32
-// exponent re-biased and the top three fraction bits are the E4M3 fields
-template <class F> __device__ __forceinline__ uint32_t fp6_as_e4m3(uint32_t code)
+// Expansion to E4M3 bytes, four codes at a time in the bytes of a dword. Every 6-bit magnitude is zero or a normal
+// E4M3 number with at most 3 mantissa bits. A normal 6-bit number keeps its fields: exponent re-biased by 7 - BIAS,
+// mantissa left-aligned in three bits, i.e. (magnitude << (3 - M)) + ((7 - BIAS) << 3). Zero and the 2^M - 1 subnormal
+// magnitudes m * 2^(EMIN - M) come from an eight-byte table through one byte permute.
+template <class F> constexpr uint32_t fp6_subnormal_as_e4m3(int m)  // E4M3 byte of m * 2^(EMIN - M), 0 <= m < 2^M
 {
-    const uint32_t fb = __float_as_uint(fp6_magnitude<F>(code));
-    const uint32_t mag = fb == 0 ? 0u : ((((fb >> 23) - 127u + 7u) << 3) | ((fb >> 20) & 7u));
-    return mag | ((code & 32u) << 2);
+    if (m == 0)
+        return 0u;
+    int p = 0;
+    while ((2 << p) <= m)
+        ++p;  // m = 2^p * (1 + f)
+    return (uint32_t)(((p + F::EMIN - F::M + 7) << 3) | (((m - (1 << p)) << (3 - p)) & 7));
+}
+template <class F> constexpr uint32_t fp6_subnormal_table(int first)  // entries first .. first + 3, one per byte
+{
+    uint32_t t = 0;
+    for (int i = 0; i < 4; ++i)
+        if (first + i < (1 << F::M))
+            t |= fp6_subnormal_as_e4m3<F>(first + i) << (8 * i);
+    return t;
+}
+
+__device__ __forceinline__ uint32_t fp6_spread4(uint32_t x)  // four codes in bits 0 .. 23 -> one per byte
+{
+    return (x & 0x3Fu) | ((x << 2) & 0x3F00u) | ((x << 4) & 0x3F0000u) | ((x << 6) & 0x3F000000u);
+}
+
+template <class F> __device__ __forceinline__ uint32_t fp6x4_as_e4m3(uint32_t codes)  // one code per byte in, one E4M3 byte each out
+{
+    const uint32_t mag = codes & 0x1F1F1F1Fu;
+    uint32_t any = mag >> F::M;  // bit 0 of a byte <- the OR of its exponent bits (what spills in from the next byte lands above bit 0)
+#pragma unroll
+    for (int i = 1; i < F::E; ++i)
+        any |= mag >> (F::M + i);
+    const uint32_t one = any & 0x01010101u;
+    const uint32_t normal = (one << 8) - one;  // 0xFF in the bytes that hold a normal number
+    const uint32_t kept = (mag << (3 - F::M)) + 0x01010101u * (uint32_t)((7 - F::BIAS) << 3);
+    const uint32_t looked_up = __builtin_amdgcn_perm(fp6_subnormal_table<F>(4), fp6_subnormal_table<F>(0), mag & 0x07070707u);
+    return (normal & kept) | (~normal & looked_up) | ((codes & 0x20202020u) << 2);
 }
 
 template <class F>
@@ -334,10 +366,15 @@ __global__ __launch_bounds__(256) void expand_fp6_kernel(const uint8_t *__restri
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < blocks; t += (int64_t)gridDim.x * blockDim.x) {
         uint32_t w[6];
         fp6_load_block(q + t * kFp6BlockBytes, w);
-        uint32_t o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        uint32_t o[8];
 #pragma unroll
-        for (int i = 0; i < kBlock; ++i)
-            o[i / 4] |= fp6_as_e4m3<F>(fp6_code_at(w, i)) << (8 * (i % 4));
+        for (int h = 0; h < 2; ++h) {  // three dwords hold sixteen codes: 24 bits at offsets 0, 24, 48, 72
+            const uint32_t a = w[3 * h], b = w[3 * h + 1], c = w[3 * h + 2];
+            o[4 * h] = fp6x4_as_e4m3<F>(fp6_spread4(a));
+            o[4 * h + 1] = fp6x4_as_e4m3<F>(fp6_spread4((a >> 24) | (b << 8)));
+            o[4 * h + 2] = fp6x4_as_e4m3<F>(fp6_spread4((b >> 16) | (c << 16)));
+            o[4 * h + 3] = fp6x4_as_e4m3<F>(fp6_spread4(c >> 8));
+        }
         uint4 *d = reinterpret_cast<uint4 *>(q8 + t * kBlock);
         d[0] = make_uint4(o[0], o[1], o[2], o[3]);
         d[1] = make_uint4(o[4], o[5], o[6], o[7]);

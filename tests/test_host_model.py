@@ -342,6 +342,36 @@ def test_dequantize_tiled_scales(hostmodel, tmp_path):
     assert np.array_equal(got[~np.isnan(want)], want[~np.isnan(want)])
 
 
+@pytest.mark.parametrize("bf16,tiled,rows,cols,cus", [(False, True, 100, 96, 1), (True, False, 300, 160, 1),
+                                                       (True, True, 515, 64, 1), (False, False, 257, 224, 2)])
+def test_dequantize_resident_grid_unrolled_loop_and_tail(hostmodel, tmp_path, bf16, tiled, rows, cols, cus):
+    """On a device shrunk to 1 or 2 compute units the grid is smaller than the work: work-items take several rounds
+    with four loads in flight, then single items, and some take none; padded output rows stay untouched."""
+    rng = np.random.default_rng(rows + cols)
+    q = rng.integers(0, 256, (rows, cols), dtype=np.uint8)
+    s = rng.integers(90, 160, (rows, cols // 32), dtype=np.uint8)
+    s[rows // 2, 0] = 255                                  # a NaN block
+    ld = cols + 8
+    out = str(tmp_path / "d.bin")
+    _, calls = run_case(hostmodel, tmp_path, [
+        f"dequantize {rows} {cols} {'bf16' if bf16 else 'f32'} {ld} {put(tmp_path, 'q.bin', q)} "
+        f"{put(tmp_path, 's.bin', sl.tile(s) if tiled else s)} {out}" + (" tiled" if tiled else "")], WAVESIM_CUS=cus)
+    assert calls[0][0] == 0
+    dt = np.uint16 if bf16 else np.uint32
+    n = (rows - 1) * ld + cols
+    got = np.zeros(rows * ld, dt)
+    got[:n] = np.fromfile(out, dt)
+    got = got.reshape(rows, ld)
+    want = oracle.dequantize(q, s, "bf16" if bf16 else "f32")
+    want = np.asarray(want, np.uint16) if bf16 else np.asarray(want, np.float32).view(np.uint32)
+    nan = ((want & 0x7FFF) > 0x7F80) if bf16 else np.isnan(want.view(np.float32))
+    val = got[:, :cols]
+    assert nan[rows // 2, :32].all()
+    assert np.array_equal(((val & 0x7FFF) > 0x7F80) if bf16 else np.isnan(val.view(np.float32)), nan)
+    assert np.array_equal(val[~nan], want[~nan])
+    assert (got[:-1, cols:] == (0xA5A5 if bf16 else 0xA5A5A5A5)).all()
+
+
 # ---- persistent GEMM kernel (every problem made of full tiles; max_workgroups bounds its grid) ------------
 @pytest.mark.parametrize("mode,tiled", [(MODES[0], False), (MODES[3], True)], ids=["lazy-up-rowmajor", "eager-down-tiled"])
 def test_gemm_persistent_small_tiles(hostmodel, tmp_path, mode, tiled):
