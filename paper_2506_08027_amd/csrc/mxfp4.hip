@@ -228,6 +228,11 @@ template <bool BF16, bool TILED>
 __global__ __launch_bounds__(256) void dequantize_fp4_kernel(const uint8_t *__restrict__ q, const uint8_t *__restrict__ s,
                                                              int64_t rows, int64_t cols, uint8_t *__restrict__ dst, int64_t ld_bytes)
 {
+    // the 16 values of the format in 16 LDS banks: a lookup per element, no bank conflicts between different codes
+    __shared__ float value_of[16];
+    if (threadIdx.x < 16)
+        value_of[threadIdx.x] = fp4_value(threadIdx.x);
+    __syncthreads();
     const int64_t per_row = cols / 8, nb = cols / kBlock, total = rows * per_row;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
         const int64_t r = t / per_row, j = t - r * per_row;
@@ -236,7 +241,7 @@ __global__ __launch_bounds__(256) void dequantize_fp4_kernel(const uint8_t *__re
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            v[i] = sb == 0xFFu ? __uint_as_float(0x7FC00000u) : ldexpf(fp4_value((w >> (4 * i)) & 0xFu), (int)sb - 127);
+            v[i] = sb == 0xFFu ? __uint_as_float(0x7FC00000u) : ldexpf(value_of[(w >> (4 * i)) & 0xFu], (int)sb - 127);
         uint8_t *out = dst + r * ld_bytes + j * 8 * (BF16 ? 2 : 4);
         if constexpr (BF16) {
             uint32_t p[4];

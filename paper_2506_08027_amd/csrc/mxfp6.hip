@@ -286,35 +286,43 @@ template <class F, bool BF16, bool TILED>
 __global__ __launch_bounds__(256) void dequantize_fp6_kernel(const uint8_t *__restrict__ q, const uint8_t *__restrict__ s,
                                                              int64_t rows, int64_t cols, uint8_t *__restrict__ dst, int64_t ld_bytes)
 {
-    const int64_t nb = cols / kBlock, total = rows * nb;
+    // The 64 values of the format, one per LDS bank: lanes that look up different codes never collide, lanes with
+    // the same code share a broadcast. A lookup replaces about ten vector instructions per element.
+    __shared__ float value_of[64];
+    if (threadIdx.x < 64) {
+        const float mag = fp6_magnitude<F>(threadIdx.x);
+        value_of[threadIdx.x] = (threadIdx.x & 32u) ? -mag : mag;
+    }
+    __syncthreads();
+    // An item = a quarter of a block: eight codes (48 bits at byte 6k of the block) -> 16 bytes of BF16 or 32 bytes of
+    // FP32, so that neighbouring work-items read overlapping dwords of one line and store neighbouring pieces.
+    const int64_t nb = cols / kBlock, total = rows * nb * 4;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t r = t / nb, b = t - r * nb;
+        const int64_t blk = t >> 2;
+        const int k = (int)(t & 3);
+        const int64_t r = blk / nb, b = blk - r * nb;
         const uint32_t sb = s[fp6_scale_index<TILED>(r, b, nb)];
-        uint32_t w[6];
-        fp6_load_block(q + (r * nb + b) * kFp6BlockBytes, w);
-        float v[kBlock];
+        // two dwords from the dword boundary at or below byte 6k (bytes 0, 4, 12, 16 of the 24): all inside the block
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(q + blk * kFp6BlockBytes + ((6 * k) & ~3));
+        const uint64_t both = ((uint64_t)src[1] << 32) | src[0];
+        const uint64_t bits = both >> (16 * (k & 1));
+        float v[8];
 #pragma unroll
-        for (int i = 0; i < kBlock; ++i) {
-            const uint32_t c = fp6_code_at(w, i);
-            const float mag = ldexpf(fp6_magnitude<F>(c), (int)sb - 127);
-            v[i] = sb == 0xFFu ? __uint_as_float(0x7FC00000u) : ((c & 32u) ? -mag : mag);
-        }
-        uint8_t *out = dst + r * ld_bytes + b * kBlock * (BF16 ? 2 : 4);
+        for (int i = 0; i < 8; ++i)
+            v[i] = sb == 0xFFu ? __uint_as_float(0x7FC00000u)
+                               : ldexpf(value_of[(uint32_t)(bits >> (6 * i)) & 63u], (int)sb - 127);
+        uint8_t *out = dst + r * ld_bytes + (b * kBlock + 8 * k) * (BF16 ? 2 : 4);
         if constexpr (BF16) {
+            uint32_t p[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                uint32_t p[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v2bf h = {(__bf16)v[8 * k + 2 * e], (__bf16)v[8 * k + 2 * e + 1]};
-                    p[e] = __builtin_bit_cast(uint32_t, h);
-                }
-                *reinterpret_cast<uint4 *>(out + 16 * k) = make_uint4(p[0], p[1], p[2], p[3]);
+            for (int e = 0; e < 4; ++e) {
+                v2bf h = {(__bf16)v[2 * e], (__bf16)v[2 * e + 1]};
+                p[e] = __builtin_bit_cast(uint32_t, h);
             }
+            stream_store(reinterpret_cast<uint4 *>(out), make_uint4(p[0], p[1], p[2], p[3]));
         } else {
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                *reinterpret_cast<float4 *>(out + 16 * k) = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+            stream_store(reinterpret_cast<uint4 *>(out), make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+            stream_store(reinterpret_cast<uint4 *>(out + 16), make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
         }
     }
 }
@@ -390,7 +398,7 @@ static dim3 fp6_block_grid(int64_t blocks)
 hipError_t launch_dequantize_fp6(const uint8_t *q, const uint8_t *s, int64_t rows, int64_t cols, bool e3m2, void *dst, bool bf16,
                                  bool tiled, int64_t ld, hipStream_t stream)
 {
-    const dim3 grid = fp6_block_grid(rows * (cols / kBlock)), block(256);
+    const dim3 grid = fp6_block_grid(rows * (cols / kBlock) * 4), block(256);  // four work-items per block
     uint8_t *d = static_cast<uint8_t *>(dst);
     const int64_t ldb = ld * (bf16 ? 2 : 4);
 #define MXFP6_DEQ(F)                                                                                                     \
