@@ -203,6 +203,23 @@ def main():
         footprint = sets * (src.numel() * src.element_size() + 2 * r * c)
         return a.elapsed_time(b) / launches, footprint
 
+    def rotating_dequantize(sets, launches):
+        """Average time of one decode of X's row copy to BF16 over `launches` launches that walk through `sets`
+        distinct quantized tensors and as many outputs (one pair of events around the lot)."""
+        qs = [Xq["q_row"]] + [Xq["q_row"].clone() for _ in range(sets - 1)]
+        ss = [Xq["s_row"]] + [Xq["s_row"].clone() for _ in range(sets - 1)]
+        ds = [torch.empty((T, H), dtype=torch.bfloat16, device=dev) for _ in range(sets)]
+        for i in range(min(sets, 4)):
+            mx.mxfp8_dequantize_ex(qs[i], ss[i], ds[i], lay)
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(launches):
+            mx.mxfp8_dequantize_ex(qs[i % sets], ss[i % sets], ds[i % sets], lay)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / launches, sets * T * H * 3
+
     def layer_set():
         """The four linear layers of an 8B-class transformer block at 16384 tokens: every product timed on
         operands quantized on the GPU from tensors drawn on the GPU (torch generator, seed 16384)."""
@@ -339,12 +356,14 @@ def main():
         wq = mx.fp4_quantize(W, "rowwise", lay)
         ms = ms_avg(lambda: mx.mxfp8_fp4_gemm_ex(mx.FPROP, xq["q_row"], xq["s_row"], wq["q_row"], wq["s_row"], Y, lay))
         q_ms = ms_avg(lambda: mx.mxfp8_fp4_quantize_ex(X, mx.BOTH, xq["q_row"], xq["s_row"], xq["q_colT"], xq["s_colT"], lay))
+        d_ms = ms_avg(lambda: mx.mxfp8_fp4_dequantize_ex(xq["q_row"], xq["s_row"], Xd, lay))
         tf = gemm_flop / (ms * 1e-3) / 1e12
         sustained = sustained_mfma_tflops(4)
         return {"bound": "mfma", "achieved": tf, "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_FP4_PEAK_TFLOPS,
                 "peak_sustained": sustained, "frac_sustained": tf / sustained,
                 "kernel": f"gemm_persistent_kernel, MXFP4 operands (fprop {T}x{O}x{H}, BF16 out)", "avg_ms": ms, "launches": 20,
-                "quantize_X_both_ms": q_ms, "quantize_X_both_gbs": T * H * (2 + 2 * (0.5 + 1 / 32)) / (q_ms * 1e-3) / 1e9}
+                "quantize_X_both_ms": q_ms, "quantize_X_both_gbs": T * H * (2 + 2 * (0.5 + 1 / 32)) / (q_ms * 1e-3) / 1e9,
+                "dequantize_X_bf16_ms": d_ms, "dequantize_X_bf16_gbs": T * H * (0.5 + 1 / 32 + 2) / (d_ms * 1e-3) / 1e9}
 
     def mxfp6_path():
         """Table 1's 6-bit formats on the same layer: X and W converted to MXFP6-E2M3, expanded exactly to E4M3 bytes
@@ -355,11 +374,13 @@ def main():
         q_ms = ms_avg(lambda: mx.mxfp8_fp6_quantize_ex(X, mx.BOTH, mx.E2M3, xq["q_row"], xq["s_row"], xq["q_colT"], xq["s_colT"], lay))
         e_ms = ms_avg(lambda: (mx.mxfp8_fp6_expand_ex(xq["q_row"], mx.E2M3, x8), mx.mxfp8_fp6_expand_ex(wq["q_row"], mx.E2M3, w8)))
         g_ms = ms_avg(lambda: mx.mxfp8_gemm_ex(mx.FPROP, x8, xq["s_row"], w8, wq["s_row"], Y, lay))
+        d_ms = ms_avg(lambda: mx.mxfp8_fp6_dequantize_ex(xq["q_row"], xq["s_row"], mx.E2M3, Xd, lay))
         tf = gemm_flop / ((e_ms + g_ms) * 1e-3) / 1e12
         return {"bound": "mfma", "achieved": tf, "peak": MFMA_FP8_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_FP8_PEAK_TFLOPS,
                 "kernel": f"expand_fp6_kernel x2 + gemm_persistent_kernel (fprop {T}x{O}x{H}, BF16 out, E2M3 operands as E4M3)",
                 "expand_ms": e_ms, "gemm_ms": g_ms, "quantize_X_both_ms": q_ms,
-                "quantize_X_both_gbs": T * H * (2 + 2 * (0.75 + 1 / 32)) / (q_ms * 1e-3) / 1e9}
+                "quantize_X_both_gbs": T * H * (2 + 2 * (0.75 + 1 / 32)) / (q_ms * 1e-3) / 1e9,
+                "dequantize_X_bf16_ms": d_ms, "dequantize_X_bf16_gbs": T * H * (0.75 + 1 / 32 + 2) / (d_ms * 1e-3) / 1e9}
 
     def sustained_mfma_tflops(element_bits=8):
         """What the matrix pipes of this GPU sustain on the scaled matrix instruction alone (E4M3 or E2M1 operands in
@@ -408,6 +429,7 @@ def main():
         f_ms, f_fp = rotating_quantize(dY, 2, 100)
         extras["quant_bf16"] = (q_ms, q_fp, 160, rotating_copy_gbs(X, 8, 160))
         extras["quant_f32"] = (f_ms, f_fp, 100, rotating_copy_gbs(dY, 2, 100))
+        extras["dequant_bf16"] = rotating_dequantize(11, 165) + (165,)
         for key, fn in (("fused_output_quantization", fused_output_quantization), ("simulated_path", simulated_path),
                         ("grouped_moe", grouped_moe), ("single_copy", single_copy), ("mxfp4_path", mxfp4_path), ("mxfp6_path", mxfp6_path),
                         ("layer_set", layer_set)):
@@ -464,6 +486,14 @@ def main():
                         "kernel": f"quantize_kernel ({'BF16 X 8192x4096' if name == 'quant_bf16' else 'FP32 dY 8192x14336'}, both axes)",
                         "avg_ms": ms, "launches": launches, "rotating_footprint_mb": footprint / 1e6,
                         "plain_copy_gbs": copy_gbs[0], "frac_of_plain_copy": gbs / copy_gbs[0], "torch_copy_gbs": copy_gbs[1]}
+    if "dequant_bf16" in extras:
+        ms, footprint, launches = extras["dequant_bf16"]
+        nbytes = T * H * (1 + 1 / 32 + 2)
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out["roofline_dequantize"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                                      "traffic": traffic_from_profile("dequantize X"), "algorithmic_bytes": nbytes,
+                                      "kernel": f"dequantize_kernel (X {T}x{H} row copy -> BF16)", "avg_ms": ms, "launches": launches,
+                                      "rotating_footprint_mb": footprint / 1e6}
     if "roofline_quantize" in out:
         out["quantize_gbs_bf16_both"] = out["roofline_quantize"]["achieved"]
     for key in ("fused_output_quantization", "simulated_path", "grouped_moe", "single_copy", "mxfp4_path", "mxfp6_path"):
