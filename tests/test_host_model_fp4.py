@@ -52,6 +52,15 @@ def test_fp4_quantize_resident_grid_walks_over_several_tiles(hostmodel, tmp_path
     _check_quantize(hostmodel, tmp_path, x, bf16, 3, bf16, WAVESIM_CUS=1)
 
 
+@pytest.mark.parametrize("rows,cols", [(64, 96), (96, 288), (288, 96), (160, 544), (288, 320)],
+                         ids=["1x1", "1x3", "3x1", "2x5", "3x3"])
+def test_fp4_quantize_every_tile_of_small_and_odd_grids(hostmodel, tmp_path, rows, cols):
+    """Tile grids (rows x columns of 128 x 128 tiles) of one tile, one row, one column and odd counts, on two resident
+    workgroups: every tile must come out once, whatever order the workgroups take them in."""
+    x = si.fp4_hard_cases(rows, cols, seed=rows + cols)
+    _check_quantize(hostmodel, tmp_path, x, True, 3, True, WAVESIM_CUS=1)
+
+
 def test_fp4_quantize_tiny_with_specials(hostmodel, tmp_path):
     x = si.tiny_with_specials(256, seed=0)
     _check_quantize(hostmodel, tmp_path, x, False, 3, False)

@@ -41,6 +41,15 @@ def test_fp6_quantize_ties_boundaries_and_specials(hostmodel, tmp_path, fmt, ele
     _check_quantize(hostmodel, tmp_path, x, fmt, element, bf16, 3, tiled, WAVESIM_CUS=1)   # two workgroups, three tiles each
 
 
+@pytest.mark.parametrize("rows,cols", [(64, 96), (96, 288), (288, 96), (160, 544), (288, 320)],
+                         ids=["1x1", "1x3", "3x1", "2x5", "3x3"])
+def test_fp6_quantize_every_tile_of_small_and_odd_grids(hostmodel, tmp_path, rows, cols):
+    """Tile grids of one tile, one row, one column and odd counts on two resident workgroups: every tile comes out once."""
+    fmt, element = FMTS[(rows + cols) // 32 % 2]
+    x = si.fp6_hard_cases(rows, cols, seed=rows + cols, top=mxfp6.dest_max(fmt))
+    _check_quantize(hostmodel, tmp_path, x, fmt, element, True, 3, True, WAVESIM_CUS=1)
+
+
 @pytest.mark.parametrize("fmt,element", FMTS)
 @pytest.mark.parametrize("axis", [1, 2])
 def test_fp6_quantize_single_axis_padded_source(hostmodel, tmp_path, fmt, element, axis):
